@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of libgemm on one MI355X.
+
+    python bench.py [--gpus 1] [--steps 50] [--warmup 10] [--configs C3,C5,...] [--no-cpu-baseline]
+
+A "step" is one gemm_run call on the headline workload (C3: bf16 8192^3, row-major A and B,
+fp32 output) with operands resident in HBM.  The protocol follows the paper's evaluation
+(Section 5.1): warm-up launches, then timed launches, mean latency reported.  Prints ONE JSON
+line; `value` is TFLOP/s on C3, `roofline` prices the dominant kernel of C3 against the dense
+bf16 MFMA peak, `cpu_baseline` times the CPU oracle on a bounded sample of the same workload,
+and `other_configs` carries the remaining configurations (C5 is priced against HBM bandwidth).
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+HBM_PEAK_GBPS = 8000.0
+
+
+def kernel_source_hash() -> str:
+    """Hash of the kernel sources: counter-derived traffic figures are only quoted while the
+    kernels they were measured on are unchanged."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2512_16465_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        h.update(f.encode())
+        h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(name: str):
+    """HBM bytes per launch from the rocprofv3 counter runs recorded in profiles/traffic.json,
+    or None when absent or taken on different kernel sources."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path)).get(name)
+    if not rec or rec.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return rec.get("hbm_bytes_per_launch")
+
+
+def classify(cfg) -> str:
+    """The paper's roofline rule (Section 4.3): left of the ridge of the slowest unit (fp32
+    vector ALUs) is memory-bound, right of the ridge of the fastest unit (matrix cores) is
+    compute-bound, in between is the middle zone."""
+    ai = cfg.flops() / cfg.algorithmic_bytes()
+    low = FP32_VECTOR_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
+    high = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
+    return "memory-bound" if ai < low else ("compute-bound" if ai > high else "middle-zone")
+
+
+class Resident:
+    """Operands of one configuration in HBM; `copies` independent input sets are rotated so that
+    a memory-bound call cannot be served from the 256 MB last-level cache."""
+
+    def __init__(self, cfg, seed, copies=1):
+        import torch
+        import workloads as wl
+        self.cfg = cfg
+        dev = torch.device("cuda:0")
+        self.sets = []
+        self.host_inputs = None
+        for c in range(copies):
+            inp = wl.make_inputs(cfg, seed + c)
+            if c == 0:
+                self.host_inputs = inp
+            A = wl.bits_to_torch(inp["A"], cfg.dtype, dev)
+            B = wl.bits_to_torch(inp["B"], cfg.dtype, dev)
+            tdt = {wl.F32: torch.float32, wl.F16: torch.float16, wl.BF16: torch.bfloat16}[cfg.out_dtype]
+            if inp["C"] is not None:
+                C = wl.bits_to_torch(inp["C"], cfg.out_dtype, dev)
+            else:
+                C = torch.empty(cfg.M * cfg.ld_c(), dtype=tdt, device=dev)
+            bias = wl.bits_to_torch(inp["bias"], cfg.bias_dtype, dev) if inp["bias"] is not None else None
+            self.sets.append((A, B, C, bias))
+
+    def launch(self, lg, handle, i, stream):
+        cfg = self.cfg
+        A, B, C, bias = self.sets[i % len(self.sets)]
+        epi = lg.make_epilogue(cfg.out_dtype, bias.data_ptr() if bias is not None else 0, cfg.bias_dtype, cfg.act)
+        lg.gemm_run(handle, cfg.M, cfg.N, cfg.K, cfg.transA, cfg.transB, cfg.dtype, cfg.alpha,
+                    A.data_ptr(), cfg.ld_a(), B.data_ptr(), cfg.ld_b(), cfg.beta, C.data_ptr(), cfg.ld_c(), epi, stream)
+
+
+def time_config(lg, handle, res: Resident, steps: int, warmup: int):
+    """Returns (wall ms per step over the whole timed region, mean/min/std of per-launch
+    durations from HIP events recorded on the launch stream)."""
+    import torch
+    stream = torch.cuda.current_stream().cuda_stream
+    for i in range(warmup):
+        res.launch(lg, handle, i, stream)
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record()
+        res.launch(lg, handle, i, stream)
+        stops[i].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per = [starts[i].elapsed_time(stops[i]) for i in range(steps)]
+    mean = sum(per) / len(per)
+    var = sum((x - mean) ** 2 for x in per) / len(per)
+    return (t1 - t0) * 1e3 / steps, mean, min(per), var ** 0.5
+
+
+def quick_verify(res: Resident, lg, handle):
+    """A sampled check of the timed call against the oracle (256 elements), outside the timed region."""
+    import numpy as np
+    import torch
+    import oracle
+    import workloads as wl
+    cfg = res.cfg
+    inp = res.host_inputs
+    A, B, C, bias = res.sets[0]
+    if inp["C"] is not None:
+        C.copy_(wl.bits_to_torch(inp["C"], cfg.out_dtype, C.device))
+    res.launch(lg, handle, 0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    rows, cols = wl.sample_indices(cfg.M, cfg.N, 1, grid=16)
+    flat = (torch.from_numpy(rows).to(C.device) * cfg.ld_c() + torch.from_numpy(cols).to(C.device))
+    got = oracle.decode(cfg.out_dtype, wl.torch_to_bits(C[flat]))
+    prob = oracle.Problem(cfg.M, cfg.N, cfg.K, cfg.transA, cfg.transB, cfg.dtype, inp["A"], cfg.ld_a(), inp["B"], cfg.ld_b(),
+                          alpha=cfg.alpha, beta=cfg.beta, C=inp["C"], ldc=cfg.ld_c(), c_dtype=cfg.out_dtype,
+                          bias=inp["bias"], bias_dtype=cfg.bias_dtype, act=cfg.act)
+    ref, _, mag = oracle.gemm_at(prob, rows, cols)
+    tol = (1e-5 * mag + 1e-6) if cfg.dtype == wl.F32 else (4e-3 * mag + 1e-5)
+    return bool(np.all(np.abs(got - ref) <= tol))
+
+
+def cpu_baseline(res: Resident, target_seconds: float = 12.0):
+    """The oracle as it stands, on the host cores, over whole rows of C of the same workload."""
+    import oracle
+    cfg = res.cfg
+    inp = res.host_inputs
+    prob = oracle.Problem(cfg.M, cfg.N, cfg.K, cfg.transA, cfg.transB, cfg.dtype, inp["A"], cfg.ld_a(), inp["B"], cfg.ld_b(),
+                          alpha=cfg.alpha, beta=cfg.beta, C=inp["C"], ldc=cfg.ld_c(), c_dtype=cfg.out_dtype,
+                          bias=inp["bias"], bias_dtype=cfg.bias_dtype, act=cfg.act)
+    cores = oracle.num_threads()
+    t0 = time.perf_counter()
+    oracle.gemm_rows(prob, 0, 1)                      # calibration: one row
+    t_row = time.perf_counter() - t0
+    nrows = int(max(1, min(cfg.M, target_seconds / max(t_row, 1e-6))))
+    t0 = time.perf_counter()
+    oracle.gemm_rows(prob, 0, nrows)
+    dt = time.perf_counter() - t0
+    flops = 2.0 * nrows * cfg.N * cfg.K
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"rows 0..{nrows - 1} of C ({nrows} x {cfg.N} outputs, K={cfg.K}) in {dt:.1f} s; "
+                      f"projected full matrix {dt * cfg.M / nrows:.0f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--configs", default="C3,C5,C2,C4,C1", help="first one is the headline workload")
+    ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-verify", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this library is single-GPU by design; run with --gpus 1 "
+              "(sharding over several GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_16465_amd as lg
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    lg.load_library()          # fails loudly when the HIP library is not built
+    seed = wl.DEFAULT_SEED if args.seed is None else args.seed
+    handle = lg.gemm_create()
+    names = [n.strip() for n in args.configs.split(",") if n.strip()]
+    results = {}
+    headline = None
+    for idx, name in enumerate(names):
+        cfg = wl.CONFIGS[name]
+        bound = "hbm" if classify(cfg) != "compute-bound" else "mfma"
+        res = Resident(cfg, seed, copies=2 if bound == "hbm" and cfg.algorithmic_bytes() > (64 << 20) else 1)
+        ok = None if args.no_verify else quick_verify(res, lg, handle)
+        wall_ms, ev_mean, ev_min, ev_std = time_config(lg, handle, res, args.steps, args.warmup)
+        kernel, variant, split = lg.gemm_get_last_plan(handle)
+        kname = lg.gemm_variant_name(kernel, variant)
+        tflops = cfg.flops() / (wall_ms * 1e-3) / 1e12
+        gbps = cfg.algorithmic_bytes() / (wall_ms * 1e-3) / 1e9
+        if name == "C1":
+            roof = None          # launch-latency bound: no roofline is meaningful
+        elif bound == "mfma":
+            ach = cfg.flops() / (ev_mean * 1e-3) / 1e12
+            roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(name), "kernel": kname}
+        else:
+            ach = cfg.algorithmic_bytes() / (ev_mean * 1e-3) / 1e9
+            roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": ach / HBM_PEAK_GBPS, "traffic": measured_traffic(name), "kernel": kname}
+        results[name] = {
+            "workload": cfg.note, "class": classify(cfg), "kernel": kname, "split_k": split,
+            "ms_per_step": wall_ms, "launch_ms_mean": ev_mean, "launch_ms_min": ev_min, "launch_ms_std": ev_std,
+            "tflops": tflops, "algorithmic_gbps": gbps, "verified_sample": ok, "roofline": roof,
+        }
+        if idx == 0:
+            headline = (name, cfg, res, wall_ms, tflops, roof)
+        else:
+            del res
+            torch.cuda.empty_cache()
+
+    name, cfg, res, wall_ms, tflops, roof = headline
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(res)
+    torch.cuda.synchronize()
+    lg.gemm_destroy(handle)
+    line = {
+        "metric": "gemm_tflops_bf16_8192cubed" if name == "C3" else f"gemm_tflops_{name}",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == wl.BF16 else ("f16" if cfg.dtype == wl.F16 else "f32"),
+        "data": "synthetic",
+        "config": {"workload": f"{name}: {cfg.note}", "M": cfg.M, "N": cfg.N, "K": cfg.K,
+                   "accumulate": "f32", "out_dtype": {0: "f32", 1: "f16", 2: "bf16"}[cfg.out_dtype], "seed": seed},
+        "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "hbm_gbps_at_m32": results["C5"]["algorithmic_gbps"] if "C5" in results else None,
+        "other_configs": {k: v for k, v in results.items() if k != name},
+        "headline_detail": results[name],
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,146 @@
+/*
+ * libgemm -- dense GEMM with a fused epilogue for AMD Instinct MI355X (gfx950).
+ *
+ *     C = act( alpha * op(A) * op(B) + beta * C + bias )
+ *
+ * This is the operation whose hand-optimised kernels the paper studies in its GEMM case
+ * study (Section 5.4, Table 1: matrix-core use, tiling, vectorised access, padding or
+ * swizzled shared-memory layouts, thread-block swizzle, double buffering).  The paper
+ * never writes the formula; the plain BLAS statement above is what every call computes.
+ *
+ * Storage is ROW-MAJOR with explicit leading dimensions (in elements):
+ *   transA = GEMM_OP_N : A is M x K, op(A)(i,k) = A[i*lda + k], lda >= K
+ *   transA = GEMM_OP_T : A is stored K x M, op(A)(i,k) = A[k*lda + i], lda >= M
+ *   transB = GEMM_OP_N : B is K x N, op(B)(k,j) = B[k*ldb + j], ldb >= N
+ *   transB = GEMM_OP_T : B is stored N x K ("column-major B"), op(B)(k,j) = B[j*ldb + k], ldb >= K
+ *   C is M x N, C(i,j) = C[i*ldc + j], ldc >= N.
+ * Products are accumulated in fp32 (bf16 x bf16 and fp16 x fp16 products are exact), the
+ * epilogue runs in fp32, and the result is rounded once, to nearest-even, into the type of C.
+ *
+ * All matrix and bias pointers are DEVICE pointers owned by the caller; the library never
+ * allocates, frees or retains them.  gemm_run is asynchronous: it enqueues work on the given
+ * HIP stream and returns without synchronising.  Nothing here throws, aborts or prints.
+ */
+#ifndef LIBGEMM_GEMM_H
+#define LIBGEMM_GEMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gemm_handle_s* gemm_handle_t;
+
+typedef enum {
+    GEMM_OK = 0,
+    GEMM_ERR_INVALID_ARG = 1,   /* null handle/pointer, negative size, small ld, unknown enum value */
+    GEMM_ERR_UNSUPPORTED = 2,   /* a valid request outside what is built (see gemm_run) */
+    GEMM_ERR_ALLOC = 3,         /* workspace allocation failed */
+    GEMM_ERR_HIP = 4            /* a HIP call or kernel launch failed */
+} gemm_status_t;
+
+typedef enum { GEMM_OP_N = 0, GEMM_OP_T = 1 } gemm_op_t;
+
+/* Element types: IEEE binary32, IEEE binary16, bfloat16 (upper half of a binary32). */
+typedef enum { GEMM_F32 = 0, GEMM_F16 = 1, GEMM_BF16 = 2 } gemm_dtype_t;
+
+/* GEMM_ACT_GELU_ERF is the exact GELU, x * Phi(x) = x/2 * (1 + erf(x / sqrt 2)). */
+typedef enum { GEMM_ACT_NONE = 0, GEMM_ACT_GELU_ERF = 1 } gemm_act_t;
+
+/*
+ * Fused epilogue.  A NULL pointer passed to gemm_run means
+ * { out_dtype = dtype of A and B, bias = NULL, act = GEMM_ACT_NONE }.
+ */
+typedef struct {
+    gemm_dtype_t out_dtype;   /* type of C, both when read (beta != 0) and when written:
+                                 the type of A and B, or GEMM_F32 */
+    const void*  bias;        /* device pointer to N elements added to every row, or NULL */
+    gemm_dtype_t bias_dtype;  /* type of bias; ignored when bias is NULL */
+    gemm_act_t   act;         /* applied last, to alpha*op(A)*op(B) + beta*C + bias */
+} gemm_epilogue_t;
+
+/*
+ * Creates a handle on the current HIP device.  The handle owns only a split-K workspace
+ * (allocated on first need, grown on demand, freed by gemm_destroy).
+ * Errors: GEMM_ERR_INVALID_ARG if out is NULL; GEMM_ERR_HIP if no device is usable.
+ */
+gemm_status_t gemm_create(gemm_handle_t* out);
+
+/*
+ * Enqueues C = act(alpha*op(A)*op(B) + beta*C + bias) on `stream` (a hipStream_t passed as
+ * void*; NULL is the default stream).
+ *
+ *   M, N, K         sizes, >= 0.  M == 0 or N == 0: nothing is launched.  K == 0: the product is
+ *                   an empty sum, C = act(beta*C + bias).
+ *   dtype           type of A and B.
+ *   alpha, beta     host scalars.  beta == 0 makes C write-only: its old contents, NaN and Inf
+ *                   included, do not reach the result.
+ *   A, B            device pointers, read only; may be NULL only if the operand is empty.
+ *   C               device pointer, M x N, written (and read iff beta != 0).  Must not overlap A,
+ *                   B or bias.
+ *   epilogue        see gemm_epilogue_t; may be NULL.
+ *
+ * Any shape, leading dimension and alignment is accepted for all three types.  The fast
+ * matrix-core kernels need 16-byte aligned A and B, leading dimensions that are multiples of
+ * 8 elements and a contiguous dimension that is a multiple of 8 (bf16/fp16); other calls run
+ * a slower general kernel with the same result contract.
+ *
+ * Errors (C is untouched in every error case detected before launch):
+ *   GEMM_ERR_INVALID_ARG  null handle; negative size; ld smaller than the stored row; a null
+ *                         matrix pointer for a non-empty operand; an enum value out of range.
+ *   GEMM_ERR_UNSUPPORTED  out_dtype neither the input type nor GEMM_F32.
+ *   GEMM_ERR_ALLOC        the split-K workspace could not be allocated.
+ *   GEMM_ERR_HIP          a launch failed (the HIP error is consumed).
+ *
+ * A handle must not be used from two streams at once (they would share the workspace);
+ * distinct handles may run concurrently.  The same call on the same data always yields the
+ * same bits (no floating-point atomics; fixed split-K summation order).
+ */
+gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_t K,
+                       gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,
+                       float alpha, const void* A, int64_t lda,
+                       const void* B, int64_t ldb,
+                       float beta, void* C, int64_t ldc,
+                       const gemm_epilogue_t* epilogue, void* stream);
+
+/* Frees the workspace and the handle.  The caller must have synchronised the streams that used
+ * it.  NULL is accepted.  Errors: GEMM_ERR_HIP if freeing device memory failed. */
+gemm_status_t gemm_destroy(gemm_handle_t h);
+
+/* A static, never-NULL description of a status code. */
+const char* gemm_status_string(gemm_status_t s);
+
+/* ---- kernel choice: inspection and override (the paper's "tiling" strategy, Table 1, is a
+ * tunable here; the bench harness sweeps it and records the evidence) ---- */
+
+typedef enum {
+    GEMM_KERNEL_AUTO = 0,      /* let the library choose (default) */
+    GEMM_KERNEL_GENERAL = 1,   /* one thread per output element, any shape/alignment */
+    GEMM_KERNEL_MFMA_TILE = 2, /* LDS-staged macro-tile kernel on MFMA */
+    GEMM_KERNEL_SKINNY = 3     /* small-M streaming kernel with split-K */
+} gemm_kernel_t;
+
+typedef struct {
+    gemm_kernel_t kernel;   /* which family */
+    int32_t variant;        /* tile variant index within the family; -1 = automatic */
+    int32_t split_k;        /* number of K slices; 0 = automatic, 1 = none */
+} gemm_plan_t;
+
+/* Forces the plan used by later gemm_run calls on this handle; a NULL plan restores automatic
+ * choice.  A forced plan that cannot run a given call (alignment, shape) makes that call return
+ * GEMM_ERR_UNSUPPORTED.  Errors: GEMM_ERR_INVALID_ARG for a null handle or out-of-range fields. */
+gemm_status_t gemm_set_plan(gemm_handle_t h, const gemm_plan_t* plan);
+
+/* Reports the plan the most recent successful gemm_run on this handle used.
+ * Errors: GEMM_ERR_INVALID_ARG for null arguments. */
+gemm_status_t gemm_get_last_plan(gemm_handle_t h, gemm_plan_t* out);
+
+/* Name of a tile variant of a family (static storage), or NULL if the index is out of range.
+ * Lets a harness enumerate variants: loop until NULL. */
+const char* gemm_variant_name(gemm_kernel_t kernel, int32_t variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIBGEMM_GEMM_H */

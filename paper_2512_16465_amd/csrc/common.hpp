@@ -1,0 +1,98 @@
+// Internal declarations shared by the kernels of libgemm (device code for gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gemm {
+
+// numeric codes of the public enums (include/gemm.h)
+enum : int { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
+enum : int { ACT_NONE = 0, ACT_GELU_ERF = 1 };
+
+struct Args {
+    int64_t M, N, K;
+    int32_t transA, transB;
+    int32_t dtype, out_dtype, bias_dtype, act;
+    float alpha, beta;
+    const void* A; int64_t lda;
+    const void* B; int64_t ldb;
+    void* C; int64_t ldc;
+    const void* bias;
+};
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+// ---- scalar conversions (round to nearest even on the way down) ----
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);                                               // ties to even
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t b) {
+    _Float16 h;
+    __builtin_memcpy(&h, &b, 2);
+    return (float)h;
+}
+
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float x) {
+    _Float16 h = (_Float16)x;     // v_cvt_f16_f32, round to nearest even
+    uint16_t b;
+    __builtin_memcpy(&b, &h, 2);
+    return b;
+}
+
+// element idx of an array whose type is known only at run time (wave-uniform branch)
+__device__ __forceinline__ float load_elem(const void* p, int dtype, int64_t idx) {
+    if (dtype == DT_F32) return ((const float*)p)[idx];
+    const uint16_t b = ((const uint16_t*)p)[idx];
+    return dtype == DT_BF16 ? bf16_bits_to_f32(b) : f16_bits_to_f32(b);
+}
+
+__device__ __forceinline__ void store_elem(void* p, int dtype, int64_t idx, float v) {
+    if (dtype == DT_F32) ((float*)p)[idx] = v;
+    else if (dtype == DT_BF16) ((uint16_t*)p)[idx] = f32_to_bf16_bits(v);
+    else ((uint16_t*)p)[idx] = f32_to_f16_bits(v);
+}
+
+// exact GELU, x * Phi(x)
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+
+__device__ __forceinline__ float apply_act(float x, int act) { return act == ACT_GELU_ERF ? gelu_erf(x) : x; }
+
+// Everything after the contraction, for one element: act(alpha*acc + beta*C_in + bias_j).
+// c_in and bias_j are passed already widened; beta == 0 callers pass c_in = 0 without loading it.
+__device__ __forceinline__ float epilogue_value(float acc, float alpha, float beta, float c_in, float bias_j, int act) {
+    float v = alpha * acc;
+    if (beta != 0.0f) v = fmaf(beta, c_in, v);
+    v += bias_j;
+    return apply_act(v, act);
+}
+
+// ---- host-side launchers, one per kernel family; each returns a hipError_t ----
+
+struct TileVariantInfo { const char* name; int BM, BN, BK, threads; };
+
+int tile_num_variants();
+const TileVariantInfo* tile_variant_info(int variant);
+// true if the call satisfies the alignment/shape preconditions of the macro-tile kernels
+bool tile_supports(const Args& a);
+hipError_t launch_tile(const Args& a, int variant, int group_m, hipStream_t stream);
+
+bool skinny_supports(const Args& a);
+// bytes of fp32 workspace the skinny kernel needs for this split factor (0 when split_k == 1)
+size_t skinny_workspace_bytes(const Args& a, int split_k);
+int skinny_default_split(const Args& a, int num_cus);
+hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream_t stream);
+
+hipError_t launch_general(const Args& a, hipStream_t stream);
+
+}  // namespace gemm

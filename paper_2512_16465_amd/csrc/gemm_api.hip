@@ -1,0 +1,209 @@
+// C ABI of libgemm: argument validation, kernel choice, workspace ownership.
+#include <new>
+
+#include "../../include/gemm.h"
+#include "common.hpp"
+
+#define GEMM_EXPORT extern "C" __attribute__((visibility("default")))
+
+struct gemm_handle_s {
+    int device;
+    int num_cus;
+    float* workspace;
+    size_t workspace_bytes;
+    bool forced;
+    gemm_plan_t plan;        // forced plan (valid when forced)
+    gemm_plan_t last;        // plan of the last successful run
+};
+
+namespace {
+
+using gemm::Args;
+
+bool valid_dtype(int d) { return d == GEMM_F32 || d == GEMM_F16 || d == GEMM_BF16; }
+
+// Picks a tile variant for the macro-tile family: the large tile when it still yields enough
+// workgroups to occupy the compute units, the small tile otherwise.
+int choose_tile_variant(const Args& a, int num_cus) {
+    const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);
+    if (big * 2 >= num_cus) return 0;
+    return 3;
+}
+
+gemm_status_t ensure_workspace(gemm_handle_s* h, size_t bytes, hipStream_t stream) {
+    if (bytes <= h->workspace_bytes) return GEMM_OK;
+    if (h->workspace) {
+        // earlier launches on the caller's stream may still read the old buffer
+        if (hipStreamSynchronize(stream) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_HIP; }
+        if (hipFree(h->workspace) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_HIP; }
+        h->workspace = nullptr;
+        h->workspace_bytes = 0;
+    }
+    size_t want = bytes < ((size_t)32 << 20) ? ((size_t)32 << 20) : bytes;
+    void* p = nullptr;
+    if (hipMalloc(&p, want) != hipSuccess) {
+        (void)hipGetLastError();
+        return GEMM_ERR_ALLOC;
+    }
+    h->workspace = (float*)p;
+    h->workspace_bytes = want;
+    return GEMM_OK;
+}
+
+}  // namespace
+
+GEMM_EXPORT gemm_status_t gemm_create(gemm_handle_t* out) {
+    if (!out) return GEMM_ERR_INVALID_ARG;
+    *out = nullptr;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_HIP; }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return GEMM_ERR_HIP;
+    }
+    gemm_handle_s* h = new (std::nothrow) gemm_handle_s();
+    if (!h) return GEMM_ERR_ALLOC;
+    h->device = dev;
+    h->num_cus = cus > 0 ? cus : 256;
+    h->workspace = nullptr;
+    h->workspace_bytes = 0;
+    h->forced = false;
+    h->plan = gemm_plan_t{GEMM_KERNEL_AUTO, -1, 0};
+    h->last = gemm_plan_t{GEMM_KERNEL_AUTO, -1, 0};
+    *out = h;
+    return GEMM_OK;
+}
+
+GEMM_EXPORT gemm_status_t gemm_destroy(gemm_handle_t h) {
+    if (!h) return GEMM_OK;
+    gemm_status_t st = GEMM_OK;
+    if (h->workspace && hipFree(h->workspace) != hipSuccess) {
+        (void)hipGetLastError();
+        st = GEMM_ERR_HIP;
+    }
+    delete h;
+    return st;
+}
+
+GEMM_EXPORT const char* gemm_status_string(gemm_status_t s) {
+    switch (s) {
+        case GEMM_OK: return "success";
+        case GEMM_ERR_INVALID_ARG: return "invalid argument";
+        case GEMM_ERR_UNSUPPORTED: return "unsupported combination";
+        case GEMM_ERR_ALLOC: return "workspace allocation failed";
+        case GEMM_ERR_HIP: return "HIP call or kernel launch failed";
+    }
+    return "unknown status";
+}
+
+GEMM_EXPORT gemm_status_t gemm_set_plan(gemm_handle_t h, const gemm_plan_t* plan) {
+    if (!h) return GEMM_ERR_INVALID_ARG;
+    if (!plan) { h->forced = false; return GEMM_OK; }
+    if (plan->kernel < GEMM_KERNEL_AUTO || plan->kernel > GEMM_KERNEL_SKINNY) return GEMM_ERR_INVALID_ARG;
+    if (plan->split_k < 0 || plan->split_k > 64) return GEMM_ERR_INVALID_ARG;
+    if (plan->variant < -1) return GEMM_ERR_INVALID_ARG;
+    if (plan->kernel == GEMM_KERNEL_MFMA_TILE && plan->variant >= gemm::tile_num_variants()) return GEMM_ERR_INVALID_ARG;
+    h->forced = plan->kernel != GEMM_KERNEL_AUTO;
+    h->plan = *plan;
+    return GEMM_OK;
+}
+
+GEMM_EXPORT gemm_status_t gemm_get_last_plan(gemm_handle_t h, gemm_plan_t* out) {
+    if (!h || !out) return GEMM_ERR_INVALID_ARG;
+    *out = h->last;
+    return GEMM_OK;
+}
+
+GEMM_EXPORT const char* gemm_variant_name(gemm_kernel_t kernel, int32_t variant) {
+    if (kernel == GEMM_KERNEL_MFMA_TILE) {
+        const gemm::TileVariantInfo* info = gemm::tile_variant_info(variant);
+        return info ? info->name : nullptr;
+    }
+    if (kernel == GEMM_KERNEL_GENERAL) return variant == 0 ? "general_16x16" : nullptr;
+    if (kernel == GEMM_KERNEL_SKINNY) return variant == 0 ? "skinny_nn_32x256_w8" : nullptr;
+    return nullptr;
+}
+
+GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_t K,
+                                   gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,
+                                   float alpha, const void* A, int64_t lda,
+                                   const void* B, int64_t ldb,
+                                   float beta, void* C, int64_t ldc,
+                                   const gemm_epilogue_t* epilogue, void* stream_) {
+    // ---- validation: nothing is launched and C is untouched on any error below ----
+    if (!h) return GEMM_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0) return GEMM_ERR_INVALID_ARG;
+    if ((transA != GEMM_OP_N && transA != GEMM_OP_T) || (transB != GEMM_OP_N && transB != GEMM_OP_T)) return GEMM_ERR_INVALID_ARG;
+    if (!valid_dtype(dtype)) return GEMM_ERR_INVALID_ARG;
+    gemm_epilogue_t epi;
+    if (epilogue) epi = *epilogue;
+    else epi = gemm_epilogue_t{dtype, nullptr, dtype, GEMM_ACT_NONE};
+    if (!valid_dtype(epi.out_dtype)) return GEMM_ERR_INVALID_ARG;
+    if (epi.bias && !valid_dtype(epi.bias_dtype)) return GEMM_ERR_INVALID_ARG;
+    if (epi.act != GEMM_ACT_NONE && epi.act != GEMM_ACT_GELU_ERF) return GEMM_ERR_INVALID_ARG;
+    const int64_t a_cols = transA == GEMM_OP_N ? K : M, b_cols = transB == GEMM_OP_N ? N : K;
+    if (lda < (a_cols > 1 ? a_cols : 1) || ldb < (b_cols > 1 ? b_cols : 1) || ldc < (N > 1 ? N : 1)) return GEMM_ERR_INVALID_ARG;
+    if (M > 0 && N > 0 && !C) return GEMM_ERR_INVALID_ARG;
+    if (M > 0 && K > 0 && !A) return GEMM_ERR_INVALID_ARG;
+    if (N > 0 && K > 0 && !B) return GEMM_ERR_INVALID_ARG;
+    if (epi.out_dtype != dtype && epi.out_dtype != GEMM_F32) return GEMM_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return GEMM_OK;
+
+    hipStream_t stream = (hipStream_t)stream_;
+    Args a;
+    a.M = M; a.N = N; a.K = K;
+    a.transA = transA == GEMM_OP_T; a.transB = transB == GEMM_OP_T;
+    a.dtype = (int)dtype; a.out_dtype = (int)epi.out_dtype; a.bias_dtype = (int)epi.bias_dtype; a.act = (int)epi.act;
+    a.alpha = alpha; a.beta = beta;
+    a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.C = C; a.ldc = ldc;
+    a.bias = epi.bias;
+
+    // ---- plan ----
+    gemm_plan_t plan{GEMM_KERNEL_GENERAL, 0, 1};
+    const bool product = (K > 0 && alpha != 0.0f);
+    if (!product) {
+        plan = gemm_plan_t{GEMM_KERNEL_GENERAL, 0, 1};      // only the epilogue is left
+    } else if (h->forced) {
+        plan = h->plan;
+        if (plan.kernel == GEMM_KERNEL_MFMA_TILE) {
+            if (!gemm::tile_supports(a)) return GEMM_ERR_UNSUPPORTED;
+            if (plan.variant < 0) plan.variant = choose_tile_variant(a, h->num_cus);
+            plan.split_k = 1;
+        } else if (plan.kernel == GEMM_KERNEL_SKINNY) {
+            if (!gemm::skinny_supports(a)) return GEMM_ERR_UNSUPPORTED;
+            plan.variant = 0;
+            if (plan.split_k == 0) plan.split_k = gemm::skinny_default_split(a, h->num_cus);
+        } else {
+            plan = gemm_plan_t{GEMM_KERNEL_GENERAL, 0, 1};
+        }
+    } else {
+        // The paper's roofline rule (Section 4.3) in arithmetic form: few rows of C make the
+        // call bandwidth-limited (stream B once, split K); otherwise it is a matrix-core problem.
+        if (gemm::skinny_supports(a) && N >= 256 && K >= 512) {
+            plan = gemm_plan_t{GEMM_KERNEL_SKINNY, 0, gemm::skinny_default_split(a, h->num_cus)};
+        } else if (gemm::tile_supports(a)) {
+            plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, choose_tile_variant(a, h->num_cus), 1};
+        }
+    }
+
+    // ---- launch ----
+    hipError_t e = hipSuccess;
+    if (plan.kernel == GEMM_KERNEL_SKINNY) {
+        const int64_t steps = (K + 15) / 16;
+        if (plan.split_k > steps) plan.split_k = (int)steps;
+        const size_t need = gemm::skinny_workspace_bytes(a, plan.split_k);
+        if (need) {
+            const gemm_status_t st = ensure_workspace(h, need, stream);
+            if (st != GEMM_OK) return st;
+        }
+        e = gemm::launch_skinny(a, plan.split_k, h->workspace, stream);
+    } else if (plan.kernel == GEMM_KERNEL_MFMA_TILE) {
+        e = gemm::launch_tile(a, plan.variant, 8, stream);
+    } else {
+        e = gemm::launch_general(a, stream);
+    }
+    if (e != hipSuccess) return GEMM_ERR_HIP;
+    h->last = plan;
+    return GEMM_OK;
+}

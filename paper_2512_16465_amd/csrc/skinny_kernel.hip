@@ -1,0 +1,258 @@
+// The skinny kernel: M <= 32 rows of C, bf16 / fp16 operands, A row-major (k contiguous) and
+// B row-major K x N (n contiguous) -- the decode-shaped product whose cost is reading B once.
+// By the paper's roofline rule (Section 4.3) such a call sits left of the matrix-core ridge, so
+// the objective is memory throughput, not matrix-core occupancy: B streams HBM -> registers
+// with no LDS staging, many 16-byte loads in flight per wave, and the K range is split over
+// waves (reduced through LDS) and over workgroups (reduced through an fp32 workspace in a
+// fixed order, so results are reproducible bit for bit).
+//
+// Data path of one wave for one step of 16 along k and 256 columns:
+//   lane (c = lane%32, h = lane/32) loads rows k0+8h .. k0+8h+7 of B, columns 8c .. 8c+7
+//   (eight 16-byte loads), transposes the 8x8 block of 16-bit values in registers with
+//   v_perm_b32, and so holds, for each j < 8, the B operand of a 32x32x16 MFMA for column
+//   8c+j.  MFMA j accumulates C[0:32, {8c+j : c}]; a lane ends up owning 8 consecutive columns
+//   of 16 rows, which it stores as full 16- or 32-byte vectors.
+#include "common.hpp"
+
+namespace gemm {
+
+namespace {
+
+constexpr int SK_COLS = 256;     // columns per workgroup
+constexpr int SK_WAVES = 8;      // waves per workgroup, each a slice of the workgroup's k range
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t sk_rsrc(const void* base, int64_t bytes) {
+    const int64_t cap = 0xffffffffll;
+    const uint32_t n = (uint32_t)(bytes < 0 ? 0 : (bytes > cap ? cap : bytes));
+    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)n, 0x00020000);
+}
+
+template <bool IS_BF16>
+__device__ __forceinline__ f32x16 sk_mfma(u32x4 a, u32x4 b, f32x16 c) {
+    if constexpr (IS_BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+struct SkStage {
+    u32x4 a;
+    u32x4 b[8];
+};
+
+// Stores 8 consecutive outputs of one row, after the epilogue, in the type of C.
+__device__ __forceinline__ void sk_store_row(const Args& a, int64_t row, int64_t col, const float (&x)[8], bool vec_ok) {
+    float o[8];
+    const int64_t idx = row * a.ldc + col;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float c_in = (a.beta != 0.0f) ? load_elem(a.C, a.out_dtype, idx + e) : 0.0f;
+        const float bj = a.bias ? load_elem(a.bias, a.bias_dtype, col + e) : 0.0f;
+        o[e] = epilogue_value(x[e], a.alpha, a.beta, c_in, bj, a.act);
+    }
+    if (a.out_dtype == DT_F32) {
+        float* p = (float*)a.C + idx;
+        if (vec_ok) {
+            *(f32x4*)p = f32x4{o[0], o[1], o[2], o[3]};
+            *(f32x4*)(p + 4) = f32x4{o[4], o[5], o[6], o[7]};
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[e] = o[e];
+        }
+    } else {
+        uint16_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = a.out_dtype == DT_BF16 ? f32_to_bf16_bits(o[e]) : f32_to_f16_bits(o[e]);
+        uint16_t* p = (uint16_t*)a.C + idx;
+        if (vec_ok) {
+            u32x4 u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) u[e] = (uint32_t)h[2 * e] | ((uint32_t)h[2 * e + 1] << 16);
+            *(u32x4*)p = u;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[e] = h[e];
+        }
+    }
+}
+
+template <bool IS_BF16>
+__global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int split_k, float* ws, int c_vec_ok) {
+    // partial accumulators of the upper half of the waves, [wave][register][lane]
+    __shared__ float red[(SK_WAVES / 2) * 128 * 64];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int M = (int)a.M, K = (int)a.K;
+    const int64_t N = a.N;
+
+    // k range of this workgroup and of this wave, in steps of 16
+    const int total_steps = (K + 15) / 16;
+    const int per_split = (total_steps + split_k - 1) / split_k;
+    const int wg_beg = blockIdx.y * per_split;
+    const int wg_end = (wg_beg + per_split) < total_steps ? (wg_beg + per_split) : total_steps;
+    const int wg_steps = wg_end > wg_beg ? wg_end - wg_beg : 0;
+    const int per_wave = (wg_steps + SK_WAVES - 1) / SK_WAVES;
+    const int my_beg = wg_beg + wave * per_wave;
+    const int my_end = (my_beg + per_wave) < wg_end ? (my_beg + per_wave) : wg_end;
+
+    const int64_t col0 = (int64_t)blockIdx.x * SK_COLS + 8 * l32;       // first of this lane's 8 columns
+    const bool col_ok = col0 < N;                                        // N % 8 == 0: all 8 or none
+    const int64_t col_ld = col_ok ? col0 : N - 8;                        // loads stay inside the matrix
+    const int a_row = l32 < M ? l32 : M - 1;                             // rows >= M are computed from a valid row, never stored
+
+    const __amdgpu_buffer_rsrc_t rb = sk_rsrc(a.B, ((int64_t)(K - 1) * a.ldb + N) * 2);   // rows >= K read as zero
+    const __amdgpu_buffer_rsrc_t ra = sk_rsrc(a.A, ((int64_t)(M - 1) * a.lda + K) * 2);
+    const uint32_t ldb_b = (uint32_t)a.ldb * 2;
+    const uint32_t a_row_off = (uint32_t)(a_row * a.lda * 2);
+
+    f32x16 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+
+    auto load = [&](SkStage& st, int step) {
+        const int k = step * 16 + 8 * lhi;
+        // A: 8 consecutive k of row a_row; K % 8 == 0, so the chunk is inside or outside as a whole
+        const int ka = k < K ? k : K - 8;
+        st.a = __builtin_amdgcn_raw_buffer_load_b128(ra, a_row_off + (uint32_t)ka * 2, 0, 0);
+        if (k >= K) st.a = u32x4{0u, 0u, 0u, 0u};
+        uint32_t off = (uint32_t)k * ldb_b + (uint32_t)col_ld * 2;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            st.b[j] = __builtin_amdgcn_raw_buffer_load_b128(rb, off, 0, 0);
+            off += ldb_b;
+        }
+    };
+    auto process = [&](const SkStage& st) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            u32x4 o;
+            const uint32_t sel = (n & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+            for (int kp = 0; kp < 4; ++kp)
+                o[kp] = __builtin_amdgcn_perm(st.b[2 * kp + 1][n >> 1], st.b[2 * kp][n >> 1], sel);
+            acc[n] = sk_mfma<IS_BF16>(st.a, o, acc[n]);
+        }
+    };
+
+    SkStage s0, s1;
+    if (my_beg < my_end) load(s0, my_beg);
+    for (int s = my_beg; s < my_end; s += 2) {
+        if (s + 1 < my_end) load(s1, s + 1);
+        process(s0);
+        if (s + 2 < my_end) load(s0, s + 2);
+        if (s + 1 < my_end) process(s1);
+    }
+
+    // fold the waves' partial sums pairwise through LDS: (0..3)+=(4..7), (0,1)+=(2,3), 0+=1
+#pragma unroll
+    for (int half = SK_WAVES / 2; half >= 1; half >>= 1) {
+        if (wave >= half && wave < 2 * half) {
+            float* dst = red + (wave - half) * 128 * 64 + lane;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) dst[(j * 16 + v) * 64] = acc[j][v];
+        }
+        __syncthreads();
+        if (wave < half) {
+            const float* src = red + wave * 128 * 64 + lane;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[j][v] += src[(j * 16 + v) * 64];
+        }
+        __syncthreads();
+    }
+
+    if (wave == 0 && col_ok) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = 8 * (v >> 2) + 4 * lhi + (v & 3);
+            if (row < M) {
+                float x[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) x[j] = acc[j][v];
+                if (split_k > 1) {
+                    float* p = ws + ((int64_t)blockIdx.y * M + row) * N + col0;
+                    *(f32x4*)p = f32x4{x[0], x[1], x[2], x[3]};
+                    *(f32x4*)(p + 4) = f32x4{x[4], x[5], x[6], x[7]};
+                } else {
+                    sk_store_row(a, row, col0, x, c_vec_ok != 0);
+                }
+            }
+        }
+    }
+}
+
+// Sums the split-K slices in the order 0, 1, ..., S-1 and applies the epilogue; 8 columns per thread.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(Args a, int split_k, const float* ws, int c_vec_ok) {
+    const int64_t groups_per_row = a.N / 8;
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= a.M * groups_per_row) return;
+    const int64_t row = g / groups_per_row, col = (g % groups_per_row) * 8;
+    float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < split_k; ++s) {
+        const float* p = ws + ((int64_t)s * a.M + row) * a.N + col;
+        const f32x4 lo = *(const f32x4*)p, hi = *(const f32x4*)(p + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { x[e] += lo[e]; x[4 + e] += hi[e]; }
+    }
+    sk_store_row(a, row, col, x, c_vec_ok != 0);
+}
+
+}  // namespace
+
+bool skinny_supports(const Args& a) {
+    if (a.dtype != DT_BF16 && a.dtype != DT_F16) return false;
+    if (a.transA || a.transB) return false;
+    if (a.M < 1 || a.M > 32 || a.N < 8 || a.K < 8) return false;
+    if ((a.N & 7) || (a.K & 7) || (a.lda & 7) || (a.ldb & 7)) return false;
+    if (((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15)) return false;
+    // 32-bit byte offsets into A and B (with room for the rows past K that read as zero)
+    if (((a.K + 16) * a.ldb) * 2 >= ((int64_t)1 << 31)) return false;
+    if ((a.M * a.lda) * 2 >= ((int64_t)1 << 31)) return false;
+    if ((a.N + SK_COLS - 1) / SK_COLS > 65535 * 16) return false;
+    return true;
+}
+
+int skinny_default_split(const Args& a, int num_cus) {
+    const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS;
+    const int64_t steps = (a.K + 15) / 16;
+    int64_t s = (num_cus + groups - 1) / groups;          // about one workgroup per compute unit
+    const int64_t max_s = steps / (SK_WAVES * 4);         // keep at least 4 steps per wave
+    if (s > max_s) s = max_s;
+    if (s > 64) s = 64;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
+size_t skinny_workspace_bytes(const Args& a, int split_k) {
+    return split_k > 1 ? (size_t)split_k * (size_t)a.M * (size_t)a.N * sizeof(float) : 0;
+}
+
+hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream_t stream) {
+    const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS;
+    const int64_t steps = (a.K + 15) / 16;
+    if (split_k < 1) split_k = 1;
+    if (split_k > steps) split_k = (int)steps;
+    if (split_k > 1 && workspace == nullptr) return hipErrorInvalidValue;
+    const int esz = a.out_dtype == DT_F32 ? 4 : 2;
+    // 8 outputs per vector store: 32 bytes of fp32 or 16 bytes of a 16-bit type
+    const int c_vec_ok = (a.ldc % 8 == 0) && ((uintptr_t)a.C % (esz == 4 ? 16 : 16) == 0);
+    const dim3 grid((unsigned)groups, (unsigned)split_k), block(SK_WAVES * 64);
+    if (a.dtype == DT_BF16)
+        hipLaunchKernelGGL(skinny_nn_kernel<true>, grid, block, 0, stream, a, split_k, workspace, c_vec_ok);
+    else
+        hipLaunchKernelGGL(skinny_nn_kernel<false>, grid, block, 0, stream, a, split_k, workspace, c_vec_ok);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || split_k == 1) return e;
+    const int64_t threads = a.M * (a.N / 8);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
+                       a, split_k, (const float*)workspace, c_vec_ok);
+    return hipGetLastError();
+}
+
+}  // namespace gemm

@@ -1,0 +1,278 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle, element by
+element on seeded inputs at sizes the oracle finishes in seconds.  Shapes span several macro
+tiles and leave ragged tails in every dimension."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2512_16465_amd as lg
+import workloads as wl
+from gpu_harness import (DeviceProblem, assert_close, c_bits_as_uint, check_full, decode_c,
+                         expected_bits_exact, oracle_problem, stream_ptr)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def handle():
+    h = lg.gemm_create()
+    yield h
+    torch.cuda.synchronize()
+    lg.gemm_destroy(h)
+
+
+def base_cfg(M, N, K, ta, tb, dtype=wl.BF16, out=None, **kw):
+    return wl.Config("t", M, N, K, ta, tb, dtype, dtype if out is None else out, **kw)
+
+
+def num_tile_variants():
+    n = 0
+    while lg.gemm_variant_name(lg.GEMM_KERNEL_MFMA_TILE, n) is not None:
+        n += 1
+    return n
+
+
+# ------------------------------------------------------------------ C1: the fp32 parity configuration
+
+def test_c1_fp32_full_matrix(handle):
+    cfg = wl.CONFIGS["C1"]
+    inp = wl.make_inputs(cfg)
+    p = DeviceProblem(cfg, inp)
+    p.run(handle)
+    check_full(cfg, inp, p.result_bits(), "C1")
+
+
+# ------------------------------------------------------------------ macro-tile kernels, every variant
+
+@pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0), (1, 1), (1, 0)])
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F16])
+def test_tile_variants_gaussian(handle, ta, tb, dtype):
+    # 3 x 3 tiles of 256 with ragged tails; K leaves a masked partial slab (K % 64 = 40)
+    M, N, K = 520, 584, 424
+    for out in (dtype, wl.F32):
+        cfg = base_cfg(M, N, K, ta, tb, dtype, out, a_dist=("normal", 1.0), b_dist=("normal", 0.5))
+        inp = wl.make_inputs(cfg, 31 + ta * 2 + tb)
+        ref, _, mag = oracle.gemm_full(oracle_problem(cfg, inp), want_bounds=True)
+        for v in range(num_tile_variants()):
+            print(f"tile variant {v} ta={ta} tb={tb} dtype={dtype} out={out}", flush=True)
+            lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
+            p = DeviceProblem(cfg, inp)
+            p.run(handle)
+            assert lg.gemm_get_last_plan(handle)[:2] == (lg.GEMM_KERNEL_MFMA_TILE, v)
+            assert_close(cfg, decode_c(cfg, p.result_bits()), ref, mag, f"variant {v}")
+    lg.gemm_set_plan(handle)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0), (1, 1), (1, 0)])
+def test_tile_variants_integer_exact(handle, ta, tb):
+    # integer entries: every partial sum is exact in fp32, the answer is unique -> equal values required
+    M, N, K = 264, 776, 1096
+    for out in (wl.BF16, wl.F32):
+        cfg = base_cfg(M, N, K, ta, tb, wl.BF16, out, alpha=2.0, beta=-1.0, bias_dist=("normal", 1.0), bias_dtype=wl.F32,
+                       lda=(M if ta else K) + 8, ldb=(K if tb else N) + 16, ldc=N + 3)
+        inp, _ = wl.make_integer_inputs(cfg, 77, -2, 2)
+        want = oracle.decode(out, expected_bits_exact(cfg, inp))
+        for v in range(num_tile_variants()):
+            print(f"integer tile variant {v} ta={ta} tb={tb} out={out}", flush=True)
+            lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
+            p = DeviceProblem(cfg, inp)
+            p.run(handle)
+            got = decode_c(cfg, p.result_bits())
+            assert np.array_equal(got, want), f"variant {v}: {np.sum(got != want)} wrong elements"
+            # the padding columns of C (ldc > N) must be untouched
+            pad_got = p.result_bits()[:-1, cfg.N:]
+            pad_want = inp["C"].reshape(M, cfg.ld_c())[:-1, cfg.N:]
+            assert np.array_equal(pad_got, pad_want)
+    lg.gemm_set_plan(handle)
+
+
+def test_tile_epilogue_bias_gelu_beta(handle):
+    M, N, K = 300, 392, 256
+    cfg = base_cfg(M, N, K, 0, 1, wl.BF16, wl.BF16, alpha=0.5, beta=1.5, a_dist=("normal", 1.0),
+                   b_dist=("normal", 0.1), c_dist=("normal", 1.0), bias_dist=("normal", 0.5),
+                   bias_dtype=wl.BF16, act=wl.ACT_GELU_ERF)
+    inp = wl.make_inputs(cfg, 5)
+    for v in range(num_tile_variants()):
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        check_full(cfg, inp, p.result_bits(), f"epilogue variant {v}")
+    lg.gemm_set_plan(handle)
+
+
+def test_small_tile_problem_single_partial_slab(handle):
+    # K smaller than one slab; M, N smaller than one tile
+    cfg = base_cfg(40, 24, 8, 0, 1, wl.F16, wl.F16)
+    inp = wl.make_inputs(cfg, 9)
+    for v in range(num_tile_variants()):
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        check_full(cfg, inp, p.result_bits(), f"tiny variant {v}")
+    lg.gemm_set_plan(handle)
+
+
+# ------------------------------------------------------------------ skinny split-K kernel
+
+@pytest.mark.parametrize("M", [1, 5, 32])
+def test_skinny_gaussian_and_split_agreement(handle, M):
+    N, K = 776, 2056          # 4 column groups with a ragged last one; K % 16 = 8 leaves half a step
+    cfg = base_cfg(M, N, K, 0, 0, wl.BF16, wl.BF16, alpha=1.0, beta=1.0, a_dist=("normal", 1.0),
+                   b_dist=("normal", 0.02), c_dist=("normal", 1.0), lda=K + 8, ldb=N + 24)
+    inp = wl.make_inputs(cfg, 40 + M)
+    ref, _, mag = oracle.gemm_full(oracle_problem(cfg, inp), want_bounds=True)
+    for s in (1, 2, 3, 8):
+        print(f"skinny M={M} split={s}", flush=True)
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 0, s)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_SKINNY, 0, s)
+        assert_close(cfg, decode_c(cfg, p.result_bits()), ref, mag, f"skinny split {s}")
+    lg.gemm_set_plan(handle)
+
+
+@pytest.mark.parametrize("out", [wl.BF16, wl.F32])
+def test_skinny_integer_exact_all_splits_equal(handle, out):
+    M, N, K = 19, 1032, 4104
+    cfg = base_cfg(M, N, K, 0, 0, wl.BF16, out, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.BF16,
+                   ldc=N + 8)
+    inp, _ = wl.make_integer_inputs(cfg, 123, -1, 1)
+    want = oracle.decode(out, expected_bits_exact(cfg, inp))
+    for s in (0, 1, 2, 4, 7, 16):
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 0, s)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        got = decode_c(cfg, p.result_bits())
+        assert np.array_equal(got, want), f"split {s}: {np.sum(got != want)} wrong"
+    # the other kernel families agree bit for bit on integer data
+    for kern in (lg.GEMM_KERNEL_MFMA_TILE, lg.GEMM_KERNEL_GENERAL):
+        lg.gemm_set_plan(handle, kern, -1 if kern == lg.GEMM_KERNEL_MFMA_TILE else 0)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        assert np.array_equal(decode_c(cfg, p.result_bits()), want)
+    lg.gemm_set_plan(handle)
+
+
+def test_skinny_fp16_gelu(handle):
+    cfg = base_cfg(8, 512, 1024, 0, 0, wl.F16, wl.F16, a_dist=("normal", 1.0), b_dist=("normal", 0.05),
+                   bias_dist=("normal", 0.5), bias_dtype=wl.F16, act=wl.ACT_GELU_ERF)
+    inp = wl.make_inputs(cfg, 3)
+    p = DeviceProblem(cfg, inp)
+    p.run(handle)
+    assert lg.gemm_get_last_plan(handle)[0] == lg.GEMM_KERNEL_SKINNY
+    check_full(cfg, inp, p.result_bits(), "skinny fp16 gelu")
+
+
+# ------------------------------------------------------------------ general kernel: any shape, any alignment
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.F16, wl.BF16])
+def test_edge_shapes_through_the_boundary(handle, dtype):
+    rng = np.random.default_rng(17)
+    sizes = [1, 7, 31, 33, 255, 257]
+    combos = [(1, 1, 1), (7, 33, 31), (33, 7, 257), (255, 31, 7), (257, 1, 33), (1, 257, 255), (31, 255, 1)]
+    for (M, N, K) in combos:
+        assert M in sizes and N in sizes and K in sizes
+        ta, tb = int(rng.integers(2)), int(rng.integers(2))
+        cfg = base_cfg(M, N, K, ta, tb, dtype, dtype, alpha=1.25, beta=0.5, c_dist=("normal", 1.0),
+                       bias_dist=("normal", 1.0), bias_dtype=dtype,
+                       lda=(M if ta else K) + 3, ldb=(K if tb else N) + 1, ldc=N + 2)
+        inp = wl.make_inputs(cfg, 1000 + M + N + K)
+        p = DeviceProblem(cfg, inp, a_offset_elems=1, b_offset_elems=1)     # base pointers off by one element
+        p.run(handle)
+        assert lg.gemm_get_last_plan(handle)[0] == lg.GEMM_KERNEL_GENERAL
+        check_full(cfg, inp, p.result_bits(), f"edge {M}x{N}x{K} ta={ta} tb={tb}")
+
+
+def test_general_kernel_matches_on_aligned_shape(handle):
+    cfg = base_cfg(136, 264, 512, 0, 0, wl.BF16, wl.F32)
+    inp = wl.make_inputs(cfg, 2)
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_GENERAL, 0)
+    p = DeviceProblem(cfg, inp)
+    p.run(handle)
+    lg.gemm_set_plan(handle)
+    check_full(cfg, inp, p.result_bits(), "general")
+
+
+# ------------------------------------------------------------------ degenerate cases of the definition
+
+def test_empty_sum_and_zero_alpha(handle):
+    M, N = 37, 53
+    # K = 0: C = act(beta*C + bias)
+    cfg = base_cfg(M, N, 0, 0, 0, wl.BF16, wl.BF16, beta=2.0, c_dist=("normal", 1.0), bias_dist=("normal", 1.0),
+                   bias_dtype=wl.F32, act=wl.ACT_GELU_ERF, lda=8, ldb=N)
+    inp = wl.make_inputs(cfg, 4)
+    p = DeviceProblem(cfg, inp)
+    p.run(handle)
+    check_full(cfg, inp, p.result_bits(), "K=0")
+    # alpha = 0 with NaN in A: the product term is dropped altogether
+    cfg = base_cfg(M, N, 64, 0, 0, wl.BF16, wl.BF16, alpha=0.0, beta=1.0, c_dist=("normal", 1.0))
+    inp = wl.make_inputs(cfg, 6)
+    inp_nan = dict(inp)
+    inp_nan["A"] = wl.to_bits(np.full(inp["A"].shape, np.nan, np.float32), wl.BF16)
+    p = DeviceProblem(cfg, inp_nan)
+    p.run(handle)
+    got = decode_c(cfg, p.result_bits())
+    assert np.array_equal(got, oracle.decode(wl.BF16, inp["C"]).reshape(M, N))
+    # M = 0 or N = 0: nothing happens, status OK
+    ptr = p.A.data_ptr()
+    assert lg.gemm_run(handle, 0, N, 8, 0, 0, wl.BF16, 1.0, 0, 8, ptr, N, 0.0, 0, N, None, stream_ptr()) == lg.GEMM_OK
+    assert lg.gemm_run(handle, M, 0, 8, 0, 0, wl.BF16, 1.0, ptr, 8, 0, 1, 0.0, 0, 1, None, stream_ptr()) == lg.GEMM_OK
+
+
+def test_beta_zero_ignores_stale_c_and_is_deterministic(handle):
+    for (M, N, K, ta, tb) in [(512, 512, 512, 0, 1), (16, 1024, 2048, 0, 0), (100, 100, 100, 1, 0)]:
+        cfg = base_cfg(M, N, K, ta, tb, wl.BF16, wl.F32)
+        inp = wl.make_inputs(cfg, 8)
+        p = DeviceProblem(cfg, inp)            # C starts as NaN
+        p.run(handle)
+        first = c_bits_as_uint(cfg, p.result_bits()).copy()
+        assert np.all(np.isfinite(decode_c(cfg, p.result_bits())))
+        p.reset_c()
+        p.run(handle)
+        assert np.array_equal(first, c_bits_as_uint(cfg, p.result_bits()))      # same bits run to run
+
+
+def test_linearity_in_beta(handle):
+    cfg0 = base_cfg(32, 512, 1024, 0, 0, wl.BF16, wl.F32, beta=0.0)
+    cfg1 = wl.scaled(cfg0, beta=1.0, c_dist=("normal", 1.0))
+    inp0, inp1 = wl.make_inputs(cfg0, 21), wl.make_inputs(cfg1, 21)
+    p0, p1 = DeviceProblem(cfg0, inp0), DeviceProblem(cfg1, inp1)
+    p0.run(handle)
+    p1.run(handle)
+    diff = decode_c(cfg1, p1.result_bits()) - decode_c(cfg0, p0.result_bits())
+    c0 = oracle.decode(wl.F32, inp1["C"]).reshape(32, 512)
+    assert np.all(np.abs(diff - c0) <= 1e-5 * (np.abs(c0) + 1.0))
+
+
+# ------------------------------------------------------------------ error behaviour
+
+def test_invalid_arguments_leave_c_untouched(handle):
+    cfg = base_cfg(64, 64, 64, 0, 0, wl.BF16, wl.BF16)
+    inp = wl.make_inputs(cfg, 1)
+    p = DeviceProblem(cfg, inp)
+    before = p.result_bits().copy()
+    A, B, C, s = p.A.data_ptr(), p.B.data_ptr(), p.C.data_ptr(), stream_ptr()
+    run = lambda *a, **k: lg.gemm_run(*a, **k, check=False)
+    E = lg.GEMM_ERR_INVALID_ARG
+    assert run(0, 64, 64, 64, 0, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, C, 64, None, s) == E           # null handle
+    assert run(handle, -1, 64, 64, 0, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, C, 64, None, s) == E      # negative size
+    assert run(handle, 64, 64, 64, 0, 0, wl.BF16, 1.0, A, 63, B, 64, 0.0, C, 64, None, s) == E      # lda < K
+    assert run(handle, 64, 64, 64, 0, 0, wl.BF16, 1.0, A, 64, B, 63, 0.0, C, 64, None, s) == E      # ldb < N
+    assert run(handle, 64, 64, 64, 0, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, C, 63, None, s) == E      # ldc < N
+    assert run(handle, 64, 64, 64, 2, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, C, 64, None, s) == E      # bad op
+    assert run(handle, 64, 64, 64, 0, 0, 7, 1.0, A, 64, B, 64, 0.0, C, 64, None, s) == E            # bad dtype
+    assert run(handle, 64, 64, 64, 0, 0, wl.BF16, 1.0, 0, 64, B, 64, 0.0, C, 64, None, s) == E      # null A
+    assert run(handle, 64, 64, 64, 0, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, 0, 64, None, s) == E      # null C
+    bad_act = lg.make_epilogue(wl.BF16, 0, wl.BF16, 9)
+    assert run(handle, 64, 64, 64, 0, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, C, 64, bad_act, s) == E
+    f16_out = lg.make_epilogue(wl.F16, 0, wl.BF16, 0)
+    assert run(handle, 64, 64, 64, 0, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, C, 64, f16_out, s) == lg.GEMM_ERR_UNSUPPORTED
+    # a forced plan that cannot run the call is refused, not silently replaced
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 0, 2)
+    assert run(handle, 64, 64, 64, 0, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, C, 64, None, s) == lg.GEMM_ERR_UNSUPPORTED
+    lg.gemm_set_plan(handle)
+    assert lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, 99, 0, check=False) == E
+    assert "invalid" in lg.gemm_status_string(E)
+    after = p.result_bits()
+    assert np.array_equal(before.view(np.uint16), after.view(np.uint16))
