@@ -42,9 +42,8 @@ def _units():
     units = []
     for name in ("gemm_api.hip", "general_kernel.hip", "skinny_kernel.hip", "tile_dispatch.hip"):
         units.append((os.path.join(CSRC, name), os.path.join(OBJ, name.replace(".hip", ".o")), []))
-    for i in _tile_variant_indices():
-        units.append((os.path.join(CSRC, "tile_variant.hip"), os.path.join(OBJ, f"tile_variant_{i}.o"),
-                      [f"-DGEMM_TILE_VARIANT_INDEX={i}"]))
+    for i in _tile_variant_indices():      # one small source file per variant of tile_variants.def
+        units.append((os.path.join(CSRC, f"tile_variant_{i}.hip"), os.path.join(OBJ, f"tile_variant_{i}.o"), []))
     return units
 
 
@@ -52,7 +51,7 @@ def _newest_header():
     t = 0.0
     for root in (CSRC, os.path.join(os.path.dirname(HERE), "include")):
         for f in os.listdir(root):
-            if f.endswith((".hpp", ".h", ".def")):
+            if f.endswith((".hpp", ".h", ".def", ".inc")):
                 t = max(t, os.path.getmtime(os.path.join(root, f)))
     return t
 
