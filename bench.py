@@ -172,6 +172,9 @@ def main():
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true")
+    ap.add_argument("--kernel", type=int, default=0, help="force a kernel family (gemm_kernel_t); 0 = automatic")
+    ap.add_argument("--variant", type=int, default=-1, help="tile variant when --kernel is forced")
+    ap.add_argument("--split-k", type=int, default=0, help="split-K factor when --kernel is forced; 0 = automatic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library is single-GPU by design; run with --gpus 1 "
@@ -189,6 +192,8 @@ def main():
     lg.load_library()          # fails loudly when the HIP library is not built
     seed = wl.DEFAULT_SEED if args.seed is None else args.seed
     handle = lg.gemm_create()
+    if args.kernel:
+        lg.gemm_set_plan(handle, args.kernel, args.variant, args.split_k)
     names = [n.strip() for n in args.configs.split(",") if n.strip()]
     results = {}
     headline = None

@@ -57,7 +57,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const char* base, in
 template <int ROWS, int BK, int NT>
 struct LoaderKC {
     static constexpr int CPR = BK / 8, CHUNKS = ROWS * CPR, L = CHUNKS / NT;
-    static constexpr int GLOBAL_LOADS = L, LDS_WRITES = L;   // instructions per thread and slab
     static_assert(CHUNKS % NT == 0, "chunks must divide evenly over the threads");
     u32x4 r[L];
     uint32_t goff[L];
@@ -83,10 +82,16 @@ struct LoaderKC {
     }
     __device__ __forceinline__ void lstore(char* lds, int tid) const {
 #pragma unroll
-        for (int i = 0; i < L; ++i) {
-            const int id = i * NT + tid;
-            *(u32x4*)(lds + swz<CPR>(id / CPR, id % CPR)) = r[i];
-        }
+        for (int i = 0; i < L; ++i) store_piece(i, lds, tid);
+    }
+    // One piece = one 16-byte chunk: a single global load, a single LDS store.
+    static constexpr int PIECES = L;
+    __device__ __forceinline__ void load_piece(int i, __amdgpu_buffer_rsrc_t rsrc, int /*tid*/, int32_t /*ld_bytes*/) {
+        r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[i], 0, 0);
+    }
+    __device__ __forceinline__ void store_piece(int i, char* lds, int tid) const {
+        const int id = i * NT + tid;
+        *(u32x4*)(lds + swz<CPR>(id / CPR, id % CPR)) = r[i];
     }
     static __device__ __forceinline__ const char* tile_base(const void* p, int64_t first_row, int64_t ld) {
         return (const char*)p + first_row * ld * 2;
@@ -100,7 +105,6 @@ struct LoaderKC {
 template <int ROWS, int BK, int NT>
 struct LoaderMC {
     static constexpr int CPR = BK / 8, RC = ROWS / 8, UNITS = RC * CPR, U = (UNITS + NT - 1) / NT;
-    static constexpr int GLOBAL_LOADS = 8 * U, LDS_WRITES = 8 * U;
     static_assert(UNITS % 64 == 0, "whole waves must be active or idle");
     u32x4 r[U][8];
     uint32_t goff[U];
@@ -129,40 +133,31 @@ struct LoaderMC {
     }
     __device__ __forceinline__ void lstore(char* lds, int tid) const {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int unit = u * NT + tid, c = unit % RC, g = unit / RC;
-            if (UNITS % NT != 0 && unit >= UNITS) continue;
+        for (int q = 0; q < PIECES; ++q) store_piece(q, lds, tid);
+    }
+    // One load piece = one of the eight k-rows of a unit; one store piece = one of its eight
+    // output rows: four v_perm_b32 gather that row's 8 k-values, one 16-byte LDS store writes them.
+    static constexpr int PIECES = 8 * U;
+    __device__ __forceinline__ void load_piece(int q, __amdgpu_buffer_rsrc_t rsrc, int tid, int32_t ld_bytes) {
+        const int u = q / 8, j = q % 8;
+        if (UNITS % NT != 0 && u * NT + tid >= UNITS) return;
+        r[u][j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff[u], j * ld_bytes, 0);
+    }
+    __device__ __forceinline__ void store_piece(int q, char* lds, int tid) const {
+        const int u = q / 8, n = q % 8;
+        const int unit = u * NT + tid, c = unit % RC, g = unit / RC;
+        if (UNITS % NT != 0 && unit >= UNITS) return;
+        u32x4 o;
+        const uint32_t sel = (n & 1) ? 0x07060302u : 0x05040100u;   // high or low halves of both sources
 #pragma unroll
-            for (int n = 0; n < 8; ++n) {
-                u32x4 o;
-                const uint32_t sel = (n & 1) ? 0x07060302u : 0x05040100u;   // high or low halves of both sources
-#pragma unroll
-                for (int kp = 0; kp < 4; ++kp)
-                    o[kp] = __builtin_amdgcn_perm(r[u][2 * kp + 1][n >> 1], r[u][2 * kp][n >> 1], sel);
-                *(u32x4*)(lds + swz<CPR>(c * 8 + n, g)) = o;
-            }
-        }
+        for (int kp = 0; kp < 4; ++kp)
+            o[kp] = __builtin_amdgcn_perm(r[u][2 * kp + 1][n >> 1], r[u][2 * kp][n >> 1], sel);
+        *(u32x4*)(lds + swz<CPR>(c * 8 + n, g)) = o;
     }
     static __device__ __forceinline__ const char* tile_base(const void* p, int64_t first_row, int64_t /*ld*/) {
         return (const char*)p + first_row * 2;
     }
     static __device__ __forceinline__ int64_t k_step_bytes(int64_t ld) { return (int64_t)BK * ld * 2; }
-};
-
-// Scheduling hint for one k-step: NM MFMAs with NR LDS reads, NW LDS writes and NV global loads
-// spread evenly between them, so that the matrix pipe never waits for an issue slot.
-template <int M, int NM, int NR, int NW, int NV>
-struct Sched {
-    static __device__ __forceinline__ void run() {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                  // one MFMA
-        constexpr int r = (NR * (M + 1)) / NM - (NR * M) / NM;
-        constexpr int w = (NW * (M + 1)) / NM - (NW * M) / NM;
-        constexpr int v = (NV * (M + 1)) / NM - (NV * M) / NM;
-        if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);             // LDS reads
-        if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);             // global loads
-        if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);             // LDS writes
-        if constexpr (M + 1 < NM) Sched<M + 1, NM, NR, NW, NV>::run();
-    }
 };
 
 template <bool IS_BF16>
@@ -327,31 +322,67 @@ __global__ __launch_bounds__(C::NT) void tile_kernel(Args a, int tiles_m, int ti
     //   k-step  NKS-2      : ... || registers holding slab kt+1 are written to the other stage
     //   barrier (the only one per step)
     //   k-step  NKS-1      : MFMAs || LDS reads of k-step 0 of slab kt+1 || global loads of slab kt+2
-    // The fragments of the first k-step are already in registers on entry.  HOT is the
-    // steady state (slabs kt+1 and kt+2 exist and need no mask); otherwise the flags decide.
-    auto step = [&](int kt, auto hot, bool have_next, int load_mode /*0 none, 1 full, 2 masked*/) {
-        constexpr bool HOT = decltype(hot)::value;
+    // The fragments of the first k-step are already in registers on entry.  In the steady state
+    // (HOT: slabs kt+1 and kt+2 exist and need no mask) the other instructions are dealt out one
+    // slot after each MFMA and fenced there, so that they issue in the shadow of the matrix pipe
+    // instead of in bursts; the remaining steps take the flags and a plain order.
+    constexpr int NM = TM * TN, NR = TM + TN;
+    constexpr int PW = LA::PIECES + LB::PIECES;          // store (and load) pieces per slab and thread
+    constexpr int SLOTS_W = NM - NM / 4 > 0 ? NM - NM / 4 : 1;   // leave the last MFMAs free so the stores drain before the barrier
+    auto read_one = [&](int buf, int stage, int ks, int q) {
+        const char* st = lds + stage * C::STAGE;
+        if (q < TM) af[buf][q] = *(const u32x4*)(st + (fa[q] ^ (uint32_t)(ks << 5)));
+        else bf[buf][q - TM] = *(const u32x4*)(st + (fb[q - TM] ^ (uint32_t)(ks << 5)));
+    };
+    auto step_hot = [&](int kt) {
+        const int stage = kt & 1;
+        char* wr = lds + (stage ^ 1) * C::STAGE;
+        const __amdgpu_buffer_rsrc_t ra = make_rsrc(pa + (kt + 2) * a_step, a_bytes - (kt + 2) * a_step);
+        const __amdgpu_buffer_rsrc_t rb = make_rsrc(pb + (kt + 2) * b_step, b_bytes - (kt + 2) * b_step);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            const bool last = ks == NKS - 1;
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                acc[m / TN][m % TN] = mfma32<IS_BF16>(af[cur][m / TN], bf[cur][m % TN], acc[m / TN][m % TN]);
+#pragma unroll
+                for (int q = (m * NR) / NM; q < ((m + 1) * NR) / NM; ++q)
+                    read_one(nxt, last ? stage ^ 1 : stage, last ? 0 : ks + 1, q);
+                if (ks == NKS - 2 && m < SLOTS_W) {
+#pragma unroll
+                    for (int q = (m * PW) / SLOTS_W; q < ((m + 1) * PW) / SLOTS_W; ++q) {
+                        if (q < LA::PIECES) la.store_piece(q, wr, tid);
+                        else lb.store_piece(q - LA::PIECES, wr + C::A_BYTES, tid);
+                    }
+                }
+                if (last) {
+#pragma unroll
+                    for (int q = (m * PW) / NM; q < ((m + 1) * PW) / NM; ++q) {
+                        if (q < LA::PIECES) la.load_piece(q, ra, tid, lda_b);
+                        else lb.load_piece(q - LA::PIECES, rb, tid, ldb_b);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (ks == NKS - 2) __syncthreads();
+        }
+    };
+    auto step = [&](int kt, bool have_next, int load_mode /*0 none, 1 full, 2 masked*/) {
         const int stage = kt & 1;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
             if (ks < NKS - 1) {
                 read_frags(nxt, stage, ks + 1);
-                if (ks == NKS - 2 && (HOT || have_next)) lstore(stage ^ 1);
+                if (ks == NKS - 2 && have_next) lstore(stage ^ 1);
                 mfmas(cur);
-                if (HOT) {
-                    if (ks == NKS - 2) Sched<0, TM * TN, TM + TN, LA::LDS_WRITES + LB::LDS_WRITES, 0>::run();
-                    else Sched<0, TM * TN, TM + TN, 0, 0>::run();
-                }
                 if (ks == NKS - 2) __syncthreads();
-                else __builtin_amdgcn_sched_barrier(0);
             } else {
-                if (HOT || have_next) read_frags(nxt, stage ^ 1, 0);
-                if (HOT || load_mode == 1) gload(kt + 2, full_t);
+                if (have_next) read_frags(nxt, stage ^ 1, 0);
+                if (load_mode == 1) gload(kt + 2, full_t);
                 else if (load_mode == 2) gload(kt + 2, masked_t);
                 mfmas(cur);
-                if (HOT) Sched<0, TM * TN, TM + TN, 0, LA::GLOBAL_LOADS + LB::GLOBAL_LOADS>::run();
-                __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
@@ -364,10 +395,10 @@ __global__ __launch_bounds__(C::NT) void tile_kernel(Args a, int tiles_m, int ti
         read_frags(0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         int kt = 0;
-        for (; kt + 2 < full_tiles; ++kt) step(kt, std::true_type{}, true, 1);
+        for (; kt + 2 < full_tiles; ++kt) step_hot(kt);
         for (; kt < k_tiles; ++kt) {
             const int nn = kt + 2;
-            step(kt, std::false_type{}, kt + 1 < k_tiles, nn < full_tiles ? 1 : (nn < k_tiles ? 2 : 0));
+            step(kt, kt + 1 < k_tiles, nn < full_tiles ? 1 : (nn < k_tiles ? 2 : 0));
         }
         __syncthreads();                 // every wave is done with the operand stages: LDS is reused below
     }
