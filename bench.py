@@ -175,6 +175,9 @@ def main():
     ap.add_argument("--kernel", type=int, default=0, help="force a kernel family (gemm_kernel_t); 0 = automatic")
     ap.add_argument("--variant", type=int, default=-1, help="tile variant when --kernel is forced")
     ap.add_argument("--split-k", type=int, default=0, help="split-K factor when --kernel is forced; 0 = automatic")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device-to-device copy (3 times) so that a counter run can scale "
+                         "FETCH_SIZE / WRITE_SIZE by what they read for a transfer of known size")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library is single-GPU by design; run with --gpus 1 "
@@ -191,6 +194,13 @@ def main():
     torch.cuda.set_device(0)
     lg.load_library()          # fails loudly when the HIP library is not built
     seed = wl.DEFAULT_SEED if args.seed is None else args.seed
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     handle = lg.gemm_create()
     if args.kernel:
         lg.gemm_set_plan(handle, args.kernel, args.variant, args.split_k)
