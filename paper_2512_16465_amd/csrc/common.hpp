@@ -79,12 +79,14 @@ __device__ __forceinline__ float epilogue_value(float acc, float alpha, float be
 
 // ---- host-side launchers, one per kernel family; each returns a hipError_t ----
 
-struct TileVariantInfo { const char* name; int BM, BN, BK, threads; };
+struct TileVariantInfo { const char* name; int BM, BN, BK, threads, kind; };
 
 int tile_num_variants();
 const TileVariantInfo* tile_variant_info(int variant);
 // true if the call satisfies the alignment/shape preconditions of the macro-tile kernels
 bool tile_supports(const Args& a);
+// further preconditions of one variant (beyond tile_supports)
+bool tile_variant_supports(const Args& a, int variant);
 hipError_t launch_tile(const Args& a, int variant, int group_m, hipStream_t stream);
 
 bool skinny_supports(const Args& a);

@@ -22,11 +22,12 @@ using gemm::Args;
 
 bool valid_dtype(int d) { return d == GEMM_F32 || d == GEMM_F16 || d == GEMM_BF16; }
 
-// Picks a tile variant for the macro-tile family: the large tile when it still yields enough
-// workgroups to occupy the compute units, the small tile otherwise.
+// Picks a tile variant for the macro-tile family: the large direct-to-LDS tile when it still
+// yields enough workgroups to occupy the compute units (its register-staged sibling when an
+// operand is too large for the direct loads' masking offset), the small tile otherwise.
 int choose_tile_variant(const Args& a, int num_cus) {
     const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (big * 2 >= num_cus) return 0;
+    if (big * 2 >= num_cus) return gemm::tile_variant_supports(a, 4) ? 4 : 0;
     return 3;
 }
 
@@ -169,6 +170,7 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
         if (plan.kernel == GEMM_KERNEL_MFMA_TILE) {
             if (!gemm::tile_supports(a)) return GEMM_ERR_UNSUPPORTED;
             if (plan.variant < 0) plan.variant = choose_tile_variant(a, h->num_cus);
+            if (!gemm::tile_variant_supports(a, plan.variant)) return GEMM_ERR_UNSUPPORTED;
             plan.split_k = 1;
         } else if (plan.kernel == GEMM_KERNEL_SKINNY) {
             if (!gemm::skinny_supports(a)) return GEMM_ERR_UNSUPPORTED;

@@ -3,7 +3,7 @@
 
 namespace gemm {
 
-#define GEMM_TILE_VARIANT(IDX, NAME, BM, BN, BK, WM, WN) \
+#define GEMM_TILE_VARIANT(IDX, NAME, KIND, BM, BN, BK, WM, WN, NS) \
     hipError_t launch_tile_variant_##IDX(const Args& a, int group_m, hipStream_t stream);
 #include "tile_variants.def"
 #undef GEMM_TILE_VARIANT
@@ -13,13 +13,13 @@ namespace {
 typedef hipError_t (*launch_fn)(const Args&, int, hipStream_t);
 
 const TileVariantInfo kInfo[] = {
-#define GEMM_TILE_VARIANT(IDX, NAME, BM, BN, BK, WM, WN) {NAME, BM, BN, BK, (WM) * (WN) * 64},
+#define GEMM_TILE_VARIANT(IDX, NAME, KIND, BM, BN, BK, WM, WN, NS) {NAME, BM, BN, BK, (WM) * (WN) * 64, KIND},
 #include "tile_variants.def"
 #undef GEMM_TILE_VARIANT
 };
 
 const launch_fn kLaunch[] = {
-#define GEMM_TILE_VARIANT(IDX, NAME, BM, BN, BK, WM, WN) launch_tile_variant_##IDX,
+#define GEMM_TILE_VARIANT(IDX, NAME, KIND, BM, BN, BK, WM, WN, NS) launch_tile_variant_##IDX,
 #include "tile_variants.def"
 #undef GEMM_TILE_VARIANT
 };
@@ -49,6 +49,14 @@ bool tile_supports(const Args& a) {
     const int64_t tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
     if (tiles > (int64_t)1 << 30) return false;
     return true;
+}
+
+// The direct-to-LDS variants mask lanes with a fixed out-of-range offset of 2 GiB - 16.
+bool tile_variant_supports(const Args& a, int variant) {
+    if (variant < 0 || variant >= kNum) return false;
+    if (kInfo[variant].kind == 0) return true;
+    const int64_t a_bytes = ((a.transA ? a.K : a.M) * a.lda) * 2, b_bytes = ((a.transB ? a.N : a.K) * a.ldb) * 2;
+    return a_bytes < 0x7ffffff0ll && b_bytes < 0x7ffffff0ll;
 }
 
 hipError_t launch_tile(const Args& a, int variant, int group_m, hipStream_t stream) {

@@ -1,0 +1,385 @@
+// The macro-tile GEMM kernel with direct-to-LDS operand loads (bf16 / fp16, gfx950).
+//
+// Same tiling as tile_kernel.hpp (BM x BN x BK workgroup tile, 32x32x16 MFMA accumulators per
+// wave, LDS-staged epilogue), but the operand slabs travel global memory -> LDS without passing
+// through registers (buffer_load ... lds, 16 bytes per lane), into a ring of NS stages, and are
+// issued a few at a time between the MFMAs of the whole k step.  That removes the bursts of
+// global loads and of LDS stores that the register-staged kernel suffers from (the texture path
+// of a compute unit moves 64 bytes per clock, the LDS write port 128), frees 64 registers, and
+// gives every load two full k steps to arrive.  It is the CDNA4 counterpart of the paper's
+// "asynchronous copy" and "multi-stage pipeline" strategies (Section 5.4, Table 1).
+//
+// A direct-to-LDS load writes lane l of a wave to LDS byte M0 + 16*l: the destination of one
+// instruction is a contiguous kilobyte.  The swizzled layouts are therefore produced on the
+// global side: each lane fetches the chunk that belongs in its LDS slot.
+//   k-contiguous operand (A in NN/NT, B in NT): LDS rows are k-contiguous, chunk (row, c) lives
+//     in slot swz(row, c); fragments are read with ds_read_b128 as in tile_kernel.hpp.
+//   m/n-contiguous operand (B in NN, A in TN): LDS holds the slab as [k][row], 16-byte chunk c of
+//     k-row k in slot k*(ROWS/8) + (c xor ((k&3)<<2)); the MFMA operand (8 consecutive k of one
+//     row per lane) is read with two transposing loads ds_read_b64_tr_b16, in which lane j of a
+//     16-lane group supplies the address of row k0 + j/4, columns 4*(j%4).., and lane i receives
+//     column i of rows k0 .. k0+3.
+// Loads past the end of an operand return zero through the buffer descriptor's range check, so
+// edge tiles need no clamping; a partial last k slab masks the lanes whose chunk lies beyond K
+// (k-contiguous operands) by giving them an out-of-range offset.
+#pragma once
+#include "tile_kernel.hpp"
+
+namespace gemm {
+namespace tile {
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_>
+struct DmaCfg : Cfg<BM_, BN_, BK_, WM_, WN_> {
+    static constexpr int NS = NS_;     // LDS stages in the ring
+    static_assert(NS_ >= 3, "the pipeline keeps two slabs in flight behind the one being multiplied");
+};
+
+#define GEMM_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+// One direct-to-LDS load: lane l fetches 16 bytes at byte offset `off` of the buffer and the
+// wave's 64 chunks land at LDS address `dst` + 16*l.  Only the device pass of the compiler sees
+// the builtin: the host pass does not accept it inside templates and would silently drop the
+// launch stub of every kernel that reaches it.
+__device__ __forceinline__ void load_to_lds_b128(__amdgpu_buffer_rsrc_t rsrc, char* dst, uint32_t off) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, GEMM_LDS_PTR(dst), 16, off, 0, 0, 0);
+#else
+    (void)rsrc; (void)dst; (void)off;
+#endif
+}
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// ---- operand movers ----
+
+// k-contiguous operand: ROWS x BK slab, element (row, k) at base + row*ld + k.
+template <int ROWS, int BK, int NT>
+struct DmaKC {
+    static constexpr int CPR = BK / 8, SLOTS = ROWS * CPR, L = SLOTS / NT;
+    static constexpr int BYTES = ROWS * BK * 2;
+    static constexpr bool TRANSPOSED = false;
+    static_assert(SLOTS % NT == 0, "slots must divide evenly over the threads");
+    uint32_t voff[L];      // byte offset of this lane's chunk from the slab's first byte
+
+    __device__ __forceinline__ void init(int tid, int64_t ld) {
+#pragma unroll
+        for (int i = 0; i < L; ++i) {
+            const uint32_t S = i * NT + tid;                      // LDS slot this lane fills with load i
+            const uint32_t line = S >> 3;
+            const uint32_t pos = (S & 7u) ^ ((line ^ (line >> 3)) & 7u);
+            const uint32_t chunk = (line << 3) | pos;             // logical chunk: row*CPR + c
+            const uint32_t row = chunk / CPR, c = chunk % CPR;
+            voff[i] = (uint32_t)((row * ld + c * 8) * 2);
+        }
+    }
+    // k offset (in elements) of the chunk of load i inside the slab
+    __device__ __forceinline__ int chunk_k(int i, int tid) const {
+        const uint32_t S = i * NT + tid, line = S >> 3;
+        const uint32_t pos = (S & 7u) ^ ((line ^ (line >> 3)) & 7u);
+        return (int)((((line << 3) | pos) % CPR) * 8);
+    }
+    __device__ __forceinline__ void issue(bool MASKED, int i, __amdgpu_buffer_rsrc_t rsrc, char* stage, int wave, int tid, int k0,
+                                          int K) const {
+        uint32_t off = voff[i];
+        if (MASKED && k0 + chunk_k(i, tid) >= K) off = 0x7ffffff0u;       // past the end of any supported operand: the slot is filled with zeros
+        load_to_lds_b128(rsrc, stage + (i * NT + wave * 64) * 16, off);
+    }
+    static __device__ __forceinline__ const char* tile_base(const void* p, int64_t first_row, int64_t ld) {
+        return (const char*)p + first_row * ld * 2;
+    }
+    static __device__ __forceinline__ int64_t k_step_bytes(int64_t /*ld*/) { return BK * 2; }
+    static __device__ __forceinline__ int64_t total_bytes(int64_t rows, int64_t K, int64_t ld) { return ((rows - 1) * ld + K) * 2; }
+
+    // fragment addressing: byte offset inside the slab of this lane's row for 32-row block t, k-chunk lhi
+    static __device__ __forceinline__ uint32_t frag_base(int row0, int l32, int lhi) { return swz<CPR>(row0 + l32, lhi); }
+    // fragments are ordinary LDS loads: the compiler tracks their completion itself
+    typedef u32x4 Raw;
+    static constexpr bool MANUAL_WAIT = false;
+    static __device__ __forceinline__ void read_frag(const char* slab, uint32_t base, int ks, Raw& r) {
+        r = *(const u32x4*)(slab + (base ^ (uint32_t)(ks << 5)));
+    }
+    static __device__ __forceinline__ u32x4 finish(const Raw& r) { return r; }
+};
+
+// m- or n-contiguous operand: element (k, row) at base + k*ld + row; LDS keeps [k][row].
+template <int ROWS, int BK, int NT>
+struct DmaMC {
+    static constexpr int CPK = ROWS / 8, SLOTS = BK * CPK, L = SLOTS / NT;   // chunks per k-row
+    static constexpr int BYTES = ROWS * BK * 2;
+    static constexpr bool TRANSPOSED = true;
+    static_assert(SLOTS % NT == 0 && CPK % 16 == 0, "a k-row must be whole 256-byte windows");
+    uint32_t voff[L];
+
+    __device__ __forceinline__ void init(int tid, int64_t ld) {
+#pragma unroll
+        for (int i = 0; i < L; ++i) {
+            const uint32_t S = i * NT + tid;
+            const uint32_t k = S / CPK, cs = S % CPK;
+            const uint32_t c = cs ^ ((k & 3u) << 2);
+            voff[i] = (uint32_t)((k * ld + c * 8) * 2);
+        }
+    }
+    __device__ __forceinline__ void issue(bool /*masked*/, int i, __amdgpu_buffer_rsrc_t rsrc, char* stage, int wave, int /*tid*/,
+                                          int /*k0*/, int /*K*/) const {
+        // k-rows past K lie past the end of the operand and read as zero by themselves
+        load_to_lds_b128(rsrc, stage + (i * NT + wave * 64) * 16, voff[i]);
+    }
+    static __device__ __forceinline__ const char* tile_base(const void* p, int64_t first_row, int64_t /*ld*/) {
+        return (const char*)p + first_row * 2;
+    }
+    static __device__ __forceinline__ int64_t k_step_bytes(int64_t ld) { return (int64_t)BK * ld * 2; }
+    static __device__ __forceinline__ int64_t total_bytes(int64_t rows, int64_t K, int64_t ld) { return ((K - 1) * ld + rows) * 2; }
+
+    // address this lane supplies to the transposing read for 32-row block starting at row0:
+    // k-row (8*lhi + j/4), columns row0 + 16*((lane%32)/16) + 4*(j%4), j = lane%16
+    static __device__ __forceinline__ uint32_t frag_base(int row0, int l32, int lhi) {
+        const uint32_t j = l32 & 15, grp = l32 >> 4;
+        const uint32_t k = 8 * lhi + (j >> 2);
+        const uint32_t col = row0 + 16 * grp + 4 * (j & 3);
+        const uint32_t cs = (col >> 3) ^ ((k & 3u) << 2);
+        return (k * CPK + cs) * 16 + (col & 7) * 2;
+    }
+    // The transposing reads are issued as assembly: the compiler would otherwise make each of
+    // them wait for every direct-to-LDS load in flight.  It therefore does not know when their
+    // results arrive; the kernel waits (lgkmcnt) before the first use, see wait_raw.
+    struct Raw { uint2 lo, hi; };
+    static constexpr bool MANUAL_WAIT = true;
+    static constexpr int KS_BYTES = 16 * CPK * 16, HALF_BYTES = 4 * CPK * 16;   // 16 and 4 k-rows further
+    static_assert(KS_BYTES * (BK / 16 - 1) + HALF_BYTES < 65536, "offsets must fit the instruction's immediate");
+    static __device__ __forceinline__ void read_frag(const char* slab, uint32_t base, int ks, Raw& r) {
+        const uint32_t addr = (uint32_t)(uintptr_t)GEMM_LDS_PTR(slab) + base;
+        static_assert(BK <= 64, "at most four k-steps per slab");
+        if (ks == 0) {
+            asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r.lo) : "v"(addr));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(HALF_BYTES));
+        } else if (ks == 1) {
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.lo) : "v"(addr), "n"(KS_BYTES));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(KS_BYTES + HALF_BYTES));
+        } else if (ks == 2) {
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.lo) : "v"(addr), "n"(2 * KS_BYTES));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(2 * KS_BYTES + HALF_BYTES));
+        } else {
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.lo) : "v"(addr), "n"(3 * KS_BYTES));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(3 * KS_BYTES + HALF_BYTES));
+        }
+    }
+    static __device__ __forceinline__ u32x4 finish(const Raw& r) { return u32x4{r.lo.x, r.lo.y, r.hi.x, r.hi.y}; }
+};
+
+// Waits until every LDS read issued so far has returned.  The raw fragments are passed through
+// the statement so that nothing that consumes them can be moved ahead of the wait.
+template <class Raw>
+__device__ __forceinline__ void wait_raw(Raw (&r)[2]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0].lo), "+v"(r[0].hi), "+v"(r[1].lo), "+v"(r[1].hi));
+}
+template <class Raw>
+__device__ __forceinline__ void wait_raw(Raw (&r)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(r[0].lo), "+v"(r[0].hi), "+v"(r[1].lo), "+v"(r[1].hi), "+v"(r[2].lo), "+v"(r[2].hi), "+v"(r[3].lo), "+v"(r[3].hi));
+}
+__device__ __forceinline__ void wait_raw(u32x4 (&)[2]) {}
+__device__ __forceinline__ void wait_raw(u32x4 (&)[4]) {}
+
+template <class C, bool IS_BF16, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok) {
+    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NT, TM = C::TM, TN = C::TN, NS = C::NS;
+    using EL = EpiLayout<C>;
+    constexpr int RING = NS * C::STAGE;
+    constexpr int LDS_BYTES = RING > EL::BYTES ? RING : EL::BYTES;
+    __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int wm = wave % C::WM, wn = wave / C::WM;
+
+    int tm, tn;
+    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+    const int K = (int)a.K;
+
+    using LA = typename std::conditional<A_KC, DmaKC<BM, BK, NT>, DmaMC<BM, BK, NT>>::type;
+    using LB = typename std::conditional<B_KC, DmaKC<BN, BK, NT>, DmaMC<BN, BK, NT>>::type;
+    LA la;
+    LB lb;
+    la.init(tid, a.lda);
+    lb.init(tid, a.ldb);
+    const char* pa = LA::tile_base(a.A, m0, a.lda);
+    const char* pb = LB::tile_base(a.B, n0, a.ldb);
+    const int64_t a_step = LA::k_step_bytes(a.lda), b_step = LB::k_step_bytes(a.ldb);
+    const int64_t a_bytes = LA::total_bytes(a.M, a.K, a.lda) - (pa - (const char*)a.A);
+    const int64_t b_bytes = LB::total_bytes(a.N, a.K, a.ldb) - (pb - (const char*)a.B);
+
+    uint32_t fa[TM], fb[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[i] = LA::frag_base(wm * C::WTM + i * 32, l32, lhi);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[j] = C::A_BYTES + LB::frag_base(wn * C::WTN + j * 32, l32, lhi);
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int k_tiles = (K + BK - 1) / BK;
+    const int full_tiles = K / BK;
+    constexpr int NKS = BK / 16;
+    constexpr int NM = TM * TN, NR = TM + TN;
+    constexpr int LPT = LA::L + LB::L;            // direct-to-LDS loads per thread and slab
+    constexpr int D = NS - 1;                     // slab kt + D is requested while slab kt is multiplied
+
+    typename LA::Raw af[2][TM];      // operand fragments as read from LDS, double-buffered in registers
+    typename LB::Raw bf[2][TN];
+
+    auto read_one = [&](int buf, int stage, int ks, int q) {
+        const char* st = lds + stage * C::STAGE;
+        if (q < TM) LA::read_frag(st, fa[q], ks, af[buf][q]);
+        else LB::read_frag(st, fb[q - TM], ks, bf[buf][q - TM]);
+    };
+    // all MFMAs of one k-sub-step; `slot` runs after MFMA m
+    auto run_mfmas = [&](int cur, auto slot) {
+        if (LA::MANUAL_WAIT) wait_raw(af[cur]);
+        if (LB::MANUAL_WAIT) wait_raw(bf[cur]);
+        u32x4 ua[TM], ub[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) ua[i] = LA::finish(af[cur][i]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) ub[j] = LB::finish(bf[cur][j]);
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            slot(m, 0);
+            acc[m / TN][m % TN] = mfma32<IS_BF16>(ua[m / TN], ub[m % TN], acc[m / TN][m % TN]);
+            slot(m, 1);
+        }
+    };
+    auto issue_one = [&](int q, __amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, char* stage, int k0, auto masked) {
+        constexpr bool M = decltype(masked)::value;
+        if (q < LA::L) la.issue(M, q, ra, stage, wave, tid, k0, K);
+        else lb.issue(M, q - LA::L, rb, stage + C::A_BYTES, wave, tid, k0, K);
+    };
+    auto issue_tile = [&](int t, auto masked) {
+        const __amdgpu_buffer_rsrc_t ra = make_rsrc(pa + t * a_step, a_bytes - t * a_step);
+        const __amdgpu_buffer_rsrc_t rb = make_rsrc(pb + t * b_step, b_bytes - t * b_step);
+        char* stage = lds + (t % NS) * C::STAGE;
+#pragma unroll
+        for (int q = 0; q < LPT; ++q) issue_one(q, ra, rb, stage, t * BK, masked);
+    };
+
+    // The barrier of a k step: this wave's share of slab kt+1 has landed once at most `pending`
+    // younger loads are outstanding (loads complete in order); after the barrier every wave's
+    // share has, and every wave is done reading slab kt-... whose stage the next loads overwrite.
+#define GEMM_WAIT_VM_BARRIER(N)                                                                                   \
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory")
+
+    constexpr int BAR_SLOT = NM / 4;              // MFMAs of the last k-sub-step issued before the barrier
+    constexpr int LOAD_SLOTS = (NKS - 1) * NM + BAR_SLOT;   // all loads of a slab are issued before its step's barrier
+
+    // steady state: slabs kt+1 .. kt+D exist and need no mask
+    auto step_hot = [&](int kt) {
+        const int stage = kt % NS, next = (kt + 1) % NS;
+        const int t = kt + D;
+        const __amdgpu_buffer_rsrc_t ra = make_rsrc(pa + t * a_step, a_bytes - t * a_step);
+        const __amdgpu_buffer_rsrc_t rb = make_rsrc(pb + t * b_step, b_bytes - t * b_step);
+        char* dst = lds + (t % NS) * C::STAGE;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            const bool last = ks == NKS - 1;
+            run_mfmas(cur, [&](int m, int after) {
+                if (!after) {
+                    if (last && m == BAR_SLOT) GEMM_WAIT_VM_BARRIER((D - 1) * LPT);
+                    return;
+                }
+                if (!last) {
+#pragma unroll
+                    for (int q = (m * NR) / NM; q < ((m + 1) * NR) / NM; ++q) read_one(nxt, stage, ks + 1, q);
+                } else if (m >= BAR_SLOT) {
+                    constexpr int RS = NM - BAR_SLOT - NM / 4 > 0 ? NM - BAR_SLOT - NM / 4 : 1;   // slots used for the reads
+                    const int mm = m - BAR_SLOT;
+                    if (mm < RS) {
+#pragma unroll
+                        for (int q = (mm * NR) / RS; q < ((mm + 1) * NR) / RS; ++q) read_one(nxt, next, 0, q);
+                    }
+                }
+                const int slot = ks * NM + m;
+                if (slot < LOAD_SLOTS) {
+#pragma unroll
+                    for (int q = (slot * LPT) / LOAD_SLOTS; q < ((slot + 1) * LPT) / LOAD_SLOTS; ++q)
+                        issue_one(q, ra, rb, dst, t * BK, std::false_type{});
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        }
+    };
+    // the first and last steps: flags instead of assumptions, everything outstanding is awaited
+    auto step_edge = [&](int kt) {
+        const int stage = kt % NS, next = (kt + 1) % NS;
+        const int t = kt + D;
+        if (t < full_tiles) issue_tile(t, std::false_type{});
+        else if (t < k_tiles) issue_tile(t, std::true_type{});
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks < NKS - 1) {
+#pragma unroll
+                for (int q = 0; q < NR; ++q) read_one(nxt, stage, ks + 1, q);
+            } else if (kt + 1 < k_tiles) {
+                GEMM_WAIT_VM_BARRIER(0);
+#pragma unroll
+                for (int q = 0; q < NR; ++q) read_one(nxt, next, 0, q);
+            }
+            run_mfmas(cur, [](int, int) {});
+        }
+    };
+
+    if (k_tiles > 0) {
+#pragma unroll
+        for (int t = 0; t < D; ++t) {
+            if (t < full_tiles) issue_tile(t, std::false_type{});
+            else if (t < k_tiles) issue_tile(t, std::true_type{});
+        }
+        GEMM_WAIT_VM_BARRIER(0);
+#pragma unroll
+        for (int q = 0; q < NR; ++q) read_one(0, 0, 0, q);
+        __builtin_amdgcn_sched_barrier(0);
+        int kt = 0;
+        for (; kt + D < full_tiles; ++kt) step_hot(kt);
+        for (; kt < k_tiles; ++kt) step_edge(kt);
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS is reused by the epilogue
+#undef GEMM_WAIT_VM_BARRIER
+
+    tile_epilogue<C>(acc, lds, a, m0, n0, c_vec_ok);
+}
+
+template <class C>
+hipError_t launch_dma_variant(const Args& a, int group_m, hipStream_t stream) {
+    const int tiles_m = (int)((a.M + C::BM - 1) / C::BM), tiles_n = (int)((a.N + C::BN - 1) / C::BN);
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(C::NT);
+    const bool bf = a.dtype == DT_BF16;
+    const bool akc = !a.transA, bkc = a.transB != 0;
+    const int c_vec_ok = (a.ldc % 4 == 0) && ((uintptr_t)a.C % (a.out_dtype == DT_F32 ? 16 : 8) == 0);
+#define GEMM_TILE_LAUNCH(BF, AKC, BKC)                                                                           \
+    hipLaunchKernelGGL((tile_dma_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, \
+                       c_vec_ok)
+    if (bf) {
+        if (akc && bkc) GEMM_TILE_LAUNCH(true, true, true);
+        else if (akc && !bkc) GEMM_TILE_LAUNCH(true, true, false);
+        else if (!akc && bkc) GEMM_TILE_LAUNCH(true, false, true);
+        else GEMM_TILE_LAUNCH(true, false, false);
+    } else {
+        if (akc && bkc) GEMM_TILE_LAUNCH(false, true, true);
+        else if (akc && !bkc) GEMM_TILE_LAUNCH(false, true, false);
+        else if (!akc && bkc) GEMM_TILE_LAUNCH(false, false, true);
+        else GEMM_TILE_LAUNCH(false, false, false);
+    }
+#undef GEMM_TILE_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace tile
+}  // namespace gemm

@@ -238,6 +238,75 @@ struct EpiLayout {
     static_assert(LPR <= 64 && 64 % LPR == 0, "a row must be covered by a whole fraction of a wave");
 };
 
+// The epilogue of one workgroup tile.  In a 32x32 accumulator lane (l32, lhi) owns column l32 and
+// rows 8*(v/4) + 4*lhi + v%4.  Band by band (32 rows) each wave transposes that through its
+// private LDS region so that a lane ends up with four consecutive columns of one row, and C is
+// read and written with full-width vector accesses.  Every wave of the workgroup must be done
+// with the operand stages in LDS before this is called.
+template <class C>
+__device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[C::TM][C::TN], char* lds, const Args& a,
+                                              int64_t m0, int64_t n0, int c_vec_ok) {
+    constexpr int TM = C::TM, TN = C::TN;
+    using EL = EpiLayout<C>;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int wm = wave % C::WM, wn = wave / C::WM;
+    char* region = lds + wave * EL::REGION;
+    const float alpha = a.alpha, beta = a.beta;
+    const int act = a.act;
+    const int cl = (lane % EL::LPR) * 4;                 // first of this lane's four columns inside the wave sub-block
+    const int64_t col = n0 + wn * C::WTN + cl;
+    f32x4 bias4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (a.bias) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (col + e < a.N) bias4[e] = load_elem(a.bias, a.bias_dtype, col + e);
+    }
+
+    auto run_epilogue = [&](auto tag) {
+        using OV = OutVec<decltype(tag)::value>;
+        typename OV::elem* Cp = (typename OV::elem*)a.C;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    *(float*)(region + ((8 * (v >> 2) + 4 * lhi + (v & 3)) * EL::RS + j * 32 + l32) * 4) = acc[i][j][v];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll 2
+            for (int it = 0; it < 32 / EL::RPI; ++it) {
+                const int rl = it * EL::RPI + lane / EL::LPR;
+                const f32x4 s = *(const f32x4*)(region + (rl * EL::RS + cl) * 4);
+                const int64_t row = m0 + wm * C::WTM + i * 32 + rl;
+                if (row < a.M && col < a.N) {
+                    typename OV::elem* p = Cp + row * a.ldc + col;
+                    if (c_vec_ok && col + 3 < a.N) {
+                        f32x4 cin = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if (beta != 0.0f) cin = OV::load4(p);
+                        f32x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = epilogue_value(s[e], alpha, beta, cin[e], bias4[e], act);
+                        OV::store4(p, o);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < a.N) {
+                                const float cin = (beta != 0.0f) ? OV::load1(p + e) : 0.0f;
+                                OV::store1(p + e, epilogue_value(s[e], alpha, beta, cin, bias4[e], act));
+                            }
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    };
+    if (a.out_dtype == DT_F32) run_epilogue(std::integral_constant<int, DT_F32>{});
+    else if (a.out_dtype == DT_BF16) run_epilogue(std::integral_constant<int, DT_BF16>{});
+    else run_epilogue(std::integral_constant<int, DT_F16>{});
+}
+
 template <class C, bool IS_BF16, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(C::NT) void tile_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok) {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NT, TM = C::TM, TN = C::TN, CPR = C::CPR;
@@ -403,63 +472,7 @@ __global__ __launch_bounds__(C::NT) void tile_kernel(Args a, int tiles_m, int ti
         __syncthreads();                 // every wave is done with the operand stages: LDS is reused below
     }
 
-    // ---- epilogue.  In a 32x32 accumulator lane (l32, lhi) owns column l32 and rows
-    // 8*(v/4) + 4*lhi + v%4.  Band by band the wave transposes that through its private LDS
-    // region so that each lane ends up with four consecutive columns of one row, and C is read
-    // and written with full-width vector accesses.
-    char* region = lds + wave * EL::REGION;
-    const float alpha = a.alpha, beta = a.beta;
-    const int act = a.act;
-    const int cl = (lane % EL::LPR) * 4;                 // first of this lane's four columns inside the wave sub-block
-    const int64_t col = n0 + wn * C::WTN + cl;
-    f32x4 bias4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (a.bias) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (col + e < a.N) bias4[e] = load_elem(a.bias, a.bias_dtype, col + e);
-    }
-
-    auto run_epilogue = [&](auto tag) {
-        using OV = OutVec<decltype(tag)::value>;
-        typename OV::elem* Cp = (typename OV::elem*)a.C;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    *(float*)(region + ((8 * (v >> 2) + 4 * lhi + (v & 3)) * EL::RS + j * 32 + l32) * 4) = acc[i][j][v];
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll 2
-            for (int it = 0; it < 32 / EL::RPI; ++it) {
-                const int rl = it * EL::RPI + lane / EL::LPR;
-                const f32x4 s = *(const f32x4*)(region + (rl * EL::RS + cl) * 4);
-                const int64_t row = m0 + wm * C::WTM + i * 32 + rl;
-                if (row < a.M && col < a.N) {
-                    typename OV::elem* p = Cp + row * a.ldc + col;
-                    if (c_vec_ok && col + 3 < a.N) {
-                        f32x4 cin = {0.0f, 0.0f, 0.0f, 0.0f};
-                        if (beta != 0.0f) cin = OV::load4(p);
-                        f32x4 o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = epilogue_value(s[e], alpha, beta, cin[e], bias4[e], act);
-                        OV::store4(p, o);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < a.N) {
-                                const float cin = (beta != 0.0f) ? OV::load1(p + e) : 0.0f;
-                                OV::store1(p + e, epilogue_value(s[e], alpha, beta, cin, bias4[e], act));
-                            }
-                    }
-                }
-            }
-            __builtin_amdgcn_wave_barrier();
-        }
-    };
-    if (a.out_dtype == DT_F32) run_epilogue(std::integral_constant<int, DT_F32>{});
-    else if (a.out_dtype == DT_BF16) run_epilogue(std::integral_constant<int, DT_BF16>{});
-    else run_epilogue(std::integral_constant<int, DT_F16>{});
+    tile_epilogue<C>(acc, lds, a, m0, n0, c_vec_ok);
 }
 
 // One translation unit per variant instantiates this with its Cfg.
