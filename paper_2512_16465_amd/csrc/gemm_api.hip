@@ -122,7 +122,7 @@ GEMM_EXPORT const char* gemm_variant_name(gemm_kernel_t kernel, int32_t variant)
         return info ? info->name : nullptr;
     }
     if (kernel == GEMM_KERNEL_GENERAL) return variant == 0 ? "general_16x16" : nullptr;
-    if (kernel == GEMM_KERNEL_SKINNY) return variant == 0 ? "skinny_nn_32x256_w8" : nullptr;
+    if (kernel == GEMM_KERNEL_SKINNY) return variant == 0 ? "skinny_nn_32x256_w4" : nullptr;
     return nullptr;
 }
 

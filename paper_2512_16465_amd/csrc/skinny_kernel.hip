@@ -19,7 +19,8 @@ namespace gemm {
 namespace {
 
 constexpr int SK_COLS = 256;     // columns per workgroup
-constexpr int SK_WAVES = 8;      // waves per workgroup, each a slice of the workgroup's k range
+constexpr int SK_WAVES = 4;      // waves per workgroup (one per SIMD), each a slice of the workgroup's k range
+constexpr int SK_DEPTH = 3;      // steps of 16 k-rows in flight per wave (8 KiB each)
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t sk_rsrc(const void* base, int64_t bytes) {
     const int64_t cap = 0xffffffffll;
@@ -78,8 +79,8 @@ __device__ __forceinline__ void sk_store_row(const Args& a, int64_t row, int64_t
 
 template <bool IS_BF16>
 __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int split_k, float* ws, int c_vec_ok) {
-    // partial accumulators of the upper half of the waves, [wave][register][lane]
-    __shared__ float red[(SK_WAVES / 2) * 128 * 64];
+    // partial accumulators of the upper half of the waves, [wave][register quad][lane]
+    __shared__ f32x4 red[(SK_WAVES / 2) * 32 * 64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
@@ -125,44 +126,56 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int sp
             off += ldb_b;
         }
     };
-    auto process = [&](const SkStage& st) {
+    // One step: transpose the stage's 8x8 blocks, then at once refill the stage with the step two
+    // ahead (so that the loads are not held up behind the MFMAs, which issue slowly while the
+    // other wave of the SIMD owns the matrix pipe), then the eight MFMAs.
+    auto process = [&](SkStage& st, int refill_step, bool refill) {
+        u32x4 o[8];
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
-            u32x4 o;
             const uint32_t sel = (n & 1) ? 0x07060302u : 0x05040100u;
 #pragma unroll
             for (int kp = 0; kp < 4; ++kp)
-                o[kp] = __builtin_amdgcn_perm(st.b[2 * kp + 1][n >> 1], st.b[2 * kp][n >> 1], sel);
-            acc[n] = sk_mfma<IS_BF16>(st.a, o, acc[n]);
+                o[n][kp] = __builtin_amdgcn_perm(st.b[2 * kp + 1][n >> 1], st.b[2 * kp][n >> 1], sel);
         }
+        const u32x4 a_cur = st.a;
+        if (refill) load(st, refill_step);
+#pragma unroll
+        for (int n = 0; n < 8; ++n) acc[n] = sk_mfma<IS_BF16>(a_cur, o[n], acc[n]);
     };
 
-    SkStage s0, s1;
-    if (my_beg < my_end) load(s0, my_beg);
-    for (int s = my_beg; s < my_end; s += 2) {
-        if (s + 1 < my_end) load(s1, s + 1);
-        process(s0);
-        if (s + 2 < my_end) load(s0, s + 2);
-        if (s + 1 < my_end) process(s1);
+    SkStage st[SK_DEPTH];
+#pragma unroll
+    for (int d = 0; d < SK_DEPTH; ++d)
+        if (my_beg + d < my_end) load(st[d], my_beg + d);
+    for (int s = my_beg; s < my_end; s += SK_DEPTH) {
+#pragma unroll
+        for (int d = 0; d < SK_DEPTH; ++d)
+            if (s + d < my_end) process(st[d], s + d + SK_DEPTH, s + d + SK_DEPTH < my_end);
     }
 
     // fold the waves' partial sums pairwise through LDS: (0..3)+=(4..7), (0,1)+=(2,3), 0+=1
 #pragma unroll
     for (int half = SK_WAVES / 2; half >= 1; half >>= 1) {
         if (wave >= half && wave < 2 * half) {
-            float* dst = red + (wave - half) * 128 * 64 + lane;
+            f32x4* dst = red + (wave - half) * 32 * 64 + lane;
 #pragma unroll
             for (int j = 0; j < 8; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) dst[(j * 16 + v) * 64] = acc[j][v];
+                for (int c = 0; c < 4; ++c)
+                    dst[(j * 4 + c) * 64] = f32x4{acc[j][4 * c], acc[j][4 * c + 1], acc[j][4 * c + 2], acc[j][4 * c + 3]};
         }
         __syncthreads();
         if (wave < half) {
-            const float* src = red + wave * 128 * 64 + lane;
+            const f32x4* src = red + wave * 32 * 64 + lane;
 #pragma unroll
             for (int j = 0; j < 8; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[j][v] += src[(j * 16 + v) * 64];
+                for (int c = 0; c < 4; ++c) {
+                    const f32x4 t = src[(j * 4 + c) * 64];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[j][4 * c + e] += t[e];
+                }
         }
         __syncthreads();
     }
@@ -222,7 +235,7 @@ int skinny_default_split(const Args& a, int num_cus) {
     const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS;
     const int64_t steps = (a.K + 15) / 16;
     int64_t s = (num_cus + groups - 1) / groups;          // about one workgroup per compute unit
-    const int64_t max_s = steps / (SK_WAVES * 4);         // keep at least 4 steps per wave
+    const int64_t max_s = steps / (SK_WAVES * 2 * SK_DEPTH);   // keep the pipeline of every wave filled a few times over
     if (s > max_s) s = max_s;
     if (s > 64) s = 64;
     if (s < 1) s = 1;
