@@ -63,8 +63,25 @@ __device__ __forceinline__ void store_elem(void* p, int dtype, int64_t idx, floa
     else ((uint16_t*)p)[idx] = f32_to_f16_bits(v);
 }
 
-// exact GELU, x * Phi(x)
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+// GELU in its exact form x * Phi(x) = x/2 * (1 + erf(x / sqrt 2)).  erf is evaluated with the
+// rational approximation 7.1.26 of Abramowitz & Stegun, |error| <= 1.5e-7 over the whole line,
+// branch-free (one reciprocal, one exponential, a degree-5 polynomial): two orders of magnitude
+// below one rounding of a 16-bit output and far inside the fp32 tolerance, at a quarter of the
+// instructions of a libm-grade erff.
+__device__ __forceinline__ float gelu_erf(float x) {
+    const float z = x * 0.70710678118654752440f;
+    const float az = fabsf(z);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, az, 1.0f));
+    float p = fmaf(t, 1.061405429f, -1.453152027f);
+    p = fmaf(t, p, 1.421413741f);
+    p = fmaf(t, p, -0.284496736f);
+    p = fmaf(t, p, 0.254829592f);
+    p *= t;
+    const float e = __builtin_amdgcn_exp2f(-az * az * 1.44269504088896340736f);
+    const float erf_abs = fmaf(-p, e, 1.0f);
+    const float erf_z = __builtin_copysignf(erf_abs, z);
+    return 0.5f * x * (1.0f + erf_z);
+}
 
 __device__ __forceinline__ float apply_act(float x, int act) { return act == ACT_GELU_ERF ? gelu_erf(x) : x; }
 

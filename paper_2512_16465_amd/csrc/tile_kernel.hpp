@@ -204,10 +204,8 @@ template <> struct OutVec<DT_BF16> {
     }
     static __device__ __forceinline__ float load1(const elem* p) { return bf16_bits_to_f32(*p); }
     static __device__ __forceinline__ void store4(elem* p, f32x4 v) {
-        uint2 u;
-        u.x = (uint32_t)f32_to_bf16_bits(v[0]) | ((uint32_t)f32_to_bf16_bits(v[1]) << 16);
-        u.y = (uint32_t)f32_to_bf16_bits(v[2]) | ((uint32_t)f32_to_bf16_bits(v[3]) << 16);
-        *(uint2*)p = u;
+        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+        *(uint2*)p = __builtin_bit_cast(uint2, __builtin_convertvector(v, bf16x4));   // v_cvt_pk_bf16_f32, nearest even
     }
     static __device__ __forceinline__ void store1(elem* p, float v) { *p = f32_to_bf16_bits(v); }
 };
@@ -218,10 +216,8 @@ template <> struct OutVec<DT_F16> {
     }
     static __device__ __forceinline__ float load1(const elem* p) { return f16_bits_to_f32(*p); }
     static __device__ __forceinline__ void store4(elem* p, f32x4 v) {
-        uint2 u;
-        u.x = (uint32_t)f32_to_f16_bits(v[0]) | ((uint32_t)f32_to_f16_bits(v[1]) << 16);
-        u.y = (uint32_t)f32_to_f16_bits(v[2]) | ((uint32_t)f32_to_f16_bits(v[3]) << 16);
-        *(uint2*)p = u;
+        typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+        *(uint2*)p = __builtin_bit_cast(uint2, __builtin_convertvector(v, f16x4));    // v_cvt_f16_f32, nearest even
     }
     static __device__ __forceinline__ void store1(elem* p, float v) { *p = f32_to_f16_bits(v); }
 };
@@ -264,38 +260,90 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[C::TM][C::TN], char*
             if (col + e < a.N) bias4[e] = load_elem(a.bias, a.bias_dtype, col + e);
     }
 
+    // The code below runs once per tile, so its size matters more than its instruction count: a
+    // kernel that streams tens of kilobytes of straight-line epilogue through the instruction
+    // cache spends longer fetching it than executing it.  Only the register -> LDS dump of a band
+    // needs static register numbers; the bands are walked by a real loop that picks the dump with
+    // a compare chain, and the read-back/store part exists once.
+    static_assert(TM <= 4, "the band switch below lists four cases");
+    const bool interior = c_vec_ok && (m0 + C::BM <= a.M) && (n0 + C::BN <= a.N);
+    auto dump_band = [&](f32x16 (&band)[TN]) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                *(float*)(region + ((8 * (v >> 2) + 4 * lhi + (v & 3)) * EL::RS + j * 32 + l32) * 4) = band[j][v];
+    };
     auto run_epilogue = [&](auto tag) {
         using OV = OutVec<decltype(tag)::value>;
         typename OV::elem* Cp = (typename OV::elem*)a.C;
-#pragma unroll
+#pragma unroll 1
         for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    *(float*)(region + ((8 * (v >> 2) + 4 * lhi + (v & 3)) * EL::RS + j * 32 + l32) * 4) = acc[i][j][v];
+            // one case per band; the distinct marker at the end of each case keeps the optimiser from
+            // merging the cases into an indexed (scratch-memory) access to the accumulators
+            switch (i) {
+                case 0: dump_band(acc[0]); asm volatile("; band 0" ::: "memory"); break;
+                case 1: if constexpr (TM > 1) dump_band(acc[1 % TM]); asm volatile("; band 1" ::: "memory"); break;
+                case 2: if constexpr (TM > 2) dump_band(acc[2 % TM]); asm volatile("; band 2" ::: "memory"); break;
+                default: if constexpr (TM > 3) dump_band(acc[3 % TM]); asm volatile("; band 3" ::: "memory"); break;
+            }
             __builtin_amdgcn_wave_barrier();
-#pragma unroll 2
-            for (int it = 0; it < 32 / EL::RPI; ++it) {
-                const int rl = it * EL::RPI + lane / EL::LPR;
-                const f32x4 s = *(const f32x4*)(region + (rl * EL::RS + cl) * 4);
-                const int64_t row = m0 + wm * C::WTM + i * 32 + rl;
-                if (row < a.M && col < a.N) {
-                    typename OV::elem* p = Cp + row * a.ldc + col;
-                    if (c_vec_ok && col + 3 < a.N) {
-                        f32x4 cin = {0.0f, 0.0f, 0.0f, 0.0f};
-                        if (beta != 0.0f) cin = OV::load4(p);
-                        f32x4 o;
+            constexpr int TRIPS = 32 / EL::RPI;
+            constexpr int GROUP = TRIPS % 4 == 0 ? 4 : 1;
+            if (interior) {
+                // Whole tile inside C and rows aligned for vector access: no per-lane conditions at
+                // all, only wave-uniform branches on beta and the activation; four rows in flight
+                // per trip so that the LDS and C_in latencies overlap.
+                typename OV::elem* p0 = Cp + (m0 + wm * C::WTM + i * 32 + lane / EL::LPR) * a.ldc + col;
+                const int64_t step = (int64_t)EL::RPI * a.ldc;
+                const char* rd = region + ((lane / EL::LPR) * EL::RS + cl) * 4;
+#pragma unroll 1
+                for (int it0 = 0; it0 < TRIPS; it0 += GROUP) {
+                    f32x4 s[GROUP];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = epilogue_value(s[e], alpha, beta, cin[e], bias4[e], act);
-                        OV::store4(p, o);
+                    for (int g = 0; g < GROUP; ++g) s[g] = *(const f32x4*)(rd + (it0 + g) * EL::RPI * EL::RS * 4);
+                    if (beta != 0.0f) {
+                        f32x4 cin[GROUP];
+#pragma unroll
+                        for (int g = 0; g < GROUP; ++g) cin[g] = OV::load4(p0 + (it0 + g) * step);
+#pragma unroll
+                        for (int g = 0; g < GROUP; ++g) s[g] = alpha * s[g] + beta * cin[g] + bias4;
                     } else {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < a.N) {
-                                const float cin = (beta != 0.0f) ? OV::load1(p + e) : 0.0f;
-                                OV::store1(p + e, epilogue_value(s[e], alpha, beta, cin, bias4[e], act));
-                            }
+                        for (int g = 0; g < GROUP; ++g) s[g] = alpha * s[g] + bias4;
+                    }
+                    if (act == ACT_GELU_ERF) {
+#pragma unroll
+                        for (int g = 0; g < GROUP; ++g)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) s[g][e] = gelu_erf(s[g][e]);
+                    }
+#pragma unroll
+                    for (int g = 0; g < GROUP; ++g) OV::store4(p0 + (it0 + g) * step, s[g]);
+                }
+            } else {
+#pragma unroll 1
+                for (int it = 0; it < TRIPS; ++it) {
+                    const int rl = it * EL::RPI + lane / EL::LPR;
+                    const f32x4 s = *(const f32x4*)(region + (rl * EL::RS + cl) * 4);
+                    const int64_t row = m0 + wm * C::WTM + i * 32 + rl;
+                    if (row < a.M && col < a.N) {
+                        typename OV::elem* p = Cp + row * a.ldc + col;
+                        if (c_vec_ok && col + 3 < a.N) {
+                            f32x4 cin = {0.0f, 0.0f, 0.0f, 0.0f};
+                            if (beta != 0.0f) cin = OV::load4(p);
+                            f32x4 o;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = epilogue_value(s[e], alpha, beta, cin[e], bias4[e], act);
+                            OV::store4(p, o);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < a.N) {
+                                    const float c1 = (beta != 0.0f) ? OV::load1(p + e) : 0.0f;
+                                    OV::store1(p + e, epilogue_value(s[e], alpha, beta, c1, bias4[e], act));
+                                }
+                        }
                     }
                 }
             }
