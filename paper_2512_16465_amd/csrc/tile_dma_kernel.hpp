@@ -252,7 +252,9 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
             slot(m, 0);
-            acc[m / TN][m % TN] = mfma32<IS_BF16>(ua[m / TN], ub[m % TN], acc[m / TN][m % TN]);
+            // boustrophedon order over the wave's accumulators: consecutive MFMAs share one operand
+            const int i = m / TN, j = (i & 1) ? TN - 1 - m % TN : m % TN;
+            acc[i][j] = mfma32<IS_BF16>(ua[i], ub[j], acc[i][j]);
             slot(m, 1);
         }
     };
