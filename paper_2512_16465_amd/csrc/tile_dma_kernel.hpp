@@ -180,7 +180,7 @@ __device__ __forceinline__ void wait_raw(Raw (&r)[4]) {
 __device__ __forceinline__ void wait_raw(u32x4 (&)[2]) {}
 __device__ __forceinline__ void wait_raw(u32x4 (&)[4]) {}
 
-template <class C, bool IS_BF16, bool A_KC, bool B_KC>
+template <class C, bool IS_BF16, bool A_KC, bool B_KC, bool PLAIN>
 __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok) {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NT, TM = C::TM, TN = C::TN, NS = C::NS;
     using EL = EpiLayout<C>;
@@ -355,7 +355,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS is reused by the epilogue
 #undef GEMM_WAIT_VM_BARRIER
 
-    tile_epilogue<C>(acc, lds, a, m0, n0, c_vec_ok);
+    if constexpr (PLAIN) tile_epilogue_plain<C>(acc, a, m0, n0);
+    else tile_epilogue<C>(acc, lds, a, m0, n0, c_vec_ok);
 }
 
 template <class C>
@@ -365,9 +366,16 @@ hipError_t launch_dma_variant(const Args& a, int group_m, hipStream_t stream) {
     const bool bf = a.dtype == DT_BF16;
     const bool akc = !a.transA, bkc = a.transB != 0;
     const int c_vec_ok = (a.ldc % 4 == 0) && ((uintptr_t)a.C % (a.out_dtype == DT_F32 ? 16 : 8) == 0);
-#define GEMM_TILE_LAUNCH(BF, AKC, BKC)                                                                           \
-    hipLaunchKernelGGL((tile_dma_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, \
-                       c_vec_ok)
+    const bool plain = plain_epilogue_applies<C>(a);
+#define GEMM_TILE_LAUNCH(BF, AKC, BKC)                                                                         \
+    do {                                                                                                       \
+        if (plain)                                                                                             \
+            hipLaunchKernelGGL((tile_dma_kernel<C, BF, AKC, BKC, true>), grid, block, 0, stream, a, tiles_m,   \
+                               tiles_n, group_m, c_vec_ok);                                                    \
+        else                                                                                                   \
+            hipLaunchKernelGGL((tile_dma_kernel<C, BF, AKC, BKC, false>), grid, block, 0, stream, a, tiles_m,  \
+                               tiles_n, group_m, c_vec_ok);                                                    \
+    } while (0)
     if (bf) {
         if (akc && bkc) GEMM_TILE_LAUNCH(true, true, true);
         else if (akc && !bkc) GEMM_TILE_LAUNCH(true, true, false);

@@ -207,7 +207,7 @@ template <> struct OutVec<DT_BF16> {
         typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
         *(uint2*)p = __builtin_bit_cast(uint2, __builtin_convertvector(v, bf16x4));   // v_cvt_pk_bf16_f32, nearest even
     }
-    static __device__ __forceinline__ void store1(elem* p, float v) { *p = f32_to_bf16_bits(v); }
+    static __device__ __forceinline__ void store1(elem* p, float v) { *p = __builtin_bit_cast(uint16_t, (__bf16)v); }
 };
 template <> struct OutVec<DT_F16> {
     typedef uint16_t elem;
@@ -353,6 +353,45 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[C::TM][C::TN], char*
     if (a.out_dtype == DT_F32) run_epilogue(std::integral_constant<int, DT_F32>{});
     else if (a.out_dtype == DT_BF16) run_epilogue(std::integral_constant<int, DT_BF16>{});
     else run_epilogue(std::integral_constant<int, DT_F16>{});
+}
+
+// The plainest epilogue, C = alpha*A*B on a problem made of whole tiles (beta == 0, no bias, no
+// activation): no LDS, every accumulator register is scaled, rounded and stored straight from
+// the MFMA layout.  A store instruction covers two rows x 32 columns (128-byte segments in
+// fp32); the row base is wave-uniform, the lane part is one 32-bit offset.  It lives in kernel
+// instances of its own: a kernel that contains both epilogues copies all 256 accumulators into
+// vector registers ahead of the branch between them, and spills.
+template <class C>
+__device__ __forceinline__ void tile_epilogue_plain(f32x16 (&acc)[C::TM][C::TN], const Args& a, int64_t m0, int64_t n0) {
+    constexpr int TM = C::TM, TN = C::TN;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const int wm = wave % C::WM, wn = wave / C::WM;
+    const float alpha = a.alpha;
+    auto run_direct = [&](auto tag) {
+        using OV = OutVec<decltype(tag)::value>;
+        typename OV::elem* base = (typename OV::elem*)a.C + (m0 + wm * C::WTM) * a.ldc + n0 + wn * C::WTN;
+        const uint32_t lane_off = (uint32_t)(4 * lhi * a.ldc + l32);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                typename OV::elem* rowp = base + (int64_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * a.ldc;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) OV::store1(rowp + lane_off + j * 32, alpha * acc[i][j][v]);
+            }
+    };
+    if (a.out_dtype == DT_F32) run_direct(std::integral_constant<int, DT_F32>{});
+    else if (a.out_dtype == DT_BF16) run_direct(std::integral_constant<int, DT_BF16>{});
+    else run_direct(std::integral_constant<int, DT_F16>{});
+}
+
+// true if the call can use the kernels built around tile_epilogue_plain
+template <class C>
+inline bool plain_epilogue_applies(const Args& a) {
+    return a.beta == 0.0f && a.bias == nullptr && a.act == ACT_NONE && a.M % C::BM == 0 && a.N % C::BN == 0 &&
+           a.ldc < (1 << 26);
 }
 
 template <class C, bool IS_BF16, bool A_KC, bool B_KC>
