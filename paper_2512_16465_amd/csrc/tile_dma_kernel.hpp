@@ -31,20 +31,22 @@ namespace tile {
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_>
 struct DmaCfg : Cfg<BM_, BN_, BK_, WM_, WN_> {
     static constexpr int NS = NS_;     // LDS stages in the ring
-    static_assert(NS_ >= 3, "the pipeline keeps two slabs in flight behind the one being multiplied");
+    static_assert(NS_ >= 2, "one stage is multiplied while the others are filled");
 };
 
 #define GEMM_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-// One direct-to-LDS load: lane l fetches 16 bytes at byte offset `off` of the buffer and the
-// wave's 64 chunks land at LDS address `dst` + 16*l.  Only the device pass of the compiler sees
-// the builtin: the host pass does not accept it inside templates and would silently drop the
-// launch stub of every kernel that reaches it.
-__device__ __forceinline__ void load_to_lds_b128(__amdgpu_buffer_rsrc_t rsrc, char* dst, uint32_t off) {
+// One direct-to-LDS load: lane l fetches 16 bytes at byte offset `off` + `soff` of the buffer and
+// the wave's 64 chunks land at LDS address `dst` + 16*l.  `soff` is wave-uniform and is NOT part
+// of the descriptor's range check (only `off` is): callers add it only where every lane whose
+// `off` is in range stays inside the operand.  Only the device pass of the compiler sees the
+// builtin: the host pass does not accept it inside templates and would silently drop the launch
+// stub of every kernel that reaches it.
+__device__ __forceinline__ void load_to_lds_b128(__amdgpu_buffer_rsrc_t rsrc, char* dst, uint32_t off, uint32_t soff) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, GEMM_LDS_PTR(dst), 16, off, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, GEMM_LDS_PTR(dst), 16, off, soff, 0, 0);
 #else
-    (void)rsrc; (void)dst; (void)off;
+    (void)rsrc; (void)dst; (void)off; (void)soff;
 #endif
 }
 
@@ -79,10 +81,10 @@ struct DmaKC {
         return (int)((((line << 3) | pos) % CPR) * 8);
     }
     __device__ __forceinline__ void issue(bool MASKED, int i, __amdgpu_buffer_rsrc_t rsrc, char* stage, int wave, int tid, int k0,
-                                          int K) const {
+                                          int K, uint32_t soff = 0) const {
         uint32_t off = voff[i];
         if (MASKED && k0 + chunk_k(i, tid) >= K) off = 0x7ffffff0u;       // past the end of any supported operand: the slot is filled with zeros
-        load_to_lds_b128(rsrc, stage + (i * NT + wave * 64) * 16, off);
+        load_to_lds_b128(rsrc, stage + (i * NT + wave * 64) * 16, off, soff);
     }
     static __device__ __forceinline__ const char* tile_base(const void* p, int64_t first_row, int64_t ld) {
         return (const char*)p + first_row * ld * 2;
@@ -120,9 +122,10 @@ struct DmaMC {
         }
     }
     __device__ __forceinline__ void issue(bool /*masked*/, int i, __amdgpu_buffer_rsrc_t rsrc, char* stage, int wave, int /*tid*/,
-                                          int /*k0*/, int /*K*/) const {
-        // k-rows past K lie past the end of the operand and read as zero by themselves
-        load_to_lds_b128(rsrc, stage + (i * NT + wave * 64) * 16, voff[i]);
+                                          int /*k0*/, int /*K*/, uint32_t soff = 0) const {
+        // k-rows past K lie past the end of the operand and read as zero by themselves (as long
+        // as the descriptor starts at the slab, i.e. soff == 0)
+        load_to_lds_b128(rsrc, stage + (i * NT + wave * 64) * 16, voff[i], soff);
     }
     static __device__ __forceinline__ const char* tile_base(const void* p, int64_t first_row, int64_t /*ld*/) {
         return (const char*)p + first_row * 2;
@@ -258,10 +261,11 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
             slot(m, 1);
         }
     };
-    auto issue_one = [&](int q, __amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, char* stage, int k0, auto masked) {
+    auto issue_one = [&](int q, __amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, char* stage, int k0, auto masked,
+                         uint32_t soff_a = 0, uint32_t soff_b = 0) {
         constexpr bool M = decltype(masked)::value;
-        if (q < LA::L) la.issue(M, q, ra, stage, wave, tid, k0, K);
-        else lb.issue(M, q - LA::L, rb, stage + C::A_BYTES, wave, tid, k0, K);
+        if (q < LA::L) la.issue(M, q, ra, stage, wave, tid, k0, K, soff_a);
+        else lb.issue(M, q - LA::L, rb, stage + C::A_BYTES, wave, tid, k0, K, soff_b);
     };
     auto issue_tile = [&](int t, auto masked) {
         const __amdgpu_buffer_rsrc_t ra = make_rsrc(pa + t * a_step, a_bytes - t * a_step);
@@ -278,14 +282,22 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory")
 
     constexpr int BAR_SLOT = NM / 4;              // MFMAs of the last k-sub-step issued before the barrier
-    constexpr int LOAD_SLOTS = (NKS - 1) * NM + BAR_SLOT;   // all loads of a slab are issued before its step's barrier
+    // All loads of a slab are issued before its step's barrier.  With a single slab of lookahead the
+    // barrier of the same step waits for them, so they go out first, one per MFMA.
+    constexpr int BEFORE_BAR = (NKS - 1) * NM + BAR_SLOT;
+    constexpr int LOAD_SLOTS = (D == 1 && LPT < BEFORE_BAR) ? LPT : BEFORE_BAR;
 
-    // steady state: slabs kt+1 .. kt+D exist and need no mask
+    // Steady state: slabs kt+1 .. kt+D exist and need no mask.  The descriptors stay at the tile's
+    // first slab and the k advance travels as the loads' scalar offset (one scalar add per operand
+    // and step): a wave has room for only a handful of instructions next to each MFMA, and
+    // rebuilding two descriptors costs two dozen.  The scalar offset escapes the range check, which
+    // is safe here because every lane whose own offset is in range addresses a row of the operand,
+    // and slab t lies wholly inside K.
+    const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(pa, a_bytes), rb0 = make_rsrc(pb, b_bytes);
     auto step_hot = [&](int kt) {
         const int stage = kt % NS, next = (kt + 1) % NS;
         const int t = kt + D;
-        const __amdgpu_buffer_rsrc_t ra = make_rsrc(pa + t * a_step, a_bytes - t * a_step);
-        const __amdgpu_buffer_rsrc_t rb = make_rsrc(pb + t * b_step, b_bytes - t * b_step);
+        const uint32_t soff_a = (uint32_t)(t * a_step), soff_b = (uint32_t)(t * b_step);
         char* dst = lds + (t % NS) * C::STAGE;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
@@ -311,7 +323,7 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
                 if (slot < LOAD_SLOTS) {
 #pragma unroll
                     for (int q = (slot * LPT) / LOAD_SLOTS; q < ((slot + 1) * LPT) / LOAD_SLOTS; ++q)
-                        issue_one(q, ra, rb, dst, t * BK, std::false_type{});
+                        issue_one(q, ra0, rb0, dst, t * BK, std::false_type{}, soff_a, soff_b);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             });

@@ -87,6 +87,25 @@ def test_tile_variants_integer_exact(handle, ta, tb):
     lg.gemm_set_plan(handle)
 
 
+@pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0)])
+def test_tile_variants_every_small_slab_count(handle, ta, tb):
+    # 1 .. 13 k slabs of 32 (and the matching counts of 64), with and without a partial last slab:
+    # every entry into and exit from the software pipelines, whatever their depth
+    M, N = 72, 136
+    for K in (16, 32, 40, 64, 96, 104, 128, 160, 168, 192, 224, 256, 264, 288, 320, 352, 384, 416):
+        cfg = base_cfg(M, N, K, ta, tb, wl.BF16, wl.F32, alpha=1.0, beta=0.0)
+        inp, _ = wl.make_integer_inputs(cfg, 100 + K, -2, 2)
+        want = oracle.decode(wl.F32, expected_bits_exact(cfg, inp))
+        for v in range(num_tile_variants()):
+            print(f"slab-count sweep K={K} variant {v} ta={ta} tb={tb}", flush=True)
+            lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
+            p = DeviceProblem(cfg, inp)
+            p.run(handle)
+            got = decode_c(cfg, p.result_bits())
+            assert np.array_equal(got, want), f"K={K} variant {v}: {np.sum(got != want)} wrong elements"
+    lg.gemm_set_plan(handle)
+
+
 def test_tile_epilogue_bias_gelu_beta(handle):
     M, N, K = 300, 392, 256
     cfg = base_cfg(M, N, K, 0, 1, wl.BF16, wl.BF16, alpha=0.5, beta=1.5, a_dist=("normal", 1.0),
