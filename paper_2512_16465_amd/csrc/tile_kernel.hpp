@@ -239,14 +239,16 @@ struct EpiLayout {
 // private LDS region so that a lane ends up with four consecutive columns of one row, and C is
 // read and written with full-width vector accesses.  Every wave of the workgroup must be done
 // with the operand stages in LDS before this is called.
-template <class C>
-__device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[C::TM][C::TN], char* lds, const Args& a,
-                                              int64_t m0, int64_t n0, int c_vec_ok) {
-    constexpr int TM = C::TM, TN = C::TN;
+//
+// `dump(band, region)` writes rows 32*band .. 32*band+31 of the wave's sub-block, as held in
+// that wave's accumulators, to region[(row * EL::RS + column) * 4]; `band` is an
+// std::integral_constant, so the accumulator registers it names are static.
+template <class C, class Dump>
+__device__ __forceinline__ void tile_epilogue_bands(Dump dump, char* lds, const Args& a, int64_t m0, int64_t n0, int c_vec_ok) {
+    constexpr int TM = C::TM;
     using EL = EpiLayout<C>;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, lhi = lane >> 5;
     const int wm = wave % C::WM, wn = wave / C::WM;
     char* region = lds + wave * EL::REGION;
     const float alpha = a.alpha, beta = a.beta;
@@ -267,13 +269,6 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[C::TM][C::TN], char*
     // a compare chain, and the read-back/store part exists once.
     static_assert(TM <= 4, "the band switch below lists four cases");
     const bool interior = c_vec_ok && (m0 + C::BM <= a.M) && (n0 + C::BN <= a.N);
-    auto dump_band = [&](f32x16 (&band)[TN]) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-                *(float*)(region + ((8 * (v >> 2) + 4 * lhi + (v & 3)) * EL::RS + j * 32 + l32) * 4) = band[j][v];
-    };
     auto run_epilogue = [&](auto tag) {
         using OV = OutVec<decltype(tag)::value>;
         typename OV::elem* Cp = (typename OV::elem*)a.C;
@@ -282,10 +277,10 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[C::TM][C::TN], char*
             // one case per band; the distinct marker at the end of each case keeps the optimiser from
             // merging the cases into an indexed (scratch-memory) access to the accumulators
             switch (i) {
-                case 0: dump_band(acc[0]); asm volatile("; band 0" ::: "memory"); break;
-                case 1: if constexpr (TM > 1) dump_band(acc[1 % TM]); asm volatile("; band 1" ::: "memory"); break;
-                case 2: if constexpr (TM > 2) dump_band(acc[2 % TM]); asm volatile("; band 2" ::: "memory"); break;
-                default: if constexpr (TM > 3) dump_band(acc[3 % TM]); asm volatile("; band 3" ::: "memory"); break;
+                case 0: dump(std::integral_constant<int, 0>{}, region); asm volatile("; band 0" ::: "memory"); break;
+                case 1: if constexpr (TM > 1) dump(std::integral_constant<int, 1 % TM>{}, region); asm volatile("; band 1" ::: "memory"); break;
+                case 2: if constexpr (TM > 2) dump(std::integral_constant<int, 2 % TM>{}, region); asm volatile("; band 2" ::: "memory"); break;
+                default: if constexpr (TM > 3) dump(std::integral_constant<int, 3 % TM>{}, region); asm volatile("; band 3" ::: "memory"); break;
             }
             __builtin_amdgcn_wave_barrier();
             constexpr int TRIPS = 32 / EL::RPI;
@@ -353,6 +348,25 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[C::TM][C::TN], char*
     if (a.out_dtype == DT_F32) run_epilogue(std::integral_constant<int, DT_F32>{});
     else if (a.out_dtype == DT_BF16) run_epilogue(std::integral_constant<int, DT_BF16>{});
     else run_epilogue(std::integral_constant<int, DT_F16>{});
+}
+
+// The staged epilogue for accumulators of the 32x32x16 MFMA.
+template <class C>
+__device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[C::TM][C::TN], char* lds, const Args& a,
+                                              int64_t m0, int64_t n0, int c_vec_ok) {
+    using EL = EpiLayout<C>;
+    const int lane = threadIdx.x & 63;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    tile_epilogue_bands<C>(
+        [&](auto band, char* region) {
+            constexpr int b = decltype(band)::value;
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    *(float*)(region + ((8 * (v >> 2) + 4 * lhi + (v & 3)) * EL::RS + j * 32 + l32) * 4) = acc[b][j][v];
+        },
+        lds, a, m0, n0, c_vec_ok);
 }
 
 // The plainest epilogue, C = alpha*A*B on a problem made of whole tiles (beta == 0, no bias, no
