@@ -22,13 +22,15 @@ using gemm::Args;
 
 bool valid_dtype(int d) { return d == GEMM_F32 || d == GEMM_F16 || d == GEMM_BF16; }
 
-// Picks a tile variant for the macro-tile family: the large direct-to-LDS tile when it still
-// yields enough workgroups to occupy the compute units (its register-staged sibling when an
-// operand is too large for the direct loads' masking offset), the small tile otherwise.
+// Picks a tile variant for the macro-tile family: the large direct-to-LDS tile on the 16x16x32
+// MFMA when it still yields enough workgroups to occupy the compute units (its register-staged
+// sibling when an operand is too large for the direct loads' masking offset), the small tile
+// otherwise.
+constexpr int kLargeTileVariant = 9, kLargeTileFallback = 0, kSmallTileVariant = 3;
 int choose_tile_variant(const Args& a, int num_cus) {
     const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (big * 2 >= num_cus) return gemm::tile_variant_supports(a, 4) ? 4 : 0;
-    return 3;
+    if (big * 2 >= num_cus) return gemm::tile_variant_supports(a, kLargeTileVariant) ? kLargeTileVariant : kLargeTileFallback;
+    return kSmallTileVariant;
 }
 
 gemm_status_t ensure_workspace(gemm_handle_s* h, size_t bytes, hipStream_t stream) {

@@ -57,7 +57,7 @@ struct Frag16MC {
         const uint32_t j = lane & 15, g = lane >> 4;
         const uint32_t k = 8 * g + (j >> 2);
         const uint32_t col = row0 + 4 * (j & 3);
-        const uint32_t cs = (col >> 3) ^ ((k & 3u) << 2);
+        const uint32_t cs = (col >> 3) ^ mc_swizzle(k);
         return (k * CPK + cs) * 16 + (col & 7) * 2;
     }
     struct Raw { uint2 lo, hi; };

@@ -15,7 +15,7 @@
 //   k-contiguous operand (A in NN/NT, B in NT): LDS rows are k-contiguous, chunk (row, c) lives
 //     in slot swz(row, c); fragments are read with ds_read_b128 as in tile_kernel.hpp.
 //   m/n-contiguous operand (B in NN, A in TN): LDS holds the slab as [k][row], 16-byte chunk c of
-//     k-row k in slot k*(ROWS/8) + (c xor ((k&3)<<2)); the MFMA operand (8 consecutive k of one
+//     k-row k in slot k*(ROWS/8) + (c xor mc_swizzle(k)); the MFMA operand (8 consecutive k of one
 //     row per lane) is read with two transposing loads ds_read_b64_tr_b16, in which lane j of a
 //     16-lane group supplies the address of row k0 + j/4, columns 4*(j%4).., and lane i receives
 //     column i of rows k0 .. k0+3.
@@ -103,6 +103,14 @@ struct DmaKC {
     static __device__ __forceinline__ u32x4 finish(const Raw& r) { return r; }
 };
 
+// Position swizzle of the [k][row] slabs: 16-byte chunk c of k-row k is stored at chunk position
+// c xor mc_swizzle(k).  A transposing read takes 32 bytes from each of four consecutive k-rows
+// per 16 lanes, and 32 lanes are served together: bits 2-3 spread the four k-rows over the 64-byte
+// blocks of a 256-byte bank line, bit 1 separates the two 16-lane groups when they read the same
+// columns of k-rows 8 apart (16x16x32 fragments).  Only bits 1-3 move, so four consecutive
+// lanes of a direct-to-LDS load still fetch one aligned 64-byte piece.
+__device__ __forceinline__ uint32_t mc_swizzle(uint32_t k) { return ((k & 3u) << 2) ^ (((k >> 3) & 1u) << 1); }
+
 // m- or n-contiguous operand: element (k, row) at base + k*ld + row; LDS keeps [k][row].
 template <int ROWS, int BK, int NT>
 struct DmaMC {
@@ -117,7 +125,7 @@ struct DmaMC {
         for (int i = 0; i < L; ++i) {
             const uint32_t S = i * NT + tid;
             const uint32_t k = S / CPK, cs = S % CPK;
-            const uint32_t c = cs ^ ((k & 3u) << 2);
+            const uint32_t c = cs ^ mc_swizzle(k);
             voff[i] = (uint32_t)((k * ld + c * 8) * 2);
         }
     }
@@ -139,7 +147,7 @@ struct DmaMC {
         const uint32_t j = l32 & 15, grp = l32 >> 4;
         const uint32_t k = 8 * lhi + (j >> 2);
         const uint32_t col = row0 + 16 * grp + 4 * (j & 3);
-        const uint32_t cs = (col >> 3) ^ ((k & 3u) << 2);
+        const uint32_t cs = (col >> 3) ^ mc_swizzle(k);
         return (k * CPK + cs) * 16 + (col & 7) * 2;
     }
     // The transposing reads are issued as assembly: the compiler would otherwise make each of
