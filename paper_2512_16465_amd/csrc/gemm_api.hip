@@ -26,7 +26,7 @@ bool valid_dtype(int d) { return d == GEMM_F32 || d == GEMM_F16 || d == GEMM_BF1
 // MFMA when it still yields enough workgroups to occupy the compute units (its register-staged
 // sibling when an operand is too large for the direct loads' masking offset), the small tile
 // otherwise.
-constexpr int kLargeTileVariant = 9, kLargeTileFallback = 0, kSmallTileVariant = 3;
+constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant = 3;
 int choose_tile_variant(const Args& a, int num_cus) {
     const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);
     if (big * 2 >= num_cus) return gemm::tile_variant_supports(a, kLargeTileVariant) ? kLargeTileVariant : kLargeTileFallback;

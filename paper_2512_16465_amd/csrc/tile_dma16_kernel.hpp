@@ -1,7 +1,7 @@
 // Direct-to-LDS macro-tile kernel built on the 16x16x32 MFMA (bf16 / fp16, gfx950).
 //
-// Same operand movers, LDS layouts, ring of stages and slot-wise schedule as tile_dma_kernel.hpp;
-// what changes is the matrix instruction.  v_mfma_f32_16x16x32 does the same work per cycle as
+// Same operand movers and LDS layouts as tile_dma_kernel.hpp; what changes is the matrix
+// instruction and, with it, the pipeline.  v_mfma_f32_16x16x32 does the same work per cycle as
 // the 32x32x16 form but sums 32 products into each accumulator per instruction instead of 16, so
 // the accumulator registers are read and written half as often per flop.  On this part the
 // matrix pipeline is power-limited on real (non-constant) data, and that difference decides the
@@ -85,12 +85,31 @@ __device__ __forceinline__ void wait_raw8(Raw (&r)[8]) {
 }
 __device__ __forceinline__ void wait_raw8(u32x4 (&)[8]) {}
 
+// Pipeline (BK = 32, one 64-MFMA sub-step per slab).  During step kt a wave multiplies the
+// fragments of slab kt, which it read from LDS during step kt-1, so LDS holds slabs kt+1 (being
+// read) .. kt+NS-1 or kt+NS, and the stage of slab kt is free as soon as every wave has passed
+// the barrier of step kt.  That barrier sits four MFMAs into the step; behind it the step reads
+// the 16 fragments of slab kt+1 (one per two MFMAs, in the order the MFMAs will want them) and
+// requests new slabs (in the MFMA slots between the reads):
+//   ring of 4: slab kt+4 into the stage of slab kt;
+//   ring of 5, "paired": a k-contiguous operand contributes 64 bytes per row and slab, half a
+//     cache line, and the L2 serves a half-line request at the cost of a full one (16 TB/s
+//     of half lines against 27 TB/s of full lines measured for this tile stream), so slabs are
+//     requested in pairs (2j, 2j+1) with the two loads that fetch the two halves of the same rows
+//     back to back, which the L1 merges into one line request (24 TB/s).  Even step kt: first
+//     half of the rows of pair (kt+4, kt+5); odd step kt: second half of pair (kt+3, kt+4).  An
+//     n-contiguous operand already fetches whole lines; its even slab goes in the even step.
+// Loads complete in order, so the barrier's wait counts the younger ones that may stay in
+// flight: two slabs in the ring of 4; in the ring of 5 the next pair (even step) or its first
+// half (odd step).
 template <class C, bool IS_BF16, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok) {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NT, NS = C::NS;
     constexpr int TM = C::WTM / 16, TN = C::WTN / 16;        // 16x16 accumulators per wave
-    static_assert(TM == 8 && TN == 8, "the fragment waits below are written for a 128x128 wave sub-block");
-    static_assert(NS >= 3, "the barrier's load count assumes at least two slabs of lookahead");
+    static_assert(TM == 8 && TN == 8, "the slot plan below is written for a 128x128 wave sub-block");
+    static_assert(BK == 32, "one 32-wide k block per slab");
+    static_assert(NS == 4 || NS == 5, "ring of 4, or ring of 5 with paired requests");
+    constexpr bool PAIRED = NS == 5;
     using EL = EpiLayout<C>;
     constexpr int RING = NS * C::STAGE;
     constexpr int LDS_BYTES = RING > EL::BYTES ? RING : EL::BYTES;
@@ -110,6 +129,7 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     using LB = typename std::conditional<B_KC, DmaKC<BN, BK, NT>, DmaMC<BN, BK, NT>>::type;
     using FA = typename std::conditional<A_KC, Frag16KC<BM, BK>, Frag16MC<BM, BK>>::type;
     using FB = typename std::conditional<B_KC, Frag16KC<BN, BK>, Frag16MC<BN, BK>>::type;
+    static_assert(LA::L % 2 == 0 && LB::L % 2 == 0, "a slab is requested in two halves");
     LA la;
     LB lb;
     la.init(tid, a.lda);
@@ -134,20 +154,18 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
 
     const int k_tiles = (K + BK - 1) / BK;
     const int full_tiles = K / BK;
-    constexpr int NKS = BK / 32;                  // k blocks (sub-steps) per slab
-    constexpr int NM = TM * TN, NR = TM + TN;     // MFMAs and fragments per sub-step
-    constexpr int LPT = LA::L + LB::L;
-    constexpr int D = NS - 1;
+    constexpr int NM = TM * TN, NR = TM + TN;     // MFMAs and fragments per step
+    constexpr int LPT = LA::L + LB::L;            // loads per thread and slab (= per half of a pair)
 
-    typename FA::Raw af[2][TM];                   // fragments of two consecutive sub-steps
+    typename FA::Raw af[2][TM];                   // fragments of two consecutive slabs
     typename FB::Raw bf[2][TN];
 
-    // Fragment q of a sub-step in the order the MFMAs first need them: A0, B0..B7, A1..A7.
-    auto read_one = [&](int buf, int stage, int ks, int q) {
+    // Fragment q of a slab in the order the MFMAs first need them: A0, B0..B7, A1..A7.
+    auto read_one = [&](int buf, int stage, int q) {
         const char* st = lds + stage * C::STAGE;
-        if (q == 0) FA::read(st, fa[0], ks, af[buf][0]);
-        else if (q <= TN) FB::read(st, fb[q - 1], ks, bf[buf][q - 1]);
-        else FA::read(st, fa[q - TN], ks, af[buf][q - TN]);
+        if (q == 0) FA::read(st, fa[0], 0, af[buf][0]);
+        else if (q <= TN) FB::read(st, fb[q - 1], 0, bf[buf][q - 1]);
+        else FA::read(st, fa[q - TN], 0, af[buf][q - TN]);
     };
     auto run_mfmas = [&](int cur, auto slot) {
         if (FA::MANUAL_WAIT) wait_raw8(af[cur]);
@@ -165,113 +183,124 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
             slot(m, 1);
         }
     };
-    auto issue_one = [&](int q, __amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, char* stage, int k0, auto masked,
-                         uint32_t soff_a = 0, uint32_t soff_b = 0) {
-        constexpr bool M = decltype(masked)::value;
-        if (q < LA::L) la.issue(M, q, ra, stage, wave, tid, k0, K, soff_a);
-        else lb.issue(M, q - LA::L, rb, stage + C::A_BYTES, wave, tid, k0, K, soff_b);
+
+    // ---- what a step requests ----
+    // Load q (0 .. LPT-1) of a step: operand, slab, instruction of that slab.  `even` is the
+    // parity of the step.  Ring of 4: all of slab kt+4.  Ring of 5: see above; a k-contiguous
+    // operand alternates the two slabs of the pair, an n-contiguous one takes one slab per step.
+    struct Pick { bool is_a; int slab_off, i; };
+    auto pick = [](bool even, int q) -> Pick {
+        const bool is_a = q < LA::L;
+        const int r = is_a ? q : q - LA::L;
+        const int L = is_a ? LA::L : LB::L;
+        const bool transposed = is_a ? LA::TRANSPOSED : LB::TRANSPOSED;
+        if (!PAIRED) return Pick{is_a, NS, r};
+        const int first = even ? 4 : 3;                       // offset of the pair's even slab from kt
+        if (transposed) return Pick{is_a, first + (even ? 0 : 1), r};
+        return Pick{is_a, first + (r & 1), (even ? 0 : L / 2) + (r >> 1)};
     };
-    auto issue_tile = [&](int t, auto masked) {
-        const __amdgpu_buffer_rsrc_t ra = make_rsrc(pa + t * a_step, a_bytes - t * a_step);
-        const __amdgpu_buffer_rsrc_t rb = make_rsrc(pb + t * b_step, b_bytes - t * b_step);
+    const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(pa, a_bytes), rb0 = make_rsrc(pb, b_bytes);
+    // steady state: the slab exists and lies wholly inside K; the k advance is the loads' scalar
+    // offset, which the range check ignores (see load_to_lds_b128)
+    // position in the ring of slab kt + d, given that of slab kt (d <= NS): no division in the loop
+    auto ring_at = [](int ring, int d) { return ring + d >= NS ? ring + d - NS : ring + d; };
+    auto issue_hot = [&](int kt, int ring, bool even, int q) {
+        const Pick p = pick(even, q);
+        const int t = kt + p.slab_off;
+        char* stage = lds + ring_at(ring, p.slab_off) * C::STAGE;
+        if (p.is_a) la.issue(false, p.i, ra0, stage, wave, tid, 0, K, (uint32_t)(t * a_step));
+        else lb.issue(false, p.i, rb0, stage + C::A_BYTES, wave, tid, 0, K, (uint32_t)(t * b_step));
+    };
+    // first and last steps: a descriptor per slab (its range check cuts off k-rows past K), a
+    // mask for the chunks of a partial slab, nothing for slabs past the end
+    auto issue_checked = [&](int kt, bool even, int q) {
+        const Pick p = pick(even, q);
+        const int t = kt + p.slab_off;
+        if (t >= k_tiles) return;
         char* stage = lds + (t % NS) * C::STAGE;
-#pragma unroll
-        for (int q = 0; q < LPT; ++q) issue_one(q, ra, rb, stage, t * BK, masked);
+        if (p.is_a) {
+            const __amdgpu_buffer_rsrc_t r = make_rsrc(pa + t * a_step, a_bytes - t * a_step);
+            if (t < full_tiles) la.issue(false, p.i, r, stage, wave, tid, t * BK, K);
+            else la.issue(true, p.i, r, stage, wave, tid, t * BK, K);
+        } else {
+            const __amdgpu_buffer_rsrc_t r = make_rsrc(pb + t * b_step, b_bytes - t * b_step);
+            if (t < full_tiles) lb.issue(false, p.i, r, stage + C::A_BYTES, wave, tid, t * BK, K);
+            else lb.issue(true, p.i, r, stage + C::A_BYTES, wave, tid, t * BK, K);
+        }
     };
 
 #define GEMM_WAIT_VM_BARRIER(N) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory")
 
-    // Slots of a k step: NKS * NM MFMAs.  The barrier of the step sits BAR_SLOT MFMAs into the last
-    // sub-step; behind it the first fragments of the next slab are read, one per READ_EVERY slots.
-    // The loads of slab kt+D go out one per LOAD_EVERY slots from the top of the step.
-    constexpr int SLOTS = NKS * NM;
+    // Slot plan of a step (slot m follows MFMA m): barrier before MFMA BAR_SLOT; fragment q of the
+    // next slab after MFMA BAR_SLOT + 2q; loads after the odd MFMAs in between, singly every
+    // fourth slot or, paired, two every eighth.
     constexpr int BAR_SLOT = 4;
-    constexpr int BAR_POS = (NKS - 1) * NM + BAR_SLOT;
-    constexpr int READ_EVERY = 2;                               // 16 fragments in 32 slots
-    constexpr int LOAD_EVERY = SLOTS / LPT >= 4 ? 4 : SLOTS / LPT;
-    constexpr int LOADS_BEFORE_BAR = (BAR_POS + LOAD_EVERY - 1) / LOAD_EVERY < LPT ? (BAR_POS + LOAD_EVERY - 1) / LOAD_EVERY : LPT;
-    static_assert(BAR_SLOT + READ_EVERY * NR <= NM - 8, "the last fragment is read at least 8 MFMAs before the next sub-step");
-    static_assert(LOAD_EVERY * LPT <= SLOTS, "all loads of a slab fit in the step");
+    constexpr int LOAD_FIRST = BAR_SLOT + 1, LOAD_EVERY = PAIRED ? 8 : 4, LOAD_GROUP = PAIRED ? 2 : 1;
+    static_assert(BAR_SLOT + 2 * NR <= NM - 8, "the last fragment is read at least 8 MFMAs before the next step");
+    static_assert(LOAD_FIRST + (LPT / LOAD_GROUP - 1) * LOAD_EVERY < NM, "all loads of a step fit in the step");
+    // loads that may still be in flight when slab kt+1 must have landed
+    constexpr int PENDING_EVEN = PAIRED ? 2 * LPT : (NS - 2) * LPT, PENDING_ODD = PAIRED ? LPT : (NS - 2) * LPT;
 
-    // Steady state: slabs kt+1 .. kt+D exist and need no mask; the k advance travels as the loads'
-    // scalar offset (see tile_dma_kernel.hpp).  `base` is the parity of the step's first sub-step.
-    const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(pa, a_bytes), rb0 = make_rsrc(pb, b_bytes);
-    auto step_hot = [&](int kt, auto base_parity) {
-        constexpr int P0 = decltype(base_parity)::value;
-        const int stage = kt % NS, next = (kt + 1) % NS;
-        const int t = kt + D;
-        const uint32_t soff_a = (uint32_t)(t * a_step), soff_b = (uint32_t)(t * b_step);
-        char* dst = lds + (t % NS) * C::STAGE;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            const int cur = (P0 + ks) & 1, nxt = cur ^ 1;
-            const bool last = ks == NKS - 1;
-            run_mfmas(cur, [&](int m, int after) {
-                const int slot = ks * NM + m;
-                if (!after) {
-                    // loads issued so far in this step: slots 0, LOAD_EVERY, ... below BAR_POS
-                    if (last && m == BAR_SLOT) GEMM_WAIT_VM_BARRIER((D - 2) * LPT + LOADS_BEFORE_BAR);
-                    return;
-                }
-                if (!last) {
-                    if (m % READ_EVERY == 0 && m / READ_EVERY < NR) read_one(nxt, stage, ks + 1, m / READ_EVERY);
-                } else if (m >= BAR_SLOT) {
-                    const int mm = m - BAR_SLOT;
-                    if (mm % READ_EVERY == 0 && mm / READ_EVERY < NR) read_one(nxt, next, 0, mm / READ_EVERY);
-                }
-                if (slot % LOAD_EVERY == 0 && slot / LOAD_EVERY < LPT)
-                    issue_one(slot / LOAD_EVERY, ra0, rb0, dst, t * BK, std::false_type{}, soff_a, soff_b);
-                __builtin_amdgcn_sched_barrier(0);
-            });
-        }
-    };
-    // the first and last steps: flags instead of assumptions, everything outstanding is awaited
-    auto step_edge = [&](int kt, auto base_parity) {
-        constexpr int P0 = decltype(base_parity)::value;
-        const int stage = kt % NS, next = (kt + 1) % NS;
-        const int t = kt + D;
-        if (t < full_tiles) issue_tile(t, std::false_type{});
-        else if (t < k_tiles) issue_tile(t, std::true_type{});
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            const int cur = (P0 + ks) & 1, nxt = cur ^ 1;
-            if (ks < NKS - 1) {
-#pragma unroll
-                for (int q = 0; q < NR; ++q) read_one(nxt, stage, ks + 1, q);
-            } else if (kt + 1 < k_tiles) {
-                GEMM_WAIT_VM_BARRIER(0);
-#pragma unroll
-                for (int q = 0; q < NR; ++q) read_one(nxt, next, 0, q);
+    auto step_hot = [&](int kt, int ring, auto parity) {
+        constexpr bool EVEN = decltype(parity)::value == 0;
+        constexpr int cur = EVEN ? 0 : 1, nxt = cur ^ 1;
+        const int next = ring_at(ring, 1);
+        run_mfmas(cur, [&](int m, int after) {
+            if (!after) {
+                if (m == BAR_SLOT) GEMM_WAIT_VM_BARRIER(EVEN ? PENDING_EVEN : PENDING_ODD);
+                return;
             }
-            run_mfmas(cur, [](int, int) {});
-        }
+            if (m >= BAR_SLOT && (m - BAR_SLOT) % 2 == 0 && (m - BAR_SLOT) / 2 < NR) read_one(nxt, next, (m - BAR_SLOT) / 2);
+            if (m >= LOAD_FIRST && (m - LOAD_FIRST) % LOAD_EVERY == 0 && (m - LOAD_FIRST) / LOAD_EVERY < LPT / LOAD_GROUP) {
+#pragma unroll
+                for (int u = 0; u < LOAD_GROUP; ++u) issue_hot(kt, ring, EVEN, (m - LOAD_FIRST) / LOAD_EVERY * LOAD_GROUP + u);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
-    // With one sub-step per slab the fragment buffers alternate from step to step, so steps are
-    // taken two at a time to keep the register names static.
-    constexpr int STRIDE = (NKS & 1) ? 2 : 1;
-    using Par0 = std::integral_constant<int, 0>;
-    using Par1 = std::integral_constant<int, NKS & 1>;
+    auto step_edge = [&](int kt, auto parity) {
+        constexpr bool EVEN = decltype(parity)::value == 0;
+        constexpr int cur = EVEN ? 0 : 1, nxt = cur ^ 1;
+        if (kt + 1 < k_tiles) {
+            GEMM_WAIT_VM_BARRIER(0);
+#pragma unroll
+            for (int q = 0; q < LPT; ++q) issue_checked(kt, EVEN, q);
+#pragma unroll
+            for (int q = 0; q < NR; ++q) read_one(nxt, (kt + 1) % NS, q);
+        }
+        run_mfmas(cur, [](int, int) {});
+    };
+    using Even = std::integral_constant<int, 0>;
+    using Odd = std::integral_constant<int, 1>;
 
     if (k_tiles > 0) {
+        // slabs 0 .. 3: what the steps "before the first" would have requested
 #pragma unroll
-        for (int t = 0; t < D; ++t) {
-            if (t < full_tiles) issue_tile(t, std::false_type{});
-            else if (t < k_tiles) issue_tile(t, std::true_type{});
+        for (int kt = -4; kt < 0; ++kt) {
+            if (!PAIRED) {
+#pragma unroll
+                for (int q = 0; q < LPT; ++q) issue_checked(kt, true, q);
+            } else if ((kt & 1) == 0) {
+#pragma unroll
+                for (int q = 0; q < LPT; ++q) issue_checked(kt, true, q);
+            } else {
+#pragma unroll
+                for (int q = 0; q < LPT; ++q) issue_checked(kt, false, q);
+            }
         }
         GEMM_WAIT_VM_BARRIER(0);
 #pragma unroll
-        for (int q = 0; q < NR; ++q) read_one(0, 0, 0, q);
+        for (int q = 0; q < NR; ++q) read_one(0, 0, q);
         __builtin_amdgcn_sched_barrier(0);
-        int kt = 0;
-        for (; kt + STRIDE - 1 + D < full_tiles; kt += STRIDE) {
-            step_hot(kt, Par0{});
-            if constexpr (STRIDE == 2) step_hot(kt + 1, Par1{});
+        int kt = 0, ring = 0;                            // ring = kt % NS
+        for (; kt + 1 + NS < full_tiles; kt += 2) {      // the two steps request slabs up to kt + 5
+            step_hot(kt, ring, Even{});
+            step_hot(kt + 1, ring_at(ring, 1), Odd{});
+            ring = ring_at(ring, 2);
         }
-        for (; kt < k_tiles; kt += STRIDE) {
-            step_edge(kt, Par0{});
-            if constexpr (STRIDE == 2) {
-                if (kt + 1 < k_tiles) step_edge(kt + 1, Par1{});
-            }
+        for (; kt < k_tiles; kt += 2) {
+            step_edge(kt, Even{});
+            if (kt + 1 < k_tiles) step_edge(kt + 1, Odd{});
         }
     }
     // LDS is reused by the epilogue; the wait states let the last MFMAs retire before their results are read
