@@ -21,7 +21,7 @@ LIB = os.path.join(HERE, "libgemm.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-c++20-extensions", "-fPIC", "-fvisibility=hidden",
     "-fno-gpu-rdc", "-Wall", "-Wno-unused-function", "-Wno-unknown-pragmas",
     # never let the compiler form packed-fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

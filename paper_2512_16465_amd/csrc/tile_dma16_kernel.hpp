@@ -12,10 +12,18 @@
 // reads one 16-byte fragment per 16 rows of A and per 16 columns of B:
 //   operand A of the MFMA: lane l holds row l%16, k = 8*(l/16) .. +7; operand B: column l%16,
 //   same k; accumulator register v of lane l is row 4*(l/16)+v, column l%16.
-//   k-contiguous operand: one ds_read_b128 of chunk (row, l/16) of the swizzled slab.
+//   k-contiguous operand: one ds_read_b128 of chunk (row, l/16) of the swizzled slab; the slab
+//   is periodic in 16 rows (kc_line_hash<false>), so tile i is tile 0's address + 1024*i.
 //   m/n-contiguous operand ([k][row] slab): two ds_read_b64_tr_b16; lane j of a 16-lane group
 //   supplies k-row 8*(l/16) + j/4 (+4 for the second read), columns 4*(j%4)...
+//
+// One wave per SIMD issues one instruction every four cycles and an MFMA lasts sixteen: next to
+// each MFMA there is room for three other instructions (two if they are vector ALU).  The steady
+// state is therefore laid out slot by slot (slot m follows MFMA m), all fragment reads are
+// assembly with fixed addresses + immediates, and the scalar bookkeeping of the next two steps is
+// done in the otherwise empty slots at the end of a step.
 #pragma once
+#include <utility>
 #include "tile_dma_kernel.hpp"
 
 namespace gemm {
@@ -33,26 +41,37 @@ __device__ __forceinline__ void mfma16(f32x4& c, u32x4 a, u32x4 b) {
     else asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
-// ---- fragment readers for 16-row tiles; the slabs are those written by DmaKC / DmaMC ----
+// ---- fragment readers for 16-row tiles ----
+// Both take absolute LDS byte addresses and are assembly, so the compiler neither reorders them
+// nor waits for them: the kernel waits (lgkmcnt) itself before the fragments are used.
+
+struct Frag16Raw { uint2 lo, hi; };
 
 template <int ROWS, int BK>
 struct Frag16KC {
     static constexpr int CPR = BK / 8;
-    static_assert(BK == 32 || BK == 64, "one or two 32-wide k blocks per slab");
-    static __device__ __forceinline__ uint32_t base(int row0, int lane) { return swz<CPR>(row0 + (lane & 15), lane >> 4); }
-    typedef u32x4 Raw;
-    static constexpr bool MANUAL_WAIT = false;
-    // k block ks of the slab: chunk index + 4 flips bit 2 of the swizzled position
-    static __device__ __forceinline__ void read(const char* slab, uint32_t b, int ks, Raw& r) {
-        r = *(const u32x4*)(slab + (b ^ (uint32_t)(ks << 6)));
+    static_assert(BK == 32, "one 32-wide k block per slab");
+    static constexpr bool PER_TILE_ADDRESS = false;            // tile i = tile 0 + 1024 * i
+    // byte offset inside the operand's slab of this lane's chunk of the tile that starts at row0
+    static __device__ __forceinline__ uint32_t base(int row0, int lane) {
+        const uint32_t chunk = (uint32_t)(row0 + (lane & 15)) * CPR + (uint32_t)(lane >> 4);
+        const uint32_t line = chunk >> 3;
+        return (line << 7) | (((chunk & 7u) ^ kc_line_hash<false>(line)) << 4);
     }
-    static __device__ __forceinline__ u32x4 finish(const Raw& r) { return r; }
+    template <int TILE>
+    static __device__ __forceinline__ void read(uint32_t addr, Frag16Raw& r) {
+        u32x4 v;
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(TILE * 1024));
+        r.lo = uint2{v[0], v[1]};
+        r.hi = uint2{v[2], v[3]};
+    }
 };
 
 template <int ROWS, int BK>
 struct Frag16MC {
     static constexpr int CPK = ROWS / 8;
-    static_assert(BK == 32 || BK == 64, "one or two 32-wide k blocks per slab");
+    static_assert(BK == 32, "one 32-wide k block per slab");
+    static constexpr bool PER_TILE_ADDRESS = true;             // the swizzle is not additive in the tile index
     static __device__ __forceinline__ uint32_t base(int row0, int lane) {
         const uint32_t j = lane & 15, g = lane >> 4;
         const uint32_t k = 8 * g + (j >> 2);
@@ -60,44 +79,33 @@ struct Frag16MC {
         const uint32_t cs = (col >> 3) ^ mc_swizzle(k);
         return (k * CPK + cs) * 16 + (col & 7) * 2;
     }
-    struct Raw { uint2 lo, hi; };
-    static constexpr bool MANUAL_WAIT = true;
-    static constexpr int KS_BYTES = 32 * CPK * 16, HALF_BYTES = 4 * CPK * 16;   // 32 and 4 k-rows further
-    static_assert(KS_BYTES + HALF_BYTES < 65536, "offsets must fit the instruction's immediate");
-    static __device__ __forceinline__ void read(const char* slab, uint32_t b, int ks, Raw& r) {
-        const uint32_t addr = (uint32_t)(uintptr_t)GEMM_LDS_PTR(slab) + b;
-        if (ks == 0) {
-            asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r.lo) : "v"(addr));
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(HALF_BYTES));
-        } else {
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.lo) : "v"(addr), "n"(KS_BYTES));
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(KS_BYTES + HALF_BYTES));
-        }
+    static constexpr int HALF_BYTES = 4 * CPK * 16;            // 4 k-rows further
+    template <int TILE>
+    static __device__ __forceinline__ void read(uint32_t addr, Frag16Raw& r) {
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r.lo) : "v"(addr));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(HALF_BYTES));
     }
-    static __device__ __forceinline__ u32x4 finish(const Raw& r) { return u32x4{r.lo.x, r.lo.y, r.hi.x, r.hi.y}; }
 };
 
-template <class Raw>
-__device__ __forceinline__ void wait_raw8(Raw (&r)[8]) {
+__device__ __forceinline__ void wait_raw8(Frag16Raw (&r)[8]) {
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+v"(r[0].lo), "+v"(r[0].hi), "+v"(r[1].lo), "+v"(r[1].hi), "+v"(r[2].lo), "+v"(r[2].hi), "+v"(r[3].lo), "+v"(r[3].hi),
                    "+v"(r[4].lo), "+v"(r[4].hi), "+v"(r[5].lo), "+v"(r[5].hi), "+v"(r[6].lo), "+v"(r[6].hi), "+v"(r[7].lo), "+v"(r[7].hi));
 }
-__device__ __forceinline__ void wait_raw8(u32x4 (&)[8]) {}
 
-// Pipeline (BK = 32, one 64-MFMA sub-step per slab).  During step kt a wave multiplies the
+// Pipeline (BK = 32, one 64-MFMA step per slab).  During step kt a wave multiplies the
 // fragments of slab kt, which it read from LDS during step kt-1, so LDS holds slabs kt+1 (being
 // read) .. kt+NS-1 or kt+NS, and the stage of slab kt is free as soon as every wave has passed
 // the barrier of step kt.  That barrier sits four MFMAs into the step; behind it the step reads
 // the 16 fragments of slab kt+1 (one per two MFMAs, in the order the MFMAs will want them) and
-// requests new slabs (in the MFMA slots between the reads):
+// requests new slabs (one load per four MFMAs, in the slots between the reads):
 //   ring of 4: slab kt+4 into the stage of slab kt;
 //   ring of 5, "paired": a k-contiguous operand contributes 64 bytes per row and slab, half a
 //     cache line, and the L2 serves a half-line request at the cost of a full one (16 TB/s
 //     of half lines against 27 TB/s of full lines measured for this tile stream), so slabs are
 //     requested in pairs (2j, 2j+1) with the two loads that fetch the two halves of the same rows
-//     back to back, which the L1 merges into one line request (24 TB/s).  Even step kt: first
-//     half of the rows of pair (kt+4, kt+5); odd step kt: second half of pair (kt+3, kt+4).  An
+//     next to each other, which the L1 merges into one line request.  Even step kt: first half
+//     of the rows of pair (kt+4, kt+5); odd step kt: second half of pair (kt+3, kt+4).  An
 //     n-contiguous operand already fetches whole lines; its even slab goes in the even step.
 // Loads complete in order, so the barrier's wait counts the younger ones that may stay in
 // flight: two slabs in the ring of 4; in the ring of 5 the next pair (even step) or its first
@@ -125,8 +133,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
     const int K = (int)a.K;
 
-    using LA = typename std::conditional<A_KC, DmaKC<BM, BK, NT>, DmaMC<BM, BK, NT>>::type;
-    using LB = typename std::conditional<B_KC, DmaKC<BN, BK, NT>, DmaMC<BN, BK, NT>>::type;
+    using LA = typename std::conditional<A_KC, DmaKC<BM, BK, NT, false>, DmaMC<BM, BK, NT>>::type;
+    using LB = typename std::conditional<B_KC, DmaKC<BN, BK, NT, false>, DmaMC<BN, BK, NT>>::type;
     using FA = typename std::conditional<A_KC, Frag16KC<BM, BK>, Frag16MC<BM, BK>>::type;
     using FB = typename std::conditional<B_KC, Frag16KC<BN, BK>, Frag16MC<BN, BK>>::type;
     static_assert(LA::L % 2 == 0 && LB::L % 2 == 0, "a slab is requested in two halves");
@@ -140,11 +148,14 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     const int64_t a_bytes = LA::total_bytes(a.M, a.K, a.lda) - (pa - (const char*)a.A);
     const int64_t b_bytes = LB::total_bytes(a.N, a.K, a.ldb) - (pb - (const char*)a.B);
 
-    uint32_t fa[TM], fb[TN];
+    // LDS addresses of this lane's fragments in stage 0: one per operand, or one per tile
+    constexpr int NFA = FA::PER_TILE_ADDRESS ? TM : 1, NFB = FB::PER_TILE_ADDRESS ? TN : 1;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)GEMM_LDS_PTR(lds);
+    uint32_t fa[NFA], fb[NFB];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[i] = FA::base(wm * C::WTM + i * 16, lane);
+    for (int i = 0; i < NFA; ++i) fa[i] = lds0 + FA::base(wm * C::WTM + i * 16, lane);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[j] = C::A_BYTES + FB::base(wn * C::WTN + j * 16, lane);
+    for (int j = 0; j < NFB; ++j) fb[j] = lds0 + C::A_BYTES + FB::base(wn * C::WTN + j * 16, lane);
 
     f32x4 acc[TM][TN];
 #pragma unroll
@@ -157,65 +168,71 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     constexpr int NM = TM * TN, NR = TM + TN;     // MFMAs and fragments per step
     constexpr int LPT = LA::L + LB::L;            // loads per thread and slab (= per half of a pair)
 
-    typename FA::Raw af[2][TM];                   // fragments of two consecutive slabs
-    typename FB::Raw bf[2][TN];
+    Frag16Raw af[2][TM];                          // fragments of two consecutive slabs
+    Frag16Raw bf[2][TN];
 
-    // Fragment q of a slab in the order the MFMAs first need them: A0, B0..B7, A1..A7.
-    auto read_one = [&](int buf, int stage, int q) {
-        const char* st = lds + stage * C::STAGE;
-        if (q == 0) FA::read(st, fa[0], 0, af[buf][0]);
-        else if (q <= TN) FB::read(st, fb[q - 1], 0, bf[buf][q - 1]);
-        else FA::read(st, fa[q - TN], 0, af[buf][q - TN]);
+    // Fragment q of the slab in the stage at byte offset `off`, in the order the MFMAs first need
+    // them: A0, B0..B7, A1..A7.  `ka`, `kb`: fragment addresses of tile 0 in that stage, for the
+    // operands that need only one.
+    auto read_a = [&](auto tile, int buf, uint32_t off, uint32_t ka) {
+        constexpr int T = decltype(tile)::value;
+        if constexpr (FA::PER_TILE_ADDRESS) FA::template read<T>(fa[T % NFA] + off, af[buf][T]);
+        else FA::template read<T>(ka, af[buf][T]);
+    };
+    auto read_b = [&](auto tile, int buf, uint32_t off, uint32_t kb) {
+        constexpr int T = decltype(tile)::value;
+        if constexpr (FB::PER_TILE_ADDRESS) FB::template read<T>(fb[T % NFB] + off, bf[buf][T]);
+        else FB::template read<T>(kb, bf[buf][T]);
+    };
+    auto read_one = [&](auto qc, int buf, uint32_t off, uint32_t ka, uint32_t kb) {
+        constexpr int q = decltype(qc)::value;
+        if constexpr (q == 0) read_a(std::integral_constant<int, 0>{}, buf, off, ka);
+        else if constexpr (q <= TN) read_b(std::integral_constant<int, (q - 1) % TN>{}, buf, off, kb);
+        else read_a(std::integral_constant<int, (q - TN) % TM>{}, buf, off, ka);
+    };
+    auto read_all = [&](int buf, uint32_t off) {
+        const uint32_t ka = fa[0] + off, kb = fb[0] + off;
+        [&]<int... Q>(std::integer_sequence<int, Q...>) { (read_one(std::integral_constant<int, Q>{}, buf, off, ka, kb), ...); }
+        (std::make_integer_sequence<int, NR>{});
     };
     auto run_mfmas = [&](int cur, auto slot) {
-        if (FA::MANUAL_WAIT) wait_raw8(af[cur]);
-        if (FB::MANUAL_WAIT) wait_raw8(bf[cur]);
+        wait_raw8(af[cur]);
+        wait_raw8(bf[cur]);
         u32x4 ua[TM], ub[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) ua[i] = FA::finish(af[cur][i]);
+        for (int i = 0; i < TM; ++i) ua[i] = u32x4{af[cur][i].lo.x, af[cur][i].lo.y, af[cur][i].hi.x, af[cur][i].hi.y};
 #pragma unroll
-        for (int j = 0; j < TN; ++j) ub[j] = FB::finish(bf[cur][j]);
-#pragma unroll
-        for (int m = 0; m < NM; ++m) {
-            slot(m, 0);
-            const int i = m / TN, j = (i & 1) ? TN - 1 - m % TN : m % TN;     // boustrophedon: consecutive MFMAs share an operand
-            mfma16<IS_BF16>(acc[i][j], ua[i], ub[j]);
-            slot(m, 1);
+        for (int j = 0; j < TN; ++j) ub[j] = u32x4{bf[cur][j].lo.x, bf[cur][j].lo.y, bf[cur][j].hi.x, bf[cur][j].hi.y};
+        [&]<int... M>(std::integer_sequence<int, M...>) {
+            ([&] {
+                slot(std::integral_constant<int, M>{}, std::false_type{});
+                constexpr int i = M / TN, j = (i & 1) ? TN - 1 - M % TN : M % TN;     // boustrophedon: consecutive MFMAs share an operand
+                mfma16<IS_BF16>(acc[i][j], ua[i], ub[j]);
+                slot(std::integral_constant<int, M>{}, std::true_type{});
+            }(), ...);
         }
+        (std::make_integer_sequence<int, NM>{});
     };
 
     // ---- what a step requests ----
-    // Load q (0 .. LPT-1) of a step: operand, slab, instruction of that slab.  `even` is the
-    // parity of the step.  Ring of 4: all of slab kt+4.  Ring of 5: see above; a k-contiguous
-    // operand alternates the two slabs of the pair, an n-contiguous one takes one slab per step.
-    struct Pick { bool is_a; int slab_off, i; };
+    // Load q (0 .. LPT-1) of a step: operand, which of the two slabs (kt_even+4, kt_even+5) of the
+    // current pair of steps, instruction of that slab.  Ring of 4: all of slab kt+4.  Ring of 5:
+    // see above; a k-contiguous operand alternates the two slabs, an n-contiguous one takes one
+    // slab per step.
+    struct Pick { bool is_a; int which, i; };
     auto pick = [](bool even, int q) -> Pick {
         const bool is_a = q < LA::L;
         const int r = is_a ? q : q - LA::L;
         const int L = is_a ? LA::L : LB::L;
         const bool transposed = is_a ? LA::TRANSPOSED : LB::TRANSPOSED;
-        if (!PAIRED) return Pick{is_a, NS, r};
-        const int first = even ? 4 : 3;                       // offset of the pair's even slab from kt
-        if (transposed) return Pick{is_a, first + (even ? 0 : 1), r};
-        return Pick{is_a, first + (r & 1), (even ? 0 : L / 2) + (r >> 1)};
-    };
-    const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(pa, a_bytes), rb0 = make_rsrc(pb, b_bytes);
-    // steady state: the slab exists and lies wholly inside K; the k advance is the loads' scalar
-    // offset, which the range check ignores (see load_to_lds_b128)
-    // position in the ring of slab kt + d, given that of slab kt (d <= NS): no division in the loop
-    auto ring_at = [](int ring, int d) { return ring + d >= NS ? ring + d - NS : ring + d; };
-    auto issue_hot = [&](int kt, int ring, bool even, int q) {
-        const Pick p = pick(even, q);
-        const int t = kt + p.slab_off;
-        char* stage = lds + ring_at(ring, p.slab_off) * C::STAGE;
-        if (p.is_a) la.issue(false, p.i, ra0, stage, wave, tid, 0, K, (uint32_t)(t * a_step));
-        else lb.issue(false, p.i, rb0, stage + C::A_BYTES, wave, tid, 0, K, (uint32_t)(t * b_step));
+        if (!PAIRED || transposed) return Pick{is_a, even ? 0 : 1, r};
+        return Pick{is_a, r & 1, (even ? 0 : L / 2) + (r >> 1)};
     };
     // first and last steps: a descriptor per slab (its range check cuts off k-rows past K), a
     // mask for the chunks of a partial slab, nothing for slabs past the end
-    auto issue_checked = [&](int kt, bool even, int q) {
+    auto issue_checked = [&](int kt_even, bool even, int q) {
         const Pick p = pick(even, q);
-        const int t = kt + p.slab_off;
+        const int t = kt_even + 4 + p.which;
         if (t >= k_tiles) return;
         char* stage = lds + (t % NS) * C::STAGE;
         if (p.is_a) {
@@ -231,31 +248,55 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
 
 #define GEMM_WAIT_VM_BARRIER(N) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory")
 
-    // Slot plan of a step (slot m follows MFMA m): barrier before MFMA BAR_SLOT; fragment q of the
-    // next slab after MFMA BAR_SLOT + 2q; loads after the odd MFMAs in between, singly every
-    // fourth slot or, paired, two every eighth.
-    constexpr int BAR_SLOT = 4;
-    constexpr int LOAD_FIRST = BAR_SLOT + 1, LOAD_EVERY = PAIRED ? 8 : 4, LOAD_GROUP = PAIRED ? 2 : 1;
-    static_assert(BAR_SLOT + 2 * NR <= NM - 8, "the last fragment is read at least 8 MFMAs before the next step");
-    static_assert(LOAD_FIRST + (LPT / LOAD_GROUP - 1) * LOAD_EVERY < NM, "all loads of a step fit in the step");
+    // Slot plan of a step: barrier before MFMA BAR_SLOT; fragment q of the next slab after MFMA
+    // BAR_SLOT + 2q; load q after MFMA LOAD_FIRST + 4q (odd slots); the scalars of the next pair
+    // of steps from slot TAIL_FIRST on.
+    constexpr int BAR_SLOT = 4, LOAD_FIRST = BAR_SLOT + 1, LOAD_EVERY = 4, TAIL_FIRST = 40;
+    static_assert(BAR_SLOT + 2 * NR <= TAIL_FIRST && LOAD_FIRST + (LPT - 1) * LOAD_EVERY < TAIL_FIRST, "reads and loads end before the tail");
     // loads that may still be in flight when slab kt+1 must have landed
     constexpr int PENDING_EVEN = PAIRED ? 2 * LPT : (NS - 2) * LPT, PENDING_ODD = PAIRED ? LPT : (NS - 2) * LPT;
 
-    auto step_hot = [&](int kt, int ring, auto parity) {
+    // Scalars of a pair of steps (kt even, kt+1): byte offsets of the stages read in the two steps
+    // (slabs kt+1, kt+2) and written (slabs kt+4, kt+5), and the operands' byte offsets of the
+    // written slabs.  Advanced by two slabs in the tail of the odd step.
+    struct Sched { uint32_t r1, r2, w0, w1, sa0, sa1, sb0, sb1; };
+    auto stage_off = [](int pos) { return (uint32_t)((pos % NS) * C::STAGE); };
+    auto advance2 = [](uint32_t off) { const uint32_t n = off + 2 * C::STAGE; return n >= (uint32_t)RING ? n - RING : n; };
+    const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(pa, a_bytes), rb0 = make_rsrc(pb, b_bytes);
+    char* const wave_lds = lds + wave * 1024;
+
+    // Steady state: every slab requested exists and lies wholly inside K; the k advance is the
+    // loads' scalar offset, which the range check ignores (see load_to_lds_b128).
+    auto step_hot = [&](Sched& s, auto parity) {
         constexpr bool EVEN = decltype(parity)::value == 0;
         constexpr int cur = EVEN ? 0 : 1, nxt = cur ^ 1;
-        const int next = ring_at(ring, 1);
-        run_mfmas(cur, [&](int m, int after) {
-            if (!after) {
-                if (m == BAR_SLOT) GEMM_WAIT_VM_BARRIER(EVEN ? PENDING_EVEN : PENDING_ODD);
-                return;
+        const uint32_t roff = EVEN ? s.r1 : s.r2;
+        uint32_t ka = 0, kb = 0;
+        run_mfmas(cur, [&](auto mc, auto after) {
+            constexpr int m = decltype(mc)::value;
+            if constexpr (!decltype(after)::value) {
+                if constexpr (m == BAR_SLOT) GEMM_WAIT_VM_BARRIER(EVEN ? PENDING_EVEN : PENDING_ODD);
+            } else {
+                if constexpr (m == 1) ka = fa[0] + roff;
+                if constexpr (m == 2) kb = fb[0] + roff;
+                if constexpr (m >= BAR_SLOT && (m - BAR_SLOT) % 2 == 0 && (m - BAR_SLOT) / 2 < NR)
+                    read_one(std::integral_constant<int, (m - BAR_SLOT) / 2 % NR>{}, nxt, roff, ka, kb);
+                if constexpr (m >= LOAD_FIRST && (m - LOAD_FIRST) % LOAD_EVERY == 0 && (m - LOAD_FIRST) / LOAD_EVERY < LPT) {
+                    const Pick p = pick(EVEN, (m - LOAD_FIRST) / LOAD_EVERY);
+                    char* dst = wave_lds + (p.which ? s.w1 : s.w0);
+                    if (p.is_a) la.issue_at(p.i, ra0, dst, p.which ? s.sa1 : s.sa0);
+                    else lb.issue_at(p.i, rb0, dst + C::A_BYTES, p.which ? s.sb1 : s.sb0);
+                }
+                if constexpr (!EVEN) {      // next pair of steps: everything moves on by two slabs
+                    if constexpr (m == TAIL_FIRST) s.r1 = advance2(s.r1);
+                    if constexpr (m == TAIL_FIRST + 2) s.r2 = advance2(s.r2);
+                    if constexpr (m == TAIL_FIRST + 4) s.w0 = advance2(s.w0);
+                    if constexpr (m == TAIL_FIRST + 6) s.w1 = advance2(s.w1);
+                    if constexpr (m == TAIL_FIRST + 8) { s.sa0 += (uint32_t)(2 * a_step); s.sa1 += (uint32_t)(2 * a_step); }
+                    if constexpr (m == TAIL_FIRST + 9) { s.sb0 += (uint32_t)(2 * b_step); s.sb1 += (uint32_t)(2 * b_step); }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (m >= BAR_SLOT && (m - BAR_SLOT) % 2 == 0 && (m - BAR_SLOT) / 2 < NR) read_one(nxt, next, (m - BAR_SLOT) / 2);
-            if (m >= LOAD_FIRST && (m - LOAD_FIRST) % LOAD_EVERY == 0 && (m - LOAD_FIRST) / LOAD_EVERY < LPT / LOAD_GROUP) {
-#pragma unroll
-                for (int u = 0; u < LOAD_GROUP; ++u) issue_hot(kt, ring, EVEN, (m - LOAD_FIRST) / LOAD_EVERY * LOAD_GROUP + u);
-            }
-            __builtin_amdgcn_sched_barrier(0);
         });
     };
     auto step_edge = [&](int kt, auto parity) {
@@ -264,39 +305,32 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
         if (kt + 1 < k_tiles) {
             GEMM_WAIT_VM_BARRIER(0);
 #pragma unroll
-            for (int q = 0; q < LPT; ++q) issue_checked(kt, EVEN, q);
-#pragma unroll
-            for (int q = 0; q < NR; ++q) read_one(nxt, (kt + 1) % NS, q);
+            for (int q = 0; q < LPT; ++q) issue_checked(EVEN ? kt : kt - 1, EVEN, q);
+            read_all(nxt, stage_off(kt + 1));
         }
-        run_mfmas(cur, [](int, int) {});
+        run_mfmas(cur, [](auto, auto) {});
     };
     using Even = std::integral_constant<int, 0>;
     using Odd = std::integral_constant<int, 1>;
 
     if (k_tiles > 0) {
-        // slabs 0 .. 3: what the steps "before the first" would have requested
+        // slabs 0 .. 3: what the two pairs of steps "before the first" would have requested
 #pragma unroll
-        for (int kt = -4; kt < 0; ++kt) {
-            if (!PAIRED) {
+        for (int kt_even = -4; kt_even < 0; kt_even += 2) {
 #pragma unroll
-                for (int q = 0; q < LPT; ++q) issue_checked(kt, true, q);
-            } else if ((kt & 1) == 0) {
+            for (int q = 0; q < LPT; ++q) issue_checked(kt_even, true, q);
 #pragma unroll
-                for (int q = 0; q < LPT; ++q) issue_checked(kt, true, q);
-            } else {
-#pragma unroll
-                for (int q = 0; q < LPT; ++q) issue_checked(kt, false, q);
-            }
+            for (int q = 0; q < LPT; ++q) issue_checked(kt_even, false, q);
         }
         GEMM_WAIT_VM_BARRIER(0);
-#pragma unroll
-        for (int q = 0; q < NR; ++q) read_one(0, 0, q);
+        read_all(0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        int kt = 0, ring = 0;                            // ring = kt % NS
+        int kt = 0;
+        Sched s{stage_off(1), stage_off(2), stage_off(4), stage_off(5), (uint32_t)(4 * a_step), (uint32_t)(5 * a_step),
+                (uint32_t)(4 * b_step), (uint32_t)(5 * b_step)};
         for (; kt + 1 + NS < full_tiles; kt += 2) {      // the two steps request slabs up to kt + 5
-            step_hot(kt, ring, Even{});
-            step_hot(kt + 1, ring_at(ring, 1), Odd{});
-            ring = ring_at(ring, 2);
+            step_hot(s, Even{});
+            step_hot(s, Odd{});
         }
         for (; kt < k_tiles; kt += 2) {
             step_edge(kt, Even{});

@@ -54,8 +54,16 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 // ---- operand movers ----
 
+// Hash of the 128-byte line number that is XOR-ed into the chunk position of a k-contiguous slab.
+// FOLD = true is the layout of tile_kernel.hpp's swz (fragments that span 32 rows: 16 lines);
+// FOLD = false uses the low three bits only, which is enough for fragments that span 16 rows and
+// makes the slab periodic in 1024 bytes (16 rows), so that the fragments of successive 16-row
+// tiles lie at a fixed distance from each other.
+template <bool FOLD>
+__device__ __forceinline__ uint32_t kc_line_hash(uint32_t line) { return FOLD ? ((line ^ (line >> 3)) & 7u) : (line & 7u); }
+
 // k-contiguous operand: ROWS x BK slab, element (row, k) at base + row*ld + k.
-template <int ROWS, int BK, int NT>
+template <int ROWS, int BK, int NT, bool FOLD = true>
 struct DmaKC {
     static constexpr int CPR = BK / 8, SLOTS = ROWS * CPR, L = SLOTS / NT;
     static constexpr int BYTES = ROWS * BK * 2;
@@ -68,7 +76,7 @@ struct DmaKC {
         for (int i = 0; i < L; ++i) {
             const uint32_t S = i * NT + tid;                      // LDS slot this lane fills with load i
             const uint32_t line = S >> 3;
-            const uint32_t pos = (S & 7u) ^ ((line ^ (line >> 3)) & 7u);
+            const uint32_t pos = (S & 7u) ^ kc_line_hash<FOLD>(line);
             const uint32_t chunk = (line << 3) | pos;             // logical chunk: row*CPR + c
             const uint32_t row = chunk / CPR, c = chunk % CPR;
             voff[i] = (uint32_t)((row * ld + c * 8) * 2);
@@ -77,7 +85,7 @@ struct DmaKC {
     // k offset (in elements) of the chunk of load i inside the slab
     __device__ __forceinline__ int chunk_k(int i, int tid) const {
         const uint32_t S = i * NT + tid, line = S >> 3;
-        const uint32_t pos = (S & 7u) ^ ((line ^ (line >> 3)) & 7u);
+        const uint32_t pos = (S & 7u) ^ kc_line_hash<FOLD>(line);
         return (int)((((line << 3) | pos) % CPR) * 8);
     }
     __device__ __forceinline__ void issue(bool MASKED, int i, __amdgpu_buffer_rsrc_t rsrc, char* stage, int wave, int tid, int k0,
@@ -85,6 +93,10 @@ struct DmaKC {
         uint32_t off = voff[i];
         if (MASKED && k0 + chunk_k(i, tid) >= K) off = 0x7ffffff0u;       // past the end of any supported operand: the slot is filled with zeros
         load_to_lds_b128(rsrc, stage + (i * NT + wave * 64) * 16, off, soff);
+    }
+    // unmasked load i whose destination is given for this wave: `wave_dst` = stage + wave * 1024
+    __device__ __forceinline__ void issue_at(int i, __amdgpu_buffer_rsrc_t rsrc, char* wave_dst, uint32_t soff) const {
+        load_to_lds_b128(rsrc, wave_dst + i * NT * 16, voff[i], soff);
     }
     static __device__ __forceinline__ const char* tile_base(const void* p, int64_t first_row, int64_t ld) {
         return (const char*)p + first_row * ld * 2;
@@ -134,6 +146,9 @@ struct DmaMC {
         // k-rows past K lie past the end of the operand and read as zero by themselves (as long
         // as the descriptor starts at the slab, i.e. soff == 0)
         load_to_lds_b128(rsrc, stage + (i * NT + wave * 64) * 16, voff[i], soff);
+    }
+    __device__ __forceinline__ void issue_at(int i, __amdgpu_buffer_rsrc_t rsrc, char* wave_dst, uint32_t soff) const {
+        load_to_lds_b128(rsrc, wave_dst + i * NT * 16, voff[i], soff);
     }
     static __device__ __forceinline__ const char* tile_base(const void* p, int64_t first_row, int64_t /*ld*/) {
         return (const char*)p + first_row * 2;
