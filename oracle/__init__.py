@@ -23,7 +23,7 @@ _SRC = os.path.join(_HERE, "gemm_oracle.c")
 _LIB = os.path.join(_HERE, "libgemm_oracle.so")
 
 F32, F16, BF16 = 0, 1, 2
-ACT_NONE, ACT_GELU_ERF = 0, 1
+ACT_NONE, ACT_GELU_ERF, ACT_RELU, ACT_SILU, ACT_GELU_TANH = 0, 1, 2, 3, 4
 
 _ITEMSIZE = {F32: 4, F16: 2, BF16: 2}
 
@@ -71,6 +71,8 @@ def _load():
         lib.oracle_encode_array.argtypes = [ctypes.c_int, dp, ctypes.c_int64, ctypes.c_void_p]
         lib.oracle_gelu_erf.restype = ctypes.c_double
         lib.oracle_gelu_erf.argtypes = [ctypes.c_double]
+        lib.oracle_act.restype = ctypes.c_double
+        lib.oracle_act.argtypes = [ctypes.c_int, ctypes.c_double]
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_num_threads.argtypes = []
         lib.oracle_gemm_full.restype = ctypes.c_int
@@ -174,6 +176,11 @@ def encode(dtype: int, values: np.ndarray) -> np.ndarray:
 
 def gelu_erf(x: float) -> float:
     return float(_load().oracle_gelu_erf(float(x)))
+
+
+def act(code: int, x: float) -> float:
+    """The activation `code` (ACT_*) applied to one value."""
+    return float(_load().oracle_act(int(code), float(x)))
 
 
 def num_threads() -> int:

@@ -12,7 +12,7 @@
  *
  *   acc(i,j) = sum_{k=0}^{K-1} op(A)(i,k) * op(B)(k,j)        fp64, k ascending
  *   pre(i,j) = alpha*acc(i,j) + (beta==0 ? 0 : beta*C_in(i,j)) + (bias ? bias[j] : 0)
- *   ref(i,j) = act(pre(i,j))            act = identity | x*Phi(x) (erf form)
+ *   ref(i,j) = act(pre(i,j))            act = identity | x*Phi(x) (erf form) | ReLU | SiLU | GELU (tanh form)
  *
  * Storage is row-major: op(A)(i,k) is A[i*lda+k] (transA=0) or A[k*lda+i]
  * (transA=1); op(B)(k,j) is B[k*ldb+j] (transB=0) or B[j*ldb+k] (transB=1);
@@ -34,7 +34,7 @@
 
 /* element type codes (an interface constant shared with callers by value only) */
 enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2 };
-enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_GELU_ERF = 1 };
+enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_GELU_ERF = 1, ORACLE_ACT_RELU = 2, ORACLE_ACT_SILU = 3, ORACLE_ACT_GELU_TANH = 4 };
 
 typedef struct {
     int64_t M, N, K;
@@ -138,6 +138,28 @@ void oracle_encode_array(int dtype, const double *src, int64_t n, void *dst) {
 /* x * Phi(x), Phi the standard normal CDF written with erf */
 double oracle_gelu_erf(double x) { return 0.5 * x * (1.0 + erf(x / sqrt(2.0))); }
 
+/* The other activations that a fused epilogue may apply (activation kernels are one of the
+ * benchmark families of Section 5.2).  Each is its textbook definition:
+ *   ReLU       max(x, 0); a NaN stays a NaN
+ *   SiLU       x * sigmoid(x) = x / (1 + exp(-x))
+ *   GELU-tanh  x/2 * (1 + tanh( sqrt(2/pi) * (x + 0.044715 x^3) ))   (the tanh approximation of GELU) */
+double oracle_relu(double x) { return x != x ? x : (x > 0.0 ? x : 0.0); }
+double oracle_silu(double x) { return x / (1.0 + exp(-x)); }
+double oracle_gelu_tanh(double x) {
+    const double pi = 3.14159265358979323846;
+    return 0.5 * x * (1.0 + tanh(sqrt(2.0 / pi) * (x + 0.044715 * x * x * x)));
+}
+/* act applied to one value; unknown codes are the identity's responsibility of check_problem */
+double oracle_act(int act, double x) {
+    switch (act) {
+        case ORACLE_ACT_GELU_ERF: return oracle_gelu_erf(x);
+        case ORACLE_ACT_RELU: return oracle_relu(x);
+        case ORACLE_ACT_SILU: return oracle_silu(x);
+        case ORACLE_ACT_GELU_TANH: return oracle_gelu_tanh(x);
+        default: return x;
+    }
+}
+
 int oracle_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();
@@ -152,6 +174,7 @@ static int check_problem(const oracle_problem_t *p) {
     if (!p || p->M < 0 || p->N < 0 || p->K < 0) return 1;
     if ((p->M > 0 && p->K > 0 && !p->A) || (p->N > 0 && p->K > 0 && !p->B)) return 1;
     if (p->beta != 0.0 && !p->C) return 1;
+    if (p->act < ORACLE_ACT_NONE || p->act > ORACLE_ACT_GELU_TANH) return 1;
     return 0;
 }
 
@@ -178,8 +201,7 @@ static void element(const oracle_problem_t *p, int64_t i, int64_t j,
         pre += bj;
         m += fabs(bj);
     }
-    double out = pre;
-    if (p->act == ORACLE_ACT_GELU_ERF) out = oracle_gelu_erf(pre);
+    const double out = oracle_act(p->act, pre);
     if (ref) *ref = out;
     if (sumabs) *sumabs = sa;
     if (mag) *mag = m;

@@ -139,6 +139,56 @@ def test_gelu_inside_gemm():
         assert oracle.gemm_full(p)[0, 0] == oracle.gelu_erf(x + b)
 
 
+def test_relu_silu_gelu_tanh_closed_forms_and_library():
+    import math
+    import torch
+    relu = lambda x: oracle.act(oracle.ACT_RELU, x)
+    silu = lambda x: oracle.act(oracle.ACT_SILU, x)
+    gtanh = lambda x: oracle.act(oracle.ACT_GELU_TANH, x)
+    # ReLU: exact
+    for x in [0.0, 1.0, -1.0, 3.5, -3.5, 1e-30, -1e-30, 65504.0, -65504.0]:
+        assert relu(x) == (x if x > 0 else 0.0)
+    assert math.isnan(relu(float("nan")))
+    # SiLU: sigmoid(ln 3) = 3/4, sigmoid(ln 9) = 9/10, sigmoid(-ln 3) = 1/4 (closed forms), silu(0) = 0,
+    # silu(x) - silu(-x) = x, silu(x) -> x for large x and -> 0 for large -x
+    for r, sig in [(3.0, 0.75), (9.0, 0.9), (1.0 / 3.0, 0.25), (99.0, 0.99), (1.0, 0.5)]:
+        x = math.log(r)
+        assert abs(silu(x) - x * sig) < 1e-15 * max(1.0, abs(x))
+    for x in [0.1, 0.9, 2.5, 7.0, 30.0]:
+        assert abs((silu(x) - silu(-x)) - x) < 1e-15 * max(1.0, x)
+    assert silu(0.0) == 0.0 and silu(800.0) == 800.0 and abs(silu(-800.0)) < 1e-300
+    # GELU, tanh form: g(x) - g(-x) = x (tanh is odd), g(0) = 0, within 5e-4 of the exact (erf) GELU everywhere
+    # (the known quality of that approximation) and equal to it to 1e-6 relative for |x| < 0.01
+    for x in [0.1, 0.9, 2.5, 7.0]:
+        assert abs((gtanh(x) - gtanh(-x)) - x) < 1e-15 * max(1.0, x)
+    assert gtanh(0.0) == 0.0
+    worst = max(abs(gtanh(x) - oracle.gelu_erf(x)) for x in np.linspace(-8.0, 8.0, 3201))
+    assert 1e-4 < worst < 5e-4        # a different constant or a dropped cubic term leaves this window
+    for x in [1e-3, -5e-3, 9e-3]:
+        assert abs(gtanh(x) - oracle.gelu_erf(x)) < 1e-6 * abs(x)
+    # an independent library's routines, in fp64
+    xs = torch.tensor(np.concatenate([np.linspace(-12.0, 12.0, 2001), [1e-8, -1e-8, 40.0, -40.0]]), dtype=torch.float64)
+    for code, fn in [(oracle.ACT_RELU, torch.nn.functional.relu), (oracle.ACT_SILU, torch.nn.functional.silu),
+                     (oracle.ACT_GELU_TANH, lambda t: torch.nn.functional.gelu(t, approximate="tanh")),
+                     (oracle.ACT_GELU_ERF, torch.nn.functional.gelu)]:
+        want = fn(xs).numpy()
+        got = np.array([oracle.act(code, float(x)) for x in xs.numpy()])
+        assert np.all(np.abs(got - want) <= 4e-16 * np.maximum(1.0, np.abs(want))), code
+    assert oracle.act(oracle.ACT_NONE, -2.5) == -2.5
+
+
+def test_every_activation_inside_gemm():
+    # K=1, A=[x], B=[1] -> act(x + bias); an unknown activation code is an error
+    for code in (oracle.ACT_RELU, oracle.ACT_SILU, oracle.ACT_GELU_TANH, oracle.ACT_GELU_ERF, oracle.ACT_NONE):
+        for x, b in [(1.0, 0.0), (0.5, 0.5), (-2.0, 1.0), (-0.25, -0.5)]:
+            p = problem_from(np.array([[x]]), np.array([[1.0]]), F32, 0, 0,
+                             bias=np.array([b], np.float32), bias_dtype=F32, act=code)
+            assert oracle.gemm_full(p)[0, 0] == oracle.act(code, x + b)
+    p = problem_from(np.array([[1.0]]), np.array([[1.0]]), F32, 0, 0, act=7)
+    with pytest.raises(Exception):
+        oracle.gemm_full(p)
+
+
 # ---------------------------------------------------------------- closed forms of the product
 
 @pytest.mark.parametrize("dtype", DTYPES)

@@ -20,7 +20,7 @@ import torch
 
 # element type and activation codes of the C interface (values only; no shared header)
 F32, F16, BF16 = 0, 1, 2
-ACT_NONE, ACT_GELU_ERF = 0, 1
+ACT_NONE, ACT_GELU_ERF, ACT_RELU, ACT_SILU, ACT_GELU_TANH = 0, 1, 2, 3, 4
 
 _NP_BITS = {F32: np.float32, F16: np.uint16, BF16: np.uint16}
 _TORCH = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
