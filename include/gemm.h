@@ -45,8 +45,15 @@ typedef enum { GEMM_OP_N = 0, GEMM_OP_T = 1 } gemm_op_t;
 /* Element types: IEEE binary32, IEEE binary16, bfloat16 (upper half of a binary32). */
 typedef enum { GEMM_F32 = 0, GEMM_F16 = 1, GEMM_BF16 = 2 } gemm_dtype_t;
 
-/* GEMM_ACT_GELU_ERF is the exact GELU, x * Phi(x) = x/2 * (1 + erf(x / sqrt 2)). */
-typedef enum { GEMM_ACT_NONE = 0, GEMM_ACT_GELU_ERF = 1 } gemm_act_t;
+/* Activations of the fused epilogue (activation kernels are one of the benchmark families of
+ * Section 5.2 of the paper; fused here so that C is written once):
+ *   GEMM_ACT_GELU_ERF   the exact GELU, x * Phi(x) = x/2 * (1 + erf(x / sqrt 2))
+ *   GEMM_ACT_RELU       max(x, 0); a NaN stays a NaN
+ *   GEMM_ACT_SILU       x * sigmoid(x) = x / (1 + exp(-x))
+ *   GEMM_ACT_GELU_TANH  x/2 * (1 + tanh(sqrt(2/pi) * (x + 0.044715 x^3))) */
+typedef enum {
+    GEMM_ACT_NONE = 0, GEMM_ACT_GELU_ERF = 1, GEMM_ACT_RELU = 2, GEMM_ACT_SILU = 3, GEMM_ACT_GELU_TANH = 4
+} gemm_act_t;
 
 /*
  * Fused epilogue.  A NULL pointer passed to gemm_run means

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libgemm.so")
 GEMM_OK, GEMM_ERR_INVALID_ARG, GEMM_ERR_UNSUPPORTED, GEMM_ERR_ALLOC, GEMM_ERR_HIP = 0, 1, 2, 3, 4
 GEMM_OP_N, GEMM_OP_T = 0, 1
 GEMM_F32, GEMM_F16, GEMM_BF16 = 0, 1, 2
-GEMM_ACT_NONE, GEMM_ACT_GELU_ERF = 0, 1
+GEMM_ACT_NONE, GEMM_ACT_GELU_ERF, GEMM_ACT_RELU, GEMM_ACT_SILU, GEMM_ACT_GELU_TANH = 0, 1, 2, 3, 4
 GEMM_KERNEL_AUTO, GEMM_KERNEL_GENERAL, GEMM_KERNEL_MFMA_TILE, GEMM_KERNEL_SKINNY = 0, 1, 2, 3
 
 EXPORTED_SYMBOLS = (

@@ -7,7 +7,7 @@ namespace gemm {
 
 // numeric codes of the public enums (include/gemm.h)
 enum : int { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
-enum : int { ACT_NONE = 0, ACT_GELU_ERF = 1 };
+enum : int { ACT_NONE = 0, ACT_GELU_ERF = 1, ACT_RELU = 2, ACT_SILU = 3, ACT_GELU_TANH = 4 };
 
 struct Args {
     int64_t M, N, K;
@@ -83,7 +83,51 @@ __device__ __forceinline__ float gelu_erf(float x) {
     return 0.5f * x * (1.0f + erf_z);
 }
 
-__device__ __forceinline__ float apply_act(float x, int act) { return act == ACT_GELU_ERF ? gelu_erf(x) : x; }
+// max(x, 0) that keeps a NaN
+__device__ __forceinline__ float relu(float x) { return (x > 0.0f || x != x) ? x : 0.0f; }
+
+// x * sigmoid(x) = x / (1 + exp(-x)); exp(-x) overflows to +inf for x < -88 and the quotient
+// becomes -0, the limit
+__device__ __forceinline__ float silu(float x) {
+    const float e = __builtin_amdgcn_exp2f(-x * 1.44269504088896340736f);
+    return x * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+// x/2 * (1 + tanh(u)), u = sqrt(2/pi) * (x + 0.044715 x^3), with tanh(u) = 1 - 2 / (1 + exp(2u)):
+// one exponential and one reciprocal, saturating correctly at both ends; the cancellation near
+// u = 0 costs absolute, not relative, accuracy of tanh and 1 + tanh(u) is near 1 there
+__device__ __forceinline__ float gelu_tanh(float x) {
+    const float u = 0.7978845608028654f * fmaf(0.044715f * x * x, x, x);
+    const float e = __builtin_amdgcn_exp2f(u * 2.88539008177792681472f);
+    const float t = fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + e), 1.0f);
+    return 0.5f * x * (1.0f + t);
+}
+
+__device__ __forceinline__ float apply_act(float x, int act) {
+    switch (act) {
+        case ACT_GELU_ERF: return gelu_erf(x);
+        case ACT_RELU: return relu(x);
+        case ACT_SILU: return silu(x);
+        case ACT_GELU_TANH: return gelu_tanh(x);
+        default: return x;
+    }
+}
+
+// the activation applied to G vectors of four values, the (wave-uniform) choice made once
+template <int G>
+__device__ __forceinline__ void apply_act4(f32x4 (&s)[G], int act) {
+#define GEMM_ACT_LOOP(F)                    \
+    _Pragma("unroll") for (int g = 0; g < G; ++g) \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) s[g][e] = F(s[g][e])
+    switch (act) {
+        case ACT_GELU_ERF: GEMM_ACT_LOOP(gelu_erf); break;
+        case ACT_RELU: GEMM_ACT_LOOP(relu); break;
+        case ACT_SILU: GEMM_ACT_LOOP(silu); break;
+        case ACT_GELU_TANH: GEMM_ACT_LOOP(gelu_tanh); break;
+        default: break;
+    }
+#undef GEMM_ACT_LOOP
+}
 
 // Everything after the contraction, for one element: act(alpha*acc + beta*C_in + bias_j).
 // c_in and bias_j are passed already widened; beta == 0 callers pass c_in = 0 without loading it.

@@ -144,7 +144,7 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
     else epi = gemm_epilogue_t{dtype, nullptr, dtype, GEMM_ACT_NONE};
     if (!valid_dtype(epi.out_dtype)) return GEMM_ERR_INVALID_ARG;
     if (epi.bias && !valid_dtype(epi.bias_dtype)) return GEMM_ERR_INVALID_ARG;
-    if (epi.act != GEMM_ACT_NONE && epi.act != GEMM_ACT_GELU_ERF) return GEMM_ERR_INVALID_ARG;
+    if ((int)epi.act < (int)GEMM_ACT_NONE || (int)epi.act > (int)GEMM_ACT_GELU_TANH) return GEMM_ERR_INVALID_ARG;
     const int64_t a_cols = transA == GEMM_OP_N ? K : M, b_cols = transB == GEMM_OP_N ? N : K;
     if (lda < (a_cols > 1 ? a_cols : 1) || ldb < (b_cols > 1 ? b_cols : 1) || ldc < (N > 1 ? N : 1)) return GEMM_ERR_INVALID_ARG;
     if (M > 0 && N > 0 && !C) return GEMM_ERR_INVALID_ARG;

@@ -307,12 +307,7 @@ __device__ __forceinline__ void tile_epilogue_bands(Dump dump, char* lds, const 
 #pragma unroll
                         for (int g = 0; g < GROUP; ++g) s[g] = alpha * s[g] + bias4;
                     }
-                    if (act == ACT_GELU_ERF) {
-#pragma unroll
-                        for (int g = 0; g < GROUP; ++g)
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) s[g][e] = gelu_erf(s[g][e]);
-                    }
+                    apply_act4(s, act);
 #pragma unroll
                     for (int g = 0; g < GROUP; ++g) OV::store4(p0 + (it0 + g) * step, s[g]);
                 }

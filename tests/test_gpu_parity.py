@@ -183,6 +183,52 @@ def test_skinny_fp16_gelu(handle):
     check_full(cfg, inp, p.result_bits(), "skinny fp16 gelu")
 
 
+# ------------------------------------------------------------------ every activation through every kernel family
+
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_SILU, wl.ACT_GELU_TANH, wl.ACT_GELU_ERF])
+def test_activations_in_every_kernel_family(handle, act):
+    # pre-activation values of order 1 on both sides of zero (bias shifts a third of the columns far negative
+    # and far positive, where the activations saturate)
+    cases = [
+        ("tile", base_cfg(300, 520, 192, 0, 1, wl.BF16, wl.BF16, alpha=0.25, beta=0.5, a_dist=("normal", 1.0),
+                          b_dist=("normal", 0.3), c_dist=("normal", 1.0), bias_dist=("normal", 4.0), bias_dtype=wl.F32, act=act),
+         lg.GEMM_KERNEL_MFMA_TILE),
+        ("tile fp32 out", base_cfg(264, 264, 96, 0, 0, wl.F16, wl.F32, a_dist=("normal", 1.0), b_dist=("normal", 0.2),
+                                   bias_dist=("normal", 2.0), bias_dtype=wl.F16, act=act), lg.GEMM_KERNEL_MFMA_TILE),
+        ("skinny", base_cfg(8, 512, 1024, 0, 0, wl.BF16, wl.BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.05),
+                            bias_dist=("normal", 2.0), bias_dtype=wl.BF16, act=act), lg.GEMM_KERNEL_SKINNY),
+        ("general", base_cfg(37, 29, 53, 1, 0, wl.F32, wl.F32, bias_dist=("normal", 2.0), bias_dtype=wl.F32, act=act),
+         lg.GEMM_KERNEL_GENERAL),
+    ]
+    for name, cfg, family in cases:
+        inp = wl.make_inputs(cfg, 40 + act)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        assert lg.gemm_get_last_plan(handle)[0] == family, name
+        check_full(cfg, inp, p.result_bits(), f"{name} act {act}")
+
+
+def test_relu_keeps_nan_and_is_exact(handle):
+    # integer data: the pre-activation values are exact, so ReLU's output is unique
+    cfg = base_cfg(264, 520, 160, 0, 1, wl.BF16, wl.F32, alpha=1.0, beta=0.0, act=wl.ACT_RELU)
+    inp, _ = wl.make_integer_inputs(cfg, 5, -3, 3)
+    want = oracle.decode(wl.F32, expected_bits_exact(cfg, inp))
+    p = DeviceProblem(cfg, inp)
+    p.run(handle)
+    got = decode_c(cfg, p.result_bits())
+    assert np.array_equal(got, want) and (want == 0).mean() > 0.3 and (want > 0).mean() > 0.3
+
+
+def test_unknown_activation_is_rejected(handle):
+    cfg = base_cfg(64, 64, 64, 0, 1)
+    inp = wl.make_inputs(cfg, 1)
+    p = DeviceProblem(cfg, inp)
+    epi = lg.make_epilogue(cfg.out_dtype, act=9)
+    st = lg.gemm_run(handle, cfg.M, cfg.N, cfg.K, 0, 1, cfg.dtype, 1.0, p.A.data_ptr(), cfg.ld_a(), p.B.data_ptr(), cfg.ld_b(),
+                     0.0, p.C.data_ptr(), cfg.ld_c(), epi, stream_ptr(), check=False)
+    assert st == lg.GEMM_ERR_INVALID_ARG
+
+
 # ------------------------------------------------------------------ general kernel: any shape, any alignment
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.F16, wl.BF16])
