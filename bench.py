@@ -174,7 +174,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--configs", default="C3,C5,C2,C4,C1", help="first one is the headline workload")
+    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5",
+                    help="first one is the headline workload; X* are the further shapes of workloads.EXTRA_CONFIGS")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true")
@@ -214,7 +215,7 @@ def main():
     results = {}
     headline = None
     for idx, name in enumerate(names):
-        cfg = wl.CONFIGS[name]
+        cfg = wl.CONFIGS[name] if name in wl.CONFIGS else wl.EXTRA_CONFIGS[name]
         bound = "hbm" if classify(cfg) != "compute-bound" else "mfma"
         res = Resident(cfg, seed, copies=2 if bound == "hbm" and cfg.algorithmic_bytes() > (64 << 20) else 1)
         ok = None if args.no_verify else quick_verify(res, lg, handle)

@@ -131,7 +131,13 @@ typedef enum {
 typedef struct {
     gemm_kernel_t kernel;   /* which family */
     int32_t variant;        /* tile variant index within the family; -1 = automatic */
-    int32_t split_k;        /* number of K slices; 0 = automatic, 1 = none */
+    int32_t split_k;        /* number of K slices; 0 = automatic, 1 = none.  Skinny family: every
+                             * column group is cut into that many slices.  Macro-tile family: only
+                             * the tiles of the last, partly filled round of workgroups (all tiles
+                             * when there are fewer tiles than compute units) are cut, each into
+                             * that many shares of the k range; variants that cannot do so make
+                             * the call return GEMM_ERR_UNSUPPORTED.  Slices are added in a fixed
+                             * order: results do not vary from run to run. */
 } gemm_plan_t;
 
 /* Forces the plan used by later gemm_run calls on this handle; a NULL plan restores automatic

@@ -148,7 +148,16 @@ const TileVariantInfo* tile_variant_info(int variant);
 bool tile_supports(const Args& a);
 // further preconditions of one variant (beyond tile_supports)
 bool tile_variant_supports(const Args& a, int variant);
-hipError_t launch_tile(const Args& a, int variant, int group_m, hipStream_t stream);
+// Split of the trailing tiles along K.  Tiles are numbered in launch order; those with number >=
+// first_tile are computed by `parts` workgroups each, every one over a contiguous share of the k
+// slabs, which write raw fp32 partial tiles to `partials` ([tile - first_tile][part][BM][BN]);
+// launch_tile_split_reduce then adds the parts in order and applies the epilogue.  parts <= 1
+// means no split.  It serves grids that fill only a fraction of the last round of workgroups
+// (or of the only one).
+struct TileSplit { int first_tile; int parts; float* partials; };
+bool tile_variant_splits(int variant);
+hipError_t launch_tile(const Args& a, int variant, int group_m, const TileSplit& split, hipStream_t stream);
+hipError_t launch_tile_split_reduce(const Args& a, int variant, int group_m, const TileSplit& split, hipStream_t stream);
 
 bool skinny_supports(const Args& a);
 // bytes of fp32 workspace the skinny kernel needs for this split factor (0 when split_k == 1)

@@ -22,15 +22,48 @@ using gemm::Args;
 
 bool valid_dtype(int d) { return d == GEMM_F32 || d == GEMM_F16 || d == GEMM_BF16; }
 
-// Picks a tile variant for the macro-tile family: the large direct-to-LDS tile on the 16x16x32
-// MFMA when it still yields enough workgroups to occupy the compute units (its register-staged
-// sibling when an operand is too large for the direct loads' masking offset), the small tile
-// otherwise.
-constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant = 3;
-int choose_tile_variant(const Args& a, int num_cus) {
-    const int64_t big = ((a.M + 255) / 256) * ((a.N + 255) / 256);
-    if (big * 2 >= num_cus) return gemm::tile_variant_supports(a, kLargeTileVariant) ? kLargeTileVariant : kLargeTileFallback;
-    return kSmallTileVariant;
+// Picks a tile variant for the macro-tile family by comparing two estimates of the run time, in
+// units of "one 128x128xK block on one compute unit at the large tile's speed".  The 256x256 tile
+// (16x16x32 MFMA, direct-to-LDS) does four blocks per workgroup, one workgroup per compute unit;
+// the 128x128 tile does one block per workgroup at 0.62 of that speed per compute unit (measured
+// on 8192^3: 890 against 1440 TFLOP/s).  Rounds are counted per compute unit, so a grid that
+// leaves most of the chip idle, or a dimension of 128 that would waste half of every large tile,
+// favours the small tile.  Operands of 2 GiB or more take the register-staged siblings (the
+// direct loads mask lanes with a fixed 2 GiB - 16 offset).
+constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant = 5, kSmallTileFallback = 3;
+constexpr double kSmallTileRelativeSpeed = 0.62;
+// A last round that fills less than this fraction of the compute units is split along K (when the
+// variant can): each of its tiles goes to several workgroups, each over a share of the k slabs of
+// at least kMinSlabsPerPart, and a second kernel adds the parts.  The split costs a round trip of
+// the partial tiles through memory and a launch, estimated at kSplitOverhead blocks.
+constexpr double kSplitBelow = 0.6, kSplitOverhead = 0.5;
+constexpr int kMaxParts = 16, kMinSlabsPerPart = 16;
+
+// parts per tile of the trailing `tail` tiles (1 = no split)
+int tail_parts(int64_t tail, int64_t cus, int64_t K) {
+    if (tail <= 0 || (double)tail >= kSplitBelow * (double)cus) return 1;
+    int64_t parts = cus / tail;
+    const int64_t slabs = (K + 31) / 32;
+    if (parts > slabs / kMinSlabsPerPart) parts = slabs / kMinSlabsPerPart;
+    if (parts > kMaxParts) parts = kMaxParts;
+    return parts < 2 ? 1 : (int)parts;
+}
+
+struct TileChoice { int variant; int first_split_tile; int parts; };
+TileChoice choose_tile(const Args& a, int num_cus) {
+    const int64_t cus = num_cus > 0 ? num_cus : 256;
+    const int64_t large = ((a.M + 255) / 256) * ((a.N + 255) / 256), small = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+    const bool large_ok = gemm::tile_variant_supports(a, kLargeTileVariant);
+    const int64_t tail = large % cus;
+    const int parts = large_ok ? tail_parts(tail, cus, a.K) : 1;
+    double t_large = 4.0 * (double)(large / cus);
+    if (tail) t_large += parts > 1 ? 4.0 / parts + kSplitOverhead : 4.0;
+    const double t_small = (double)((small + cus - 1) / cus) / kSmallTileRelativeSpeed;
+    if (t_large <= t_small) {
+        if (!large_ok) return TileChoice{kLargeTileFallback, 0, 1};
+        return TileChoice{kLargeTileVariant, (int)(large - tail), parts};
+    }
+    return TileChoice{gemm::tile_variant_supports(a, kSmallTileVariant) ? kSmallTileVariant : kSmallTileFallback, 0, 1};
 }
 
 gemm_status_t ensure_workspace(gemm_handle_s* h, size_t bytes, hipStream_t stream) {
@@ -164,6 +197,7 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
 
     // ---- plan ----
     gemm_plan_t plan{GEMM_KERNEL_GENERAL, 0, 1};
+    int split_first = -1;          // first tile of a split trailing round (macro-tile family)
     const bool product = (K > 0 && alpha != 0.0f);
     if (!product) {
         plan = gemm_plan_t{GEMM_KERNEL_GENERAL, 0, 1};      // only the epilogue is left
@@ -171,9 +205,22 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
         plan = h->plan;
         if (plan.kernel == GEMM_KERNEL_MFMA_TILE) {
             if (!gemm::tile_supports(a)) return GEMM_ERR_UNSUPPORTED;
-            if (plan.variant < 0) plan.variant = choose_tile_variant(a, h->num_cus);
+            if (plan.variant < 0) {
+                const TileChoice c = choose_tile(a, h->num_cus);
+                plan.variant = c.variant;
+                if (plan.split_k == 0) { plan.split_k = c.parts; split_first = c.first_split_tile; }
+            }
             if (!gemm::tile_variant_supports(a, plan.variant)) return GEMM_ERR_UNSUPPORTED;
-            plan.split_k = 1;
+            if (plan.split_k < 1) plan.split_k = 1;
+            if (plan.split_k > 1 && !gemm::tile_variant_splits(plan.variant)) return GEMM_ERR_UNSUPPORTED;
+            if (plan.split_k > 1 && split_first < 0) {
+                // a forced split applies to the trailing partial round, or to every tile of a grid smaller than one round
+                const gemm::TileVariantInfo* info = gemm::tile_variant_info(plan.variant);
+                const int64_t tiles = ((a.M + info->BM - 1) / info->BM) * ((a.N + info->BN - 1) / info->BN);
+                const int64_t cus = h->num_cus > 0 ? h->num_cus : 256;
+                split_first = (int)(tiles - tiles % cus);
+                if (split_first == tiles) plan.split_k = 1;
+            }
         } else if (plan.kernel == GEMM_KERNEL_SKINNY) {
             if (!gemm::skinny_supports(a)) return GEMM_ERR_UNSUPPORTED;
             plan.variant = 0;
@@ -187,7 +234,9 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
         if (gemm::skinny_supports(a) && N >= 256 && K >= 512) {
             plan = gemm_plan_t{GEMM_KERNEL_SKINNY, 0, gemm::skinny_default_split(a, h->num_cus)};
         } else if (gemm::tile_supports(a)) {
-            plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, choose_tile_variant(a, h->num_cus), 1};
+            const TileChoice c = choose_tile(a, h->num_cus);
+            plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, c.variant, c.parts};
+            split_first = c.first_split_tile;
         }
     }
 
@@ -203,7 +252,21 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
         }
         e = gemm::launch_skinny(a, plan.split_k, h->workspace, stream);
     } else if (plan.kernel == GEMM_KERNEL_MFMA_TILE) {
-        e = gemm::launch_tile(a, plan.variant, 8, stream);
+        gemm::TileSplit split{0, 1, nullptr};
+        if (plan.split_k > 1) {
+            const int64_t slabs = (K + 31) / 32;
+            if (plan.split_k > slabs) plan.split_k = (int)slabs;
+        }
+        if (plan.split_k > 1) {
+            const gemm::TileVariantInfo* info = gemm::tile_variant_info(plan.variant);
+            const int64_t tiles = ((a.M + info->BM - 1) / info->BM) * ((a.N + info->BN - 1) / info->BN);
+            const size_t need = (size_t)(tiles - split_first) * plan.split_k * info->BM * info->BN * sizeof(float);
+            const gemm_status_t st = ensure_workspace(h, need, stream);
+            if (st != GEMM_OK) return st;
+            split = gemm::TileSplit{split_first, plan.split_k, h->workspace};
+        }
+        e = gemm::launch_tile(a, plan.variant, 8, split, stream);
+        if (e == hipSuccess && split.parts > 1) e = gemm::launch_tile_split_reduce(a, plan.variant, 8, split, stream);
     } else {
         e = gemm::launch_general(a, stream);
     }

@@ -1,16 +1,16 @@
 // Table of macro-tile variants and the preconditions of the family.
-#include "common.hpp"
+#include "tile_kernel.hpp"
 
 namespace gemm {
 
 #define GEMM_TILE_VARIANT(IDX, NAME, KIND, BM, BN, BK, WM, WN, NS) \
-    hipError_t launch_tile_variant_##IDX(const Args& a, int group_m, hipStream_t stream);
+    hipError_t launch_tile_variant_##IDX(const Args& a, int group_m, const TileSplit& split, hipStream_t stream);
 #include "tile_variants.def"
 #undef GEMM_TILE_VARIANT
 
 namespace {
 
-typedef hipError_t (*launch_fn)(const Args&, int, hipStream_t);
+typedef hipError_t (*launch_fn)(const Args&, int, const TileSplit&, hipStream_t);
 
 const TileVariantInfo kInfo[] = {
 #define GEMM_TILE_VARIANT(IDX, NAME, KIND, BM, BN, BK, WM, WN, NS) {NAME, BM, BN, BK, (WM) * (WN) * 64, KIND},
@@ -59,9 +59,50 @@ bool tile_variant_supports(const Args& a, int variant) {
     return a_bytes < 0x7ffffff0ll && b_bytes < 0x7ffffff0ll;
 }
 
-hipError_t launch_tile(const Args& a, int variant, int group_m, hipStream_t stream) {
+bool tile_variant_splits(int variant) { return variant >= 0 && variant < kNum && kInfo[variant].kind == 3; }
+
+hipError_t launch_tile(const Args& a, int variant, int group_m, const TileSplit& split, hipStream_t stream) {
     if (variant < 0 || variant >= kNum) return hipErrorInvalidValue;
-    return kLaunch[variant](a, group_m < 1 ? 1 : group_m, stream);
+    if (split.parts > 1 && !tile_variant_splits(variant)) return hipErrorInvalidValue;
+    return kLaunch[variant](a, group_m < 1 ? 1 : group_m, split, stream);
+}
+
+namespace {
+
+// Adds the partial tiles of a split in the order of their k shares and applies the epilogue:
+// one thread per four consecutive columns of a tile row.
+__global__ __launch_bounds__(256) void tile_split_reduce_kernel(Args a, int tiles_m, int tiles_n, int group_m, int first_tile,
+                                                                int parts, const float* partials, int BM, int BN) {
+    int tm, tn;
+    tile::tile_of_workgroup(first_tile + (int)blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
+    const int idx = (int)blockIdx.y * 256 + (int)threadIdx.x;          // one of BM * BN / 4 vectors
+    const int r = idx / (BN / 4), c = (idx % (BN / 4)) * 4;
+    const int64_t row = (int64_t)tm * BM + r, col = (int64_t)tn * BN + c;
+    if (row >= a.M || col >= a.N) return;
+    const float* p = partials + ((size_t)blockIdx.x * parts) * BM * BN + (size_t)r * BN + c;
+    f32x4 s = *(const f32x4*)p;
+    for (int q = 1; q < parts; ++q) s += *(const f32x4*)(p + (size_t)q * BM * BN);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (col + e >= a.N) break;
+        const int64_t ci = row * a.ldc + col + e;
+        const float c_in = a.beta != 0.0f ? load_elem(a.C, a.out_dtype, ci) : 0.0f;
+        const float bj = a.bias ? load_elem(a.bias, a.bias_dtype, col + e) : 0.0f;
+        store_elem(a.C, a.out_dtype, ci, epilogue_value(s[e], a.alpha, a.beta, c_in, bj, a.act));
+    }
+}
+
+}  // namespace
+
+hipError_t launch_tile_split_reduce(const Args& a, int variant, int group_m, const TileSplit& split, hipStream_t stream) {
+    if (variant < 0 || variant >= kNum || split.parts <= 1) return hipErrorInvalidValue;
+    const int BM = kInfo[variant].BM, BN = kInfo[variant].BN;
+    const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
+    const int tail = tiles_m * tiles_n - split.first_tile;
+    if (tail <= 0) return hipSuccess;
+    hipLaunchKernelGGL(tile_split_reduce_kernel, dim3((unsigned)tail, (unsigned)(BM * BN / 4 / 256)), dim3(256), 0, stream, a,
+                       tiles_m, tiles_n, group_m < 1 ? 1 : group_m, split.first_tile, split.parts, (const float*)split.partials, BM, BN);
+    return hipGetLastError();
 }
 
 }  // namespace gemm

@@ -110,8 +110,13 @@ __device__ __forceinline__ void wait_raw8(Frag16Raw (&r)[8]) {
 // Loads complete in order, so the barrier's wait counts the younger ones that may stay in
 // flight: two slabs in the ring of 4; in the ring of 5 the next pair (even step) or its first
 // half (odd step).
+//
+// Tiles numbered >= split_first are computed by split_parts workgroups each (see TileSplit): such
+// a workgroup runs the same pipeline over its share of the k slabs and stores its accumulators,
+// unscaled, as an fp32 tile in `partials`.
 template <class C, bool IS_BF16, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok) {
+__global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok,
+                                                           int split_first, int split_parts, float* partials) {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NT, NS = C::NS;
     constexpr int TM = C::WTM / 16, TN = C::WTN / 16;        // 16x16 accumulators per wave
     static_assert(TM == 8 && TN == 8, "the slot plan below is written for a 128x128 wave sub-block");
@@ -128,10 +133,21 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % C::WM, wn = wave / C::WM;
 
+    int pid = (int)blockIdx.x, part = -1;
+    if (pid >= split_first) {
+        const int r = pid - split_first;
+        part = r % split_parts;
+        pid = split_first + r / split_parts;
+    }
     int tm, tn;
-    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
+    tile_of_workgroup(pid, tiles_m, tiles_n, group_m, tm, tn);
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-    const int K = (int)a.K;
+    // this workgroup's share of the k slabs: [slab0, slab0 + k_tiles), K counted from slab0
+    const int all_tiles = (int)((a.K + BK - 1) / BK);
+    // (shares start at even slabs, so that paired requests still cover whole cache lines)
+    const int slab0 = part <= 0 ? 0 : (int)((int64_t)part * all_tiles / split_parts) & ~1;
+    const int slab1 = (part < 0 || part == split_parts - 1) ? all_tiles : (int)((int64_t)(part + 1) * all_tiles / split_parts) & ~1;
+    const int K = (int)a.K - slab0 * BK;
 
     using LA = typename std::conditional<A_KC, DmaKC<BM, BK, NT, false>, DmaMC<BM, BK, NT>>::type;
     using LB = typename std::conditional<B_KC, DmaKC<BN, BK, NT, false>, DmaMC<BN, BK, NT>>::type;
@@ -142,9 +158,9 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     LB lb;
     la.init(tid, a.lda);
     lb.init(tid, a.ldb);
-    const char* pa = LA::tile_base(a.A, m0, a.lda);
-    const char* pb = LB::tile_base(a.B, n0, a.ldb);
     const int64_t a_step = LA::k_step_bytes(a.lda), b_step = LB::k_step_bytes(a.ldb);
+    const char* pa = LA::tile_base(a.A, m0, a.lda) + slab0 * a_step;
+    const char* pb = LB::tile_base(a.B, n0, a.ldb) + slab0 * b_step;
     const int64_t a_bytes = LA::total_bytes(a.M, a.K, a.lda) - (pa - (const char*)a.A);
     const int64_t b_bytes = LB::total_bytes(a.N, a.K, a.ldb) - (pb - (const char*)a.B);
 
@@ -163,8 +179,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-    const int k_tiles = (K + BK - 1) / BK;
-    const int full_tiles = K / BK;
+    const int k_tiles = slab1 - slab0;
+    const int full_tiles = K / BK < k_tiles ? K / BK : k_tiles;
     constexpr int NM = TM * TN, NR = TM + TN;     // MFMAs and fragments per step
     constexpr int LPT = LA::L + LB::L;            // loads per thread and slab (= per half of a pair)
 
@@ -341,6 +357,15 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 #undef GEMM_WAIT_VM_BARRIER
 
+    // a share of a split tile goes, as it is, to its fp32 tile among the partials
+    Args e = a;
+    int64_t em0 = m0, en0 = n0;
+    if (part >= 0) {
+        e.C = partials + ((size_t)(pid - split_first) * split_parts + part) * (BM * BN);
+        e.ldc = BN; e.M = BM; e.N = BN;
+        e.out_dtype = DT_F32; e.alpha = 1.0f; e.beta = 0.0f; e.bias = nullptr; e.act = ACT_NONE;
+        em0 = 0; en0 = 0; c_vec_ok = 1;
+    }
     // accumulator register v of lane l: row 4*(l/16) + v, column l%16 of its 16x16 tile
     const int c16 = lane & 15, g4 = lane >> 4;
     tile_epilogue_bands<C>(
@@ -354,18 +379,22 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
                     for (int v = 0; v < 4; ++v)
                         *(float*)(region + ((16 * i2 + 4 * g4 + v) * EL::RS + j * 16 + c16) * 4) = acc[2 * b + i2][j][v];
         },
-        lds, a, m0, n0, c_vec_ok);
+        lds, e, em0, en0, c_vec_ok);
 }
 
 template <class C>
-hipError_t launch_dma16_variant(const Args& a, int group_m, hipStream_t stream) {
+hipError_t launch_dma16_variant(const Args& a, int group_m, const TileSplit& split, hipStream_t stream) {
     const int tiles_m = (int)((a.M + C::BM - 1) / C::BM), tiles_n = (int)((a.N + C::BN - 1) / C::BN);
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(C::NT);
+    const int tiles = tiles_m * tiles_n;
+    const bool splits = split.parts > 1 && split.first_tile < tiles;
+    const int split_first = splits ? split.first_tile : tiles, split_parts = splits ? split.parts : 1;
+    const dim3 grid((unsigned)(split_first + (tiles - split_first) * split_parts)), block(C::NT);
     const bool bf = a.dtype == DT_BF16;
     const bool akc = !a.transA, bkc = a.transB != 0;
     const int c_vec_ok = (a.ldc % 4 == 0) && ((uintptr_t)a.C % (a.out_dtype == DT_F32 ? 16 : 8) == 0);
 #define GEMM_TILE_LAUNCH(BF, AKC, BKC) \
-    hipLaunchKernelGGL((tile_dma16_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok)
+    hipLaunchKernelGGL((tile_dma16_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok, \
+                       split_first, split_parts, split.partials)
     if (bf) {
         if (akc && bkc) GEMM_TILE_LAUNCH(true, true, true);
         else if (akc && !bkc) GEMM_TILE_LAUNCH(true, true, false);

@@ -14,7 +14,9 @@ from gpu_harness import DeviceProblem, check_sampled, decode_c, oracle_problem
 
 pytestmark = pytest.mark.gpu
 
-FULL = ["C2", "C3", "C4", "C5"]
+FULL = ["C2", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5"]
+ALL = {**wl.CONFIGS, **wl.EXTRA_CONFIGS}
+SKINNY = ("C5", "X5")
 
 
 @pytest.fixture(scope="module")
@@ -31,7 +33,7 @@ def dense(cfg, storage, shape, ld):
 
 @pytest.mark.parametrize("name", FULL)
 def test_sampled_against_oracle(handle, name):
-    cfg = wl.CONFIGS[name]
+    cfg = ALL[name]
     print(f"{name}: generating inputs", flush=True)
     inp = wl.make_inputs(cfg)
     p = DeviceProblem(cfg, inp)
@@ -40,7 +42,7 @@ def test_sampled_against_oracle(handle, name):
     bits = p.result_bits()
     kernel, variant, split = lg.gemm_get_last_plan(handle)
     print(f"{name}: plan kernel={kernel} variant={variant} split={split}; oracle on the sample", flush=True)
-    expected_kernel = lg.GEMM_KERNEL_SKINNY if name == "C5" else lg.GEMM_KERNEL_MFMA_TILE
+    expected_kernel = lg.GEMM_KERNEL_SKINNY if name in SKINNY else lg.GEMM_KERNEL_MFMA_TILE
     assert kernel == expected_kernel
     check_sampled(cfg, inp, bits, wl.DEFAULT_SEED, name)
     # same call again on the same data: same bits
@@ -55,7 +57,7 @@ def test_integer_exact_with_full_coverage(handle, name):
     """Entries in {-1, 0, 1}: every partial sum is an exact integer below 2^24, so C is unique.
     With fp32 output, C r = A (B r) and r^T C = (r^T A) B must hold EXACTLY for sign vectors r
     (int64 arithmetic on the host, O(MK + KN + MN)); each output element takes part in both."""
-    cfg = wl.scaled(wl.CONFIGS[name], out_dtype=wl.F32, act=wl.ACT_NONE, bias_dist=None)
+    cfg = wl.scaled(ALL[name], out_dtype=wl.F32, act=wl.ACT_NONE, bias_dist=None)
     inp, vals = wl.make_integer_inputs(cfg, 2024, -1, 1)
     p = DeviceProblem(cfg, inp)
     p.run(handle)
@@ -81,7 +83,7 @@ def test_integer_exact_with_full_coverage(handle, name):
 
 @pytest.mark.parametrize("name", FULL)
 def test_all_ones_gives_k(handle, name):
-    cfg = wl.scaled(wl.CONFIGS[name], act=wl.ACT_NONE, bias_dist=None)
+    cfg = wl.scaled(ALL[name], act=wl.ACT_NONE, bias_dist=None)
     one = lambda shape, ld, dt: wl.to_bits(np.ones(shape[0] * ld, np.float32), dt)
     inp = {"A": one(cfg.a_shape(), cfg.ld_a(), cfg.dtype), "B": one(cfg.b_shape(), cfg.ld_b(), cfg.dtype),
            "C": one((cfg.M, cfg.N), cfg.ld_c(), cfg.out_dtype) if cfg.beta != 0.0 else None, "bias": None}

@@ -106,6 +106,38 @@ def test_tile_variants_every_small_slab_count(handle, ta, tb):
     lg.gemm_set_plan(handle)
 
 
+@pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0), (1, 1), (1, 0)])
+def test_tile_split_of_the_trailing_round(handle, ta, tb):
+    # nine 256x256 tiles, fewer than compute units: a forced split cuts every tile's k range into shares
+    # whose fp32 partial tiles a second kernel adds (in order) before the epilogue; integer data -> exact.
+    # K = 1096 leaves a partial last slab in the last share; parts = 5 gives shares of unequal length,
+    # parts = 64 more shares than the 35 slabs (clamped)
+    M, N, K = 520, 584, 1096
+    cfg = base_cfg(M, N, K, ta, tb, wl.BF16, wl.BF16, alpha=2.0, beta=-1.0, bias_dist=("normal", 1.0), bias_dtype=wl.F32,
+                   act=wl.ACT_RELU, ldc=N + 5)
+    inp, _ = wl.make_integer_inputs(cfg, 78, -2, 2)
+    want = oracle.decode(wl.BF16, expected_bits_exact(cfg, inp))
+    splitting = [v for v in range(num_tile_variants()) if "dma16" in lg.gemm_variant_name(lg.GEMM_KERNEL_MFMA_TILE, v)]
+    assert splitting
+    for v in splitting:
+        for parts in (2, 5, 64):
+            print(f"split variant {v} parts {parts} ta={ta} tb={tb}", flush=True)
+            lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v, parts)
+            p = DeviceProblem(cfg, inp)
+            p.run(handle)
+            kernel, variant, used = lg.gemm_get_last_plan(handle)
+            assert (kernel, variant) == (lg.GEMM_KERNEL_MFMA_TILE, v) and used == min(parts, 35)
+            got = decode_c(cfg, p.result_bits())
+            assert np.array_equal(got, want), f"variant {v} parts {parts}: {np.sum(got != want)} wrong elements"
+            pad_got = p.result_bits()[:-1, cfg.N:]
+            assert np.array_equal(pad_got, inp["C"].reshape(M, cfg.ld_c())[:-1, cfg.N:])
+    # a variant that cannot split refuses
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, 4, 2)
+    p = DeviceProblem(cfg, inp)
+    assert p.run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED
+    lg.gemm_set_plan(handle)
+
+
 def test_tile_epilogue_bias_gelu_beta(handle):
     M, N, K = 300, 392, 256
     cfg = base_cfg(M, N, K, 0, 1, wl.BF16, wl.BF16, alpha=0.5, beta=1.5, a_dist=("normal", 1.0),

@@ -123,6 +123,29 @@ CONFIGS: Dict[str, Config] = {
                  note="bf16 32x16384x16384 NN skinny, alpha=beta=1, bf16 in/out"),
 }
 
+# Further shapes in the categories the paper's case study names (Section 5.4: square, transposed
+# and irregular GEMM; Section 5.3 uses GEMV as its memory-bound kernel): the remaining operand
+# layouts, sizes that are no multiple of any tile, a tall-and-narrow product and a single-row one.
+# Reported by the bench next to the five main configurations, never as its headline.
+EXTRA_CONFIGS: Dict[str, Config] = {
+    "X1": Config("X1", 8192, 8192, 8192, 1, 0, BF16, BF16,
+                 a_dist=("normal", 8192 ** -0.5), b_dist=("normal", 8192 ** -0.5),
+                 note="bf16 8192^3 TN (A stored K x M), bf16 out"),
+    "X2": Config("X2", 4096, 4096, 4096, 1, 1, F16, F16,
+                 a_dist=("normal", 1.0), b_dist=("normal", 4096 ** -0.5),
+                 note="fp16 4096^3 TT, fp16 out"),
+    "X3": Config("X3", 8000, 8200, 8136, 0, 1, BF16, BF16,
+                 a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                 bias_dist=("normal", 0.5), bias_dtype=F32, act=ACT_SILU,
+                 note="bf16 8000x8200x8136 NT (no multiple of a tile, partial last k slab) + bias + SiLU"),
+    "X4": Config("X4", 65536, 128, 4096, 0, 0, BF16, BF16,
+                 a_dist=("normal", 1.0), b_dist=("normal", 4096 ** -0.5),
+                 note="bf16 65536x128x4096 NN, tall and narrow"),
+    "X5": Config("X5", 1, 16384, 16384, 0, 0, BF16, BF16,
+                 a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                 note="bf16 1x16384x16384 NN: a matrix-vector product through the skinny path"),
+}
+
 
 def scaled(cfg: Config, **kw) -> Config:
     """A copy of cfg with some fields replaced (smaller shapes, padded leading dimensions ...)."""
