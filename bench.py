@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
 FP32_VECTOR_PEAK_TFLOPS = 157.3
+FP32_MFMA_PEAK_TFLOPS = 157.3      # fp32 matrix-core peak (same figure as the vector ALUs)
 HBM_PEAK_GBPS = 8000.0
 
 
@@ -174,7 +175,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5",
+    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5,X6",
                     help="first one is the headline workload; X* are the further shapes of workloads.EXTRA_CONFIGS")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -228,8 +229,9 @@ def main():
             roof = None          # launch-latency bound: no roofline is meaningful
         elif bound == "mfma":
             ach = cfg.flops() / (ev_mean * 1e-3) / 1e12
-            roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": measured_traffic(name), "kernel": kname}
+            peak = FP32_MFMA_PEAK_TFLOPS if cfg.dtype == wl.F32 else MFMA_BF16_PEAK_TFLOPS    # the contraction's own type
+            roof = {"bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                    "frac": ach / peak, "traffic": measured_traffic(name), "kernel": kname}
         else:
             ach = cfg.algorithmic_bytes() / (ev_mean * 1e-3) / 1e9
             roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -50,7 +50,11 @@ int tail_parts(int64_t tail, int64_t cus, int64_t K) {
 }
 
 struct TileChoice { int variant; int first_split_tile; int parts; };
+constexpr int kF32TileVariant = 11;
+constexpr int64_t kF32MinTiles = 16;       // below this many 128x128 tiles the general kernel's finer grid wins
+
 TileChoice choose_tile(const Args& a, int num_cus) {
+    if (a.dtype == gemm::DT_F32) return TileChoice{kF32TileVariant, 0, 1};
     const int64_t cus = num_cus > 0 ? num_cus : 256;
     const int64_t large = ((a.M + 255) / 256) * ((a.N + 255) / 256), small = ((a.M + 127) / 128) * ((a.N + 127) / 128);
     const bool large_ok = gemm::tile_variant_supports(a, kLargeTileVariant);
@@ -233,7 +237,8 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
         // call bandwidth-limited (stream B once, split K); otherwise it is a matrix-core problem.
         if (gemm::skinny_supports(a) && N >= 256 && K >= 512) {
             plan = gemm_plan_t{GEMM_KERNEL_SKINNY, 0, gemm::skinny_default_split(a, h->num_cus)};
-        } else if (gemm::tile_supports(a)) {
+        } else if (gemm::tile_supports(a) &&
+                   (a.dtype != gemm::DT_F32 || ((a.M + 127) / 128) * ((a.N + 127) / 128) >= kF32MinTiles)) {
             const TileChoice c = choose_tile(a, h->num_cus);
             plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, c.variant, c.parts};
             split_first = c.first_split_tile;

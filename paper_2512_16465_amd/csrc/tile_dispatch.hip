@@ -34,27 +34,30 @@ const TileVariantInfo* tile_variant_info(int variant) {
     return (variant >= 0 && variant < kNum) ? &kInfo[variant] : nullptr;
 }
 
-// 16-byte vector loads along the contiguous dimension of each operand, 32-bit byte offsets
-// inside a tile, and a 32-bit workgroup count.
+// 16-byte vector loads along the contiguous dimension of each operand (8 elements of 16 bits,
+// 4 of 32), 32-bit byte offsets inside a tile, and a 32-bit workgroup count.
 bool tile_supports(const Args& a) {
-    if (a.dtype != DT_BF16 && a.dtype != DT_F16) return false;
+    if (a.dtype != DT_BF16 && a.dtype != DT_F16 && a.dtype != DT_F32) return false;
+    const int64_t chunk = a.dtype == DT_F32 ? 4 : 8;
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return false;
     if (((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15)) return false;
-    if ((a.lda & 7) || (a.ldb & 7)) return false;
+    if ((a.lda % chunk) || (a.ldb % chunk)) return false;
     if (a.lda > (1 << 22) || a.ldb > (1 << 22)) return false;
     if (a.K > (1 << 30)) return false;
     // the contiguous dimension of each operand must be whole 16-byte chunks
-    if (!a.transA ? (a.K & 7) : (a.M & 7)) return false;
-    if (a.transB ? (a.K & 7) : (a.N & 7)) return false;
+    if ((!a.transA ? a.K : a.M) % chunk) return false;
+    if ((a.transB ? a.K : a.N) % chunk) return false;
     const int64_t tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
     if (tiles > (int64_t)1 << 30) return false;
     return true;
 }
 
-// The direct-to-LDS variants mask lanes with a fixed out-of-range offset of 2 GiB - 16.
+// A variant takes either 16-bit or 32-bit operands.  The direct-to-LDS variants mask lanes with a
+// fixed out-of-range offset of 2 GiB - 16.
 bool tile_variant_supports(const Args& a, int variant) {
     if (variant < 0 || variant >= kNum) return false;
-    if (kInfo[variant].kind == 0) return true;
+    if ((kInfo[variant].kind == 4) != (a.dtype == DT_F32)) return false;
+    if (kInfo[variant].kind == 0 || kInfo[variant].kind == 4) return true;
     const int64_t a_bytes = ((a.transA ? a.K : a.M) * a.lda) * 2, b_bytes = ((a.transB ? a.N : a.K) * a.ldb) * 2;
     return a_bytes < 0x7ffffff0ll && b_bytes < 0x7ffffff0ll;
 }

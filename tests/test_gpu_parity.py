@@ -26,11 +26,16 @@ def base_cfg(M, N, K, ta, tb, dtype=wl.BF16, out=None, **kw):
     return wl.Config("t", M, N, K, ta, tb, dtype, dtype if out is None else out, **kw)
 
 
-def num_tile_variants():
+def all_tile_variants():
     n = 0
     while lg.gemm_variant_name(lg.GEMM_KERNEL_MFMA_TILE, n) is not None:
         n += 1
     return n
+
+
+def tile_variants(f32=False):
+    """Indices of the tile variants for 16-bit (default) or fp32 operands."""
+    return [v for v in range(all_tile_variants()) if lg.gemm_variant_name(lg.GEMM_KERNEL_MFMA_TILE, v).startswith("f32_") == f32]
 
 
 # ------------------------------------------------------------------ C1: the fp32 parity configuration
@@ -54,7 +59,7 @@ def test_tile_variants_gaussian(handle, ta, tb, dtype):
         cfg = base_cfg(M, N, K, ta, tb, dtype, out, a_dist=("normal", 1.0), b_dist=("normal", 0.5))
         inp = wl.make_inputs(cfg, 31 + ta * 2 + tb)
         ref, _, mag = oracle.gemm_full(oracle_problem(cfg, inp), want_bounds=True)
-        for v in range(num_tile_variants()):
+        for v in tile_variants():
             print(f"tile variant {v} ta={ta} tb={tb} dtype={dtype} out={out}", flush=True)
             lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
             p = DeviceProblem(cfg, inp)
@@ -73,7 +78,7 @@ def test_tile_variants_integer_exact(handle, ta, tb):
                        lda=(M if ta else K) + 8, ldb=(K if tb else N) + 16, ldc=N + 3)
         inp, _ = wl.make_integer_inputs(cfg, 77, -2, 2)
         want = oracle.decode(out, expected_bits_exact(cfg, inp))
-        for v in range(num_tile_variants()):
+        for v in tile_variants():
             print(f"integer tile variant {v} ta={ta} tb={tb} out={out}", flush=True)
             lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
             p = DeviceProblem(cfg, inp)
@@ -96,7 +101,7 @@ def test_tile_variants_every_small_slab_count(handle, ta, tb):
         cfg = base_cfg(M, N, K, ta, tb, wl.BF16, wl.F32, alpha=1.0, beta=0.0)
         inp, _ = wl.make_integer_inputs(cfg, 100 + K, -2, 2)
         want = oracle.decode(wl.F32, expected_bits_exact(cfg, inp))
-        for v in range(num_tile_variants()):
+        for v in tile_variants():
             print(f"slab-count sweep K={K} variant {v} ta={ta} tb={tb}", flush=True)
             lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
             p = DeviceProblem(cfg, inp)
@@ -117,7 +122,7 @@ def test_tile_split_of_the_trailing_round(handle, ta, tb):
                    act=wl.ACT_RELU, ldc=N + 5)
     inp, _ = wl.make_integer_inputs(cfg, 78, -2, 2)
     want = oracle.decode(wl.BF16, expected_bits_exact(cfg, inp))
-    splitting = [v for v in range(num_tile_variants()) if "dma16" in lg.gemm_variant_name(lg.GEMM_KERNEL_MFMA_TILE, v)]
+    splitting = [v for v in tile_variants() if "dma16" in lg.gemm_variant_name(lg.GEMM_KERNEL_MFMA_TILE, v)]
     assert splitting
     for v in splitting:
         for parts in (2, 5, 64):
@@ -138,13 +143,57 @@ def test_tile_split_of_the_trailing_round(handle, ta, tb):
     lg.gemm_set_plan(handle)
 
 
+@pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0), (1, 1), (1, 0)])
+def test_f32_tile_variants(handle, ta, tb):
+    # fp32 operands on the fp32 matrix instruction: 3 x 5 tiles of 128 with ragged tails, K leaves a partial slab
+    # (K % 16 = 12); Gaussian data to the fp32 tolerance, integer data exactly; wrong operand type is refused
+    assert tile_variants(f32=True)
+    M, N, K = 300, 520, 172
+    for v in tile_variants(f32=True):
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
+        cfg = base_cfg(M, N, K, ta, tb, wl.F32, wl.F32, alpha=0.5, beta=2.0, a_dist=("normal", 1.0), b_dist=("normal", 0.5),
+                       c_dist=("normal", 1.0), bias_dist=("normal", 1.0), bias_dtype=wl.F32, act=wl.ACT_GELU_TANH,
+                       lda=(M if ta else K) + 4, ldb=(K if tb else N) + 8, ldc=N + 1)
+        inp = wl.make_inputs(cfg, 61 + 2 * ta + tb)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        assert lg.gemm_get_last_plan(handle)[:2] == (lg.GEMM_KERNEL_MFMA_TILE, v)
+        check_full(cfg, inp, p.result_bits(), f"f32 variant {v}")
+        cfg = base_cfg(M, N, K, ta, tb, wl.F32, wl.F32, alpha=3.0, beta=-1.0)
+        inp, _ = wl.make_integer_inputs(cfg, 62, -3, 3)
+        want = oracle.decode(wl.F32, expected_bits_exact(cfg, inp))
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        assert np.array_equal(decode_c(cfg, p.result_bits()), want)
+        # a 16-bit problem cannot run on it, nor an fp32 problem on a 16-bit variant
+        cfg16 = base_cfg(64, 64, 64, ta, tb, wl.BF16, wl.BF16)
+        assert DeviceProblem(cfg16, wl.make_inputs(cfg16, 1)).run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, tile_variants()[0])
+    cfg = base_cfg(64, 64, 64, ta, tb, wl.F32, wl.F32)
+    assert DeviceProblem(cfg, wl.make_inputs(cfg, 1)).run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED
+    lg.gemm_set_plan(handle)
+
+
+def test_f32_automatic_choice(handle):
+    # enough 128x128 tiles -> fp32 tile kernel; few tiles or unaligned -> general kernel
+    big = base_cfg(512, 640, 64, 0, 0, wl.F32, wl.F32)
+    small = base_cfg(256, 256, 256, 0, 0, wl.F32, wl.F32)
+    odd = base_cfg(512, 642, 64, 0, 0, wl.F32, wl.F32)
+    for cfg, family in ((big, lg.GEMM_KERNEL_MFMA_TILE), (small, lg.GEMM_KERNEL_GENERAL), (odd, lg.GEMM_KERNEL_GENERAL)):
+        inp = wl.make_inputs(cfg, 8)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        assert lg.gemm_get_last_plan(handle)[0] == family
+        check_full(cfg, inp, p.result_bits(), "f32 auto")
+
+
 def test_tile_epilogue_bias_gelu_beta(handle):
     M, N, K = 300, 392, 256
     cfg = base_cfg(M, N, K, 0, 1, wl.BF16, wl.BF16, alpha=0.5, beta=1.5, a_dist=("normal", 1.0),
                    b_dist=("normal", 0.1), c_dist=("normal", 1.0), bias_dist=("normal", 0.5),
                    bias_dtype=wl.BF16, act=wl.ACT_GELU_ERF)
     inp = wl.make_inputs(cfg, 5)
-    for v in range(num_tile_variants()):
+    for v in tile_variants():
         lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
         p = DeviceProblem(cfg, inp)
         p.run(handle)
@@ -156,7 +205,7 @@ def test_small_tile_problem_single_partial_slab(handle):
     # K smaller than one slab; M, N smaller than one tile
     cfg = base_cfg(40, 24, 8, 0, 1, wl.F16, wl.F16)
     inp = wl.make_inputs(cfg, 9)
-    for v in range(num_tile_variants()):
+    for v in tile_variants():
         lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
         p = DeviceProblem(cfg, inp)
         p.run(handle)

@@ -141,6 +141,9 @@ EXTRA_CONFIGS: Dict[str, Config] = {
     "X4": Config("X4", 65536, 128, 4096, 0, 0, BF16, BF16,
                  a_dist=("normal", 1.0), b_dist=("normal", 4096 ** -0.5),
                  note="bf16 65536x128x4096 NN, tall and narrow"),
+    "X6": Config("X6", 4096, 4096, 4096, 0, 0, F32, F32,
+                 a_dist=("normal", 1.0), b_dist=("normal", 4096 ** -0.5),
+                 note="fp32 4096^3 NN on the fp32 matrix instruction"),
     "X5": Config("X5", 1, 16384, 16384, 0, 0, BF16, BF16,
                  a_dist=("normal", 1.0), b_dist=("normal", 0.02),
                  note="bf16 1x16384x16384 NN: a matrix-vector product through the skinny path"),
