@@ -41,16 +41,46 @@ struct SkStage {
     u32x4 b[8];
 };
 
+// C_in and bias of 8 consecutive outputs of one row, widened to fp32 (zeros where the epilogue
+// does not use them).  Separate from the store so that a caller can have these loads in flight
+// together with the loads of its partial sums.
+struct SkRowInputs { float c_in[8]; float bias[8]; };
+
+__device__ __forceinline__ void sk_unpack16(u32x4 u, int dtype, float (&out)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint16_t b = (uint16_t)(u[e >> 1] >> (16 * (e & 1)));
+        out[e] = dtype == DT_BF16 ? bf16_bits_to_f32(b) : f16_bits_to_f32(b);
+    }
+}
+
+__device__ __forceinline__ void sk_load_row_inputs(const Args& a, int64_t row, int64_t col, bool vec_ok, SkRowInputs& in) {
+    const int64_t idx = row * a.ldc + col;
+    if (a.beta != 0.0f) {
+        if (vec_ok && a.out_dtype != DT_F32) {
+            sk_unpack16(*(const u32x4*)((const uint16_t*)a.C + idx), a.out_dtype, in.c_in);
+        } else if (vec_ok) {
+            const f32x4 lo = *(const f32x4*)((const float*)a.C + idx), hi = *(const f32x4*)((const float*)a.C + idx + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { in.c_in[e] = lo[e]; in.c_in[4 + e] = hi[e]; }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) in.c_in[e] = load_elem(a.C, a.out_dtype, idx + e);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) in.c_in[e] = 0.0f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) in.bias[e] = a.bias ? load_elem(a.bias, a.bias_dtype, col + e) : 0.0f;
+}
+
 // Stores 8 consecutive outputs of one row, after the epilogue, in the type of C.
-__device__ __forceinline__ void sk_store_row(const Args& a, int64_t row, int64_t col, const float (&x)[8], bool vec_ok) {
+__device__ __forceinline__ void sk_store_row(const Args& a, int64_t row, int64_t col, const float (&x)[8], const SkRowInputs& in, bool vec_ok) {
     float o[8];
     const int64_t idx = row * a.ldc + col;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float c_in = (a.beta != 0.0f) ? load_elem(a.C, a.out_dtype, idx + e) : 0.0f;
-        const float bj = a.bias ? load_elem(a.bias, a.bias_dtype, col + e) : 0.0f;
-        o[e] = epilogue_value(x[e], a.alpha, a.beta, c_in, bj, a.act);
-    }
+    for (int e = 0; e < 8; ++e) o[e] = epilogue_value(x[e], a.alpha, a.beta, in.c_in[e], in.bias[e], a.act);
     if (a.out_dtype == DT_F32) {
         float* p = (float*)a.C + idx;
         if (vec_ok) {
@@ -193,7 +223,9 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int sp
                     *(f32x4*)p = f32x4{x[0], x[1], x[2], x[3]};
                     *(f32x4*)(p + 4) = f32x4{x[4], x[5], x[6], x[7]};
                 } else {
-                    sk_store_row(a, row, col0, x, c_vec_ok != 0);
+                    SkRowInputs in;
+                    sk_load_row_inputs(a, row, col0, c_vec_ok != 0, in);
+                    sk_store_row(a, row, col0, x, in, c_vec_ok != 0);
                 }
             }
         }
@@ -201,19 +233,40 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int sp
 }
 
 // Sums the split-K slices in the order 0, 1, ..., S-1 and applies the epilogue; 8 columns per thread.
+// The kernel is one round trip to memory long, so everything it reads is requested before
+// anything is used: S > 0 fixes the number of slices at compile time (all their loads are issued
+// back to back, together with those of C_in and bias); S == 0 takes any number.
+template <int S>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(Args a, int split_k, const float* ws, int c_vec_ok) {
     const int64_t groups_per_row = a.N / 8;
     const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (g >= a.M * groups_per_row) return;
     const int64_t row = g / groups_per_row, col = (g % groups_per_row) * 8;
+    const int64_t slice = a.M * a.N;
+    const float* p = ws + row * a.N + col;
+    SkRowInputs in;
     float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < split_k; ++s) {
-        const float* p = ws + ((int64_t)s * a.M + row) * a.N + col;
-        const f32x4 lo = *(const f32x4*)p, hi = *(const f32x4*)(p + 4);
+    if constexpr (S > 0) {
+        f32x4 lo[S], hi[S];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { x[e] += lo[e]; x[4 + e] += hi[e]; }
+        for (int s = 0; s < S; ++s) {
+            lo[s] = *(const f32x4*)(p + s * slice);
+            hi[s] = *(const f32x4*)(p + s * slice + 4);
+        }
+        sk_load_row_inputs(a, row, col, c_vec_ok != 0, in);
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { x[e] += lo[s][e]; x[4 + e] += hi[s][e]; }
+    } else {
+        sk_load_row_inputs(a, row, col, c_vec_ok != 0, in);
+        for (int s = 0; s < split_k; ++s) {
+            const f32x4 lo = *(const f32x4*)(p + s * slice), hi = *(const f32x4*)(p + s * slice + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { x[e] += lo[e]; x[4 + e] += hi[e]; }
+        }
     }
-    sk_store_row(a, row, col, x, c_vec_ok != 0);
+    sk_store_row(a, row, col, x, in, c_vec_ok != 0);
 }
 
 }  // namespace
@@ -263,8 +316,14 @@ hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split_k == 1) return e;
     const int64_t threads = a.M * (a.N / 8);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
-                       a, split_k, (const float*)workspace, c_vec_ok);
+    const dim3 rgrid((unsigned)((threads + 255) / 256)), rblock(256);
+    const float* partials = workspace;
+    switch (split_k) {
+        case 2: hipLaunchKernelGGL(splitk_reduce_kernel<2>, rgrid, rblock, 0, stream, a, split_k, partials, c_vec_ok); break;
+        case 4: hipLaunchKernelGGL(splitk_reduce_kernel<4>, rgrid, rblock, 0, stream, a, split_k, partials, c_vec_ok); break;
+        case 8: hipLaunchKernelGGL(splitk_reduce_kernel<8>, rgrid, rblock, 0, stream, a, split_k, partials, c_vec_ok); break;
+        default: hipLaunchKernelGGL(splitk_reduce_kernel<0>, rgrid, rblock, 0, stream, a, split_k, partials, c_vec_ok); break;
+    }
     return hipGetLastError();
 }
 
