@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of libgemm on one MI355X.
 
-    python bench.py [--gpus 1] [--steps 50] [--warmup 10] [--configs C3,C5,...] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps 50] [--warmup 10] [--settle-ms 80] [--configs C3,C5,...] [--no-cpu-baseline]
 
 A "step" is one gemm_run call on the headline workload (C3: bf16 8192^3, row-major A and B,
 fp32 output) with operands resident in HBM.  The protocol follows the paper's evaluation
@@ -95,14 +95,26 @@ class Resident:
                     A.data_ptr(), cfg.ld_a(), B.data_ptr(), cfg.ld_b(), cfg.beta, C.data_ptr(), cfg.ld_c(), epi, stream)
 
 
-def time_config(lg, handle, res: Resident, steps: int, warmup: int):
+def time_config(lg, handle, res: Resident, steps: int, warmup: int, settle_ms: float = 0.0):
     """Returns (wall ms per step over the whole timed region, mean/min/std of per-launch
-    durations from HIP events recorded on the launch stream)."""
+    durations from HIP events recorded on the launch stream, warm-up launches done).
+
+    Warm-up: `warmup` launches, then further launches until `settle_ms` have passed since the
+    first one.  After an idle period (input generation, the sampled check) the part needs about
+    50 ms of continuous work before launch times stop falling (8192^3: 915 us for the first
+    launches, 750 us from the 60th on), so a warm-up counted in launches alone would leave the
+    short configurations inside that ramp.  The timed region is exactly `steps` launches."""
     import torch
     stream = torch.cuda.current_stream().cuda_stream
-    for i in range(warmup):
-        res.launch(lg, handle, i, stream)
-    torch.cuda.synchronize()
+    t_warm = time.perf_counter()
+    done = 0
+    while done < warmup or (time.perf_counter() - t_warm) * 1e3 < settle_ms:
+        batch = min(10, warmup - done) if done < warmup else 10
+        for i in range(batch):
+            res.launch(lg, handle, done + i, stream)
+        done += batch
+        if done >= warmup:
+            torch.cuda.synchronize()        # the clock is only read between batches
     # pass 1: wall time of the whole timed region, nothing but the launches between the two syncs
     t0 = time.perf_counter()
     for i in range(steps):
@@ -121,7 +133,7 @@ def time_config(lg, handle, res: Resident, steps: int, warmup: int):
     per = [starts[i].elapsed_time(stops[i]) for i in range(steps)]
     mean = sum(per) / len(per)
     var = sum((x - mean) ** 2 for x in per) / len(per)
-    return (t1 - t0) * 1e3 / steps, mean, min(per), var ** 0.5
+    return (t1 - t0) * 1e3 / steps, mean, min(per), var ** 0.5, done
 
 
 def quick_verify(res: Resident, lg, handle):
@@ -177,6 +189,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5,X6",
                     help="first one is the headline workload; X* are the further shapes of workloads.EXTRA_CONFIGS")
+    ap.add_argument("--settle-ms", type=float, default=80.0,
+                    help="the warm-up keeps launching until this much time has passed (clock ramp after idle); 0 = exactly --warmup launches")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true")
@@ -220,7 +234,7 @@ def main():
         bound = "hbm" if classify(cfg) != "compute-bound" else "mfma"
         res = Resident(cfg, seed, copies=2 if bound == "hbm" and cfg.algorithmic_bytes() > (64 << 20) else 1)
         ok = None if args.no_verify else quick_verify(res, lg, handle)
-        wall_ms, ev_mean, ev_min, ev_std = time_config(lg, handle, res, args.steps, args.warmup)
+        wall_ms, ev_mean, ev_min, ev_std, warm_done = time_config(lg, handle, res, args.steps, args.warmup, args.settle_ms)
         kernel, variant, split = lg.gemm_get_last_plan(handle)
         kname = lg.gemm_variant_name(kernel, variant)
         tflops = cfg.flops() / (wall_ms * 1e-3) / 1e12
@@ -239,7 +253,7 @@ def main():
         results[name] = {
             "workload": cfg.note, "class": classify(cfg), "kernel": kname, "split_k": split,
             "ms_per_step": wall_ms, "launch_ms_mean": ev_mean, "launch_ms_min": ev_min, "launch_ms_std": ev_std,
-            "tflops": tflops, "algorithmic_gbps": gbps, "verified_sample": ok, "roofline": roof,
+            "tflops": tflops, "algorithmic_gbps": gbps, "verified_sample": ok, "warmup_launches": warm_done, "roofline": roof,
         }
         if idx == 0:
             headline = (name, cfg, res, wall_ms, tflops, roof)

@@ -192,7 +192,7 @@ template <> struct OutVec<DT_F32> {
     typedef float elem;
     static __device__ __forceinline__ f32x4 load4(const elem* p) { return *(const f32x4*)p; }
     static __device__ __forceinline__ float load1(const elem* p) { return *p; }
-    static __device__ __forceinline__ void store4(elem* p, f32x4 v) { *(f32x4*)p = v; }
+    static __device__ __forceinline__ void store4(elem* p, f32x4 v) { __builtin_nontemporal_store(v, (f32x4*)p); }
     static __device__ __forceinline__ void store1(elem* p, float v) { *p = v; }
 };
 template <> struct OutVec<DT_BF16> {
@@ -205,7 +205,7 @@ template <> struct OutVec<DT_BF16> {
     static __device__ __forceinline__ float load1(const elem* p) { return bf16_bits_to_f32(*p); }
     static __device__ __forceinline__ void store4(elem* p, f32x4 v) {
         typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-        *(uint2*)p = __builtin_bit_cast(uint2, __builtin_convertvector(v, bf16x4));   // v_cvt_pk_bf16_f32, nearest even
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x2, __builtin_convertvector(v, bf16x4)), (u32x2*)p);   // v_cvt_pk_bf16_f32, nearest even
     }
     static __device__ __forceinline__ void store1(elem* p, float v) { *p = __builtin_bit_cast(uint16_t, (__bf16)v); }
 };
@@ -217,7 +217,7 @@ template <> struct OutVec<DT_F16> {
     static __device__ __forceinline__ float load1(const elem* p) { return f16_bits_to_f32(*p); }
     static __device__ __forceinline__ void store4(elem* p, f32x4 v) {
         typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
-        *(uint2*)p = __builtin_bit_cast(uint2, __builtin_convertvector(v, f16x4));    // v_cvt_f16_f32, nearest even
+        __builtin_nontemporal_store(__builtin_bit_cast(u32x2, __builtin_convertvector(v, f16x4)), (u32x2*)p);    // v_cvt_f16_f32, nearest even
     }
     static __device__ __forceinline__ void store1(elem* p, float v) { *p = f32_to_f16_bits(v); }
 };
