@@ -96,8 +96,9 @@ class Resident:
 
 
 def time_config(lg, handle, res: Resident, steps: int, warmup: int, settle_ms: float = 0.0):
-    """Returns (wall ms per step over the whole timed region, mean/min/std of per-launch
-    durations from HIP events recorded on the launch stream, warm-up launches done).
+    """Returns (wall ms per step over the whole timed region; mean launch duration from HIP events
+    on the launch stream around that region; min and std of single launches timed by an event
+    pair each; warm-up launches done).
 
     Warm-up: `warmup` launches, then further launches until `settle_ms` have passed since the
     first one.  After an idle period (input generation, the sampled check) the part needs about
@@ -115,14 +116,20 @@ def time_config(lg, handle, res: Resident, steps: int, warmup: int, settle_ms: f
         done += batch
         if done >= warmup:
             torch.cuda.synchronize()        # the clock is only read between batches
-    # pass 1: wall time of the whole timed region, nothing but the launches between the two syncs
+    # pass 1: the timed region, nothing but the launches between the two syncs; host wall clock
+    # around it, and one pair of events on the launch stream around the same launches (the mean
+    # launch duration that the roofline figure uses: device time, back to back, no host in it)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record()
     for i in range(steps):
         res.launch(lg, handle, i, stream)
+    ev1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    # pass 2: per-launch durations from events on the launch stream (their recording costs host time,
-    # which is why it is kept out of pass 1)
+    mean = ev0.elapsed_time(ev1) / steps
+    # pass 2: launch by launch, for the spread (an event pair per launch costs a few microseconds
+    # of its own, which is why the mean comes from pass 1)
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     for i in range(steps):
@@ -131,8 +138,8 @@ def time_config(lg, handle, res: Resident, steps: int, warmup: int, settle_ms: f
         stops[i].record()
     torch.cuda.synchronize()
     per = [starts[i].elapsed_time(stops[i]) for i in range(steps)]
-    mean = sum(per) / len(per)
-    var = sum((x - mean) ** 2 for x in per) / len(per)
+    pmean = sum(per) / len(per)
+    var = sum((x - pmean) ** 2 for x in per) / len(per)
     return (t1 - t0) * 1e3 / steps, mean, min(per), var ** 0.5, done
 
 
@@ -187,7 +194,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5,X6",
+    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5,X6,X7",
                     help="first one is the headline workload; X* are the further shapes of workloads.EXTRA_CONFIGS")
     ap.add_argument("--settle-ms", type=float, default=80.0,
                     help="the warm-up keeps launching until this much time has passed (clock ramp after idle); 0 = exactly --warmup launches")

@@ -161,6 +161,10 @@ hipError_t launch_tile(const Args& a, int variant, int group_m, const TileSplit&
 hipError_t launch_tile_split_reduce(const Args& a, int variant, int group_m, const TileSplit& split, hipStream_t stream);
 
 bool skinny_supports(const Args& a);
+const char* skinny_variant_name(int variant);
+// the variant that serves the call's layout, and the largest split factor it takes
+int skinny_variant_of(const Args& a);
+int skinny_max_split(const Args& a);
 // bytes of fp32 workspace the skinny kernel needs for this split factor (0 when split_k == 1)
 size_t skinny_workspace_bytes(const Args& a, int split_k);
 int skinny_default_split(const Args& a, int num_cus);

@@ -161,7 +161,7 @@ GEMM_EXPORT const char* gemm_variant_name(gemm_kernel_t kernel, int32_t variant)
         return info ? info->name : nullptr;
     }
     if (kernel == GEMM_KERNEL_GENERAL) return variant == 0 ? "general_16x16" : nullptr;
-    if (kernel == GEMM_KERNEL_SKINNY) return variant == 0 ? "skinny_nn_32x256_w4" : nullptr;
+    if (kernel == GEMM_KERNEL_SKINNY) return gemm::skinny_variant_name(variant);
     return nullptr;
 }
 
@@ -227,7 +227,8 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
             }
         } else if (plan.kernel == GEMM_KERNEL_SKINNY) {
             if (!gemm::skinny_supports(a)) return GEMM_ERR_UNSUPPORTED;
-            plan.variant = 0;
+            if (plan.variant >= 0 && plan.variant != gemm::skinny_variant_of(a)) return GEMM_ERR_UNSUPPORTED;
+            plan.variant = gemm::skinny_variant_of(a);
             if (plan.split_k == 0) plan.split_k = gemm::skinny_default_split(a, h->num_cus);
         } else {
             plan = gemm_plan_t{GEMM_KERNEL_GENERAL, 0, 1};
@@ -236,7 +237,7 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
         // The paper's roofline rule (Section 4.3) in arithmetic form: few rows of C make the
         // call bandwidth-limited (stream B once, split K); otherwise it is a matrix-core problem.
         if (gemm::skinny_supports(a) && N >= 256 && K >= 512) {
-            plan = gemm_plan_t{GEMM_KERNEL_SKINNY, 0, gemm::skinny_default_split(a, h->num_cus)};
+            plan = gemm_plan_t{GEMM_KERNEL_SKINNY, gemm::skinny_variant_of(a), gemm::skinny_default_split(a, h->num_cus)};
         } else if (gemm::tile_supports(a) &&
                    (a.dtype != gemm::DT_F32 || ((a.M + 127) / 128) * ((a.N + 127) / 128) >= kF32MinTiles)) {
             const TileChoice c = choose_tile(a, h->num_cus);
@@ -248,8 +249,8 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
     // ---- launch ----
     hipError_t e = hipSuccess;
     if (plan.kernel == GEMM_KERNEL_SKINNY) {
-        const int64_t steps = (K + 15) / 16;
-        if (plan.split_k > steps) plan.split_k = (int)steps;
+        const int max_split = gemm::skinny_max_split(a);
+        if (plan.split_k > max_split) plan.split_k = max_split;
         const size_t need = gemm::skinny_workspace_bytes(a, plan.split_k);
         if (need) {
             const gemm_status_t st = ensure_workspace(h, need, stream);

@@ -12,6 +12,7 @@
 //   v_perm_b32, and so holds, for each j < 8, the B operand of a 32x32x16 MFMA for column
 //   8c+j.  MFMA j accumulates C[0:32, {8c+j : c}]; a lane ends up owning 8 consecutive columns
 //   of 16 rows, which it stores as full 16- or 32-byte vectors.
+#include <type_traits>
 #include "common.hpp"
 
 namespace gemm {
@@ -232,6 +233,207 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int sp
     }
 }
 
+// ---- B stored N x K ("column-major B", the layout of a weight matrix kept as [out, in]) ----
+//
+// Every row of the stored B is one column of the product and is contiguous along k, so 16 bytes
+// of it are an MFMA operand as they come (16x16x32 MFMA: lane (c = lane%16, g = lane/16) holds
+// B[n + c][k + 8g .. +7]).  Loading them in that lane order would make neighbouring lanes fetch
+// from stored rows tens of kilobytes apart, one cache line per lane, and the address path of the
+// memory pipeline, not HBM, would set the pace.  So B goes through LDS instead, with loads whose
+// 64 lanes cover two stored rows x 512 contiguous bytes (eight whole cache lines) and write
+// straight to LDS (no registers): a "visit" is eight such instructions = 16 stored rows x 512 B
+// = 8 KiB, each wave keeps a private ring of ST_DEPTH visits, and the MFMA operands are read back
+// with ds_read_b128.  Layout of a visit in LDS: row r (of 16), 16-byte slot s (of 32) at
+// r*512 + s*16 holds piece s xor r of the row, so that the 16 lanes of an operand read (16 rows,
+// same piece) hit 16 different bank groups; the swizzle is applied on the global side, where a
+// lane simply fetches the piece that belongs in its slot.
+//
+// A wave owns 64 columns of C (four blocks of 16, visited in turn for every chunk of 256 along
+// k) over the workgroup's whole k range, so waves never add their sums to each other.  The
+// pieces of A for a chunk go to registers with the chunk's first visit and serve all four
+// blocks (the four waves of a workgroup read the same pieces: one trip to L2, three hits in L1).
+// The k range is cut over workgroups exactly as in the row-major kernel.
+//   accumulator register v of MFMA (h, jb) is C[16h + 4g + v][n0 + 16jb + c].
+constexpr int ST_COLS = 256;
+constexpr int ST_WAVES = 4;
+constexpr int ST_RUN = 8;                        // MFMA steps (32 along k) per visit: 512 contiguous bytes per stored row
+constexpr int ST_DEPTH = 4;                      // visits in flight per wave
+constexpr int ST_CHUNK = ST_RUN * 32;            // k per chunk
+constexpr int ST_VISIT_BYTES = 16 * ST_RUN * 64; // 8 KiB
+constexpr uint32_t ST_MASKED = 0x7ffffff0u;      // an offset past the end of any operand: the load returns zero
+
+template <bool IS_BF16>
+__device__ __forceinline__ f32x4 st_mfma(u32x4 a, u32x4 b, f32x4 c) {
+    if constexpr (IS_BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// Lane l fetches 16 bytes at byte offset `off` of the buffer; the wave's 64 pieces land at LDS
+// address dst + 16*l.  (Only the device pass of the compiler knows the builtin.)
+__device__ __forceinline__ void st_load_to_lds(__amdgpu_buffer_rsrc_t rsrc, char* dst, uint32_t off) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)dst, 16, off, 0, 0, 0);
+#else
+    (void)rsrc; (void)dst; (void)off;
+#endif
+}
+
+// Waits until at most N vector-memory loads issued by this wave are still in flight (they finish
+// in the order of issue).
+template <int N>
+__device__ __forceinline__ void st_wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+// H = 1 serves M <= 16, H = 2 serves M <= 32.
+template <bool IS_BF16, int H>
+__global__ __launch_bounds__(ST_WAVES * 64) void skinny_nt_kernel(Args a, int split_k, float* ws) {
+    static_assert(ST_DEPTH == 4 && ST_RUN == 8, "the visit loop and the load counts below are written for a ring of four visits of eight steps");
+    __shared__ __attribute__((aligned(1024))) char ring[ST_WAVES * ST_DEPTH * ST_VISIT_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c16 = lane & 15, g = lane >> 4;
+    const int M = (int)a.M, K = (int)a.K;
+    const int64_t N = a.N;
+
+    const int total_chunks = (K + ST_CHUNK - 1) / ST_CHUNK;
+    const int per_split = (total_chunks + split_k - 1) / split_k;
+    const int cbeg = blockIdx.y * per_split;
+    const int cend = (cbeg + per_split) < total_chunks ? (cbeg + per_split) : total_chunks;
+    const int nch = cend > cbeg ? cend - cbeg : 0;
+    const int nvis = nch * 4;                                  // visit v: chunk number v/4 of this workgroup, column block v%4
+    // The stored rows of B are a large power of two apart, so one position along k means one
+    // memory channel whatever the row: workgroups that walked k in step would all queue on the
+    // same few channels.  Every column group therefore starts at a chunk of its own and wraps
+    // around (the order of summation is a fixed function of the column group).
+    const int rot = nch > 0 ? (int)(blockIdx.x % (unsigned)nch) : 0;
+    auto chunk_of = [&](int v) {      // for v < nvis
+        const int c = (v >> 2) + rot;
+        return cbeg + (c >= nch ? c - nch : c);
+    };
+
+    const int64_t n0 = (int64_t)blockIdx.x * ST_COLS + wave * 64;
+    const __amdgpu_buffer_rsrc_t rb = sk_rsrc(a.B, ((int64_t)(N - 1) * a.ldb + K) * 2);
+    const __amdgpu_buffer_rsrc_t ra = sk_rsrc(a.A, ((int64_t)(M - 1) * a.lda + K) * 2);
+
+    // global side of a visit: instruction i fetches stored rows 2i and 2i+1 of the block; this
+    // lane serves row 2i + lr, slot ls, i.e. piece ls xor (2i + lr) of that row
+    const int lr = lane >> 5, ls = lane & 31;
+    const int n_first = (int)n0, n_last = (int)N - 1;
+    const uint32_t ldb_b = (uint32_t)a.ldb * 2;
+    char* const my_ring = ring + wave * (ST_DEPTH * ST_VISIT_BYTES);
+    // LDS side: operand of step t for this lane = row c16, piece 4t + g, kept in slot (4t + g) xor c16
+    uint32_t frag_addr[ST_RUN];
+#pragma unroll
+    for (int t = 0; t < ST_RUN; ++t)
+        frag_addr[t] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)my_ring + (uint32_t)(c16 * 512 + (((4 * t + g) ^ c16) << 4));
+
+    uint32_t a_row_off[H];
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        const int r = 16 * h + c16;
+        a_row_off[h] = (uint32_t)((r < M ? r : M - 1) * a.lda * 2);     // rows >= M repeat a valid one and are never stored
+    }
+
+    f32x4 acc[H][4];
+#pragma unroll
+    for (int h = 0; h < H; ++h)
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) acc[h][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 aq[2][H][ST_RUN];              // pieces of A of the chunk in work and of the next one
+
+    // K % 8 == 0: a piece of 8 lies inside or outside as a whole; outside, both operands read as
+    // zero (what follows a row in memory is the next row or padding, not zeros)
+    // Every visit slot of the loop below issues its loads whether the visit exists or not (a
+    // visit past the end fetches nothing: all its offsets are masked and read as zero), so the
+    // number of loads in flight behind any given one is the same on every path and the waits,
+    // the compiler's for A and the explicit ones for B, can be exact.
+    auto load_visit = [&](auto slot_c, auto jb_c, auto par_c, int v) {
+        constexpr int slot = decltype(slot_c)::value, jb = decltype(jb_c)::value, par = decltype(par_c)::value;
+        const bool live = v < nvis;
+        const int chunk = chunk_of(v);
+        if constexpr (jb == 0) {
+            const int kbase = chunk * ST_CHUNK + 8 * g;
+#pragma unroll
+            for (int t = 0; t < ST_RUN; ++t) {
+                const int k = kbase + 32 * t;
+#pragma unroll
+                for (int h = 0; h < H; ++h)
+                    aq[par][h][t] = __builtin_amdgcn_raw_buffer_load_b128(ra, (live && k < K) ? a_row_off[h] + (uint32_t)k * 2 : ST_MASKED, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int rl = 2 * i + lr;                                   // row of the block
+            const int n = n_first + 16 * jb + rl;
+            const int k = chunk * ST_CHUNK + ((ls ^ rl) << 3);
+            const uint32_t off = (uint32_t)(n < n_last ? n : n_last) * ldb_b + (uint32_t)k * 2;   // columns >= N repeat a valid one and are never stored
+            const uint32_t masked_off = (live && k < K) ? off : ST_MASKED;
+            st_load_to_lds(rb, my_ring + slot * ST_VISIT_BYTES + i * 1024, masked_off);
+        }
+    };
+    // visit d of a group of eight (two chunks): ring slot d%4, column block d%4, A buffer (d/4)%2.
+    // Loads issued after this visit's own: those of the three visits behind it in the ring, 8 each,
+    // plus the 8*H pieces of A that travel with a chunk's first visit (one of the three unless
+    // this visit is a first one itself).
+    auto process = [&](auto d_c, int v) {
+        constexpr int d = decltype(d_c)::value, slot = d % 4, jb = d % 4, par = (d / 4) % 2;
+        st_wait_loads<24 + (jb != 0 ? 8 * H : 0)>();
+        u32x4 cur[ST_RUN];
+#pragma unroll
+        for (int t = 0; t < ST_RUN; ++t)
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(cur[t]) : "v"(frag_addr[t]), "n"(slot * ST_VISIT_BYTES) : "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(cur[0]), "+v"(cur[1]), "+v"(cur[2]), "+v"(cur[3]), "+v"(cur[4]), "+v"(cur[5]), "+v"(cur[6]), "+v"(cur[7])
+                     :: "memory");
+        // the slot has been read out: refill it with visit v + 4 (same column block, the other A buffer)
+        load_visit(std::integral_constant<int, slot>{}, std::integral_constant<int, jb>{}, std::integral_constant<int, 1 - par>{}, v + 4);
+#pragma unroll
+        for (int t = 0; t < ST_RUN; ++t)
+#pragma unroll
+            for (int h = 0; h < H; ++h) acc[h][jb] = st_mfma<IS_BF16>(aq[par][h][t], cur[t], acc[h][jb]);
+    };
+
+    load_visit(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, 0);
+    load_visit(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, std::integral_constant<int, 0>{}, 1);
+    load_visit(std::integral_constant<int, 2>{}, std::integral_constant<int, 2>{}, std::integral_constant<int, 0>{}, 2);
+    load_visit(std::integral_constant<int, 3>{}, std::integral_constant<int, 3>{}, std::integral_constant<int, 0>{}, 3);
+    for (int v0 = 0; v0 < nvis; v0 += 8) {      // a trailing half group works on zeros
+        process(std::integral_constant<int, 0>{}, v0 + 0);
+        process(std::integral_constant<int, 1>{}, v0 + 1);
+        process(std::integral_constant<int, 2>{}, v0 + 2);
+        process(std::integral_constant<int, 3>{}, v0 + 3);
+        process(std::integral_constant<int, 4>{}, v0 + 4);
+        process(std::integral_constant<int, 5>{}, v0 + 5);
+        process(std::integral_constant<int, 6>{}, v0 + 6);
+        process(std::integral_constant<int, 7>{}, v0 + 7);
+    }
+    st_wait_loads<0>();      // the masked loads of the last visits still write (zeros) to LDS
+
+#pragma unroll
+    for (int h = 0; h < H; ++h)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = 16 * h + 4 * g + v;
+            if (row >= M) continue;
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+                const int64_t col = n0 + 16 * jb + c16;
+                if (col >= N) continue;
+                const float x = acc[h][jb][v];
+                if (split_k > 1) {
+                    ws[((int64_t)blockIdx.y * M + row) * N + col] = x;
+                } else {
+                    const int64_t ci = row * a.ldc + col;
+                    const float c_in = a.beta != 0.0f ? load_elem(a.C, a.out_dtype, ci) : 0.0f;
+                    const float bj = a.bias ? load_elem(a.bias, a.bias_dtype, col) : 0.0f;
+                    store_elem(a.C, a.out_dtype, ci, epilogue_value(x, a.alpha, a.beta, c_in, bj, a.act));
+                }
+            }
+        }
+}
+
 // Sums the split-K slices in the order 0, 1, ..., S-1 and applies the epilogue; 8 columns per thread.
 // The kernel is one round trip to memory long, so everything it reads is requested before
 // anything is used: S > 0 fixes the number of slices at compile time (all their loads are issued
@@ -273,22 +475,40 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(Args a, int split_k,
 
 bool skinny_supports(const Args& a) {
     if (a.dtype != DT_BF16 && a.dtype != DT_F16) return false;
-    if (a.transA || a.transB) return false;
+    if (a.transA) return false;
     if (a.M < 1 || a.M > 32 || a.N < 8 || a.K < 8) return false;
     if ((a.N & 7) || (a.K & 7) || (a.lda & 7) || (a.ldb & 7)) return false;
     if (((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15)) return false;
-    // 32-bit byte offsets into A and B (with room for the rows past K that read as zero)
-    if (((a.K + 16) * a.ldb) * 2 >= ((int64_t)1 << 31)) return false;
-    if ((a.M * a.lda) * 2 >= ((int64_t)1 << 31)) return false;
+    // 32-bit byte offsets into A and B (row-major B: with room for the rows past K that read as
+    // zero; B stored N x K: below the offset that masks a lane)
+    const int64_t b_bytes = a.transB ? a.N * a.ldb * 2 : (a.K + 16) * a.ldb * 2;
+    if (b_bytes >= (int64_t)ST_MASKED) return false;
+    if ((a.M * a.lda) * 2 >= (int64_t)ST_MASKED) return false;
     if ((a.N + SK_COLS - 1) / SK_COLS > 65535 * 16) return false;
     return true;
 }
 
+// variant 0: row-major B (K x N); variant 1: B stored N x K.  The layout of the call decides.
+const char* skinny_variant_name(int variant) {
+    return variant == 0 ? "skinny_nn_32x256_w4" : (variant == 1 ? "skinny_nt_32x256_w4" : nullptr);
+}
+
+int skinny_variant_of(const Args& a) { return a.transB ? 1 : 0; }
+
+// units the k range is cut in: steps of 16 (row-major B) or chunks of ST_CHUNK (B stored N x K)
+static int64_t skinny_k_units(const Args& a) { return a.transB ? (a.K + ST_CHUNK - 1) / ST_CHUNK : (a.K + 15) / 16; }
+
+int skinny_max_split(const Args& a) {
+    const int64_t units = skinny_k_units(a);
+    return (int)(units < 1 ? 1 : (units > 64 ? 64 : units));
+}
+
 int skinny_default_split(const Args& a, int num_cus) {
     const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS;
-    const int64_t steps = (a.K + 15) / 16;
     int64_t s = (num_cus + groups - 1) / groups;          // about one workgroup per compute unit
-    const int64_t max_s = steps / (SK_WAVES * 2 * SK_DEPTH);   // keep the pipeline of every wave filled a few times over
+    // keep the pipeline of every wave filled a few times over (row-major B: the waves of a
+    // workgroup share its k range; B stored N x K: every wave walks all of it, four visits per chunk)
+    const int64_t max_s = a.transB ? skinny_k_units(a) / 4 : skinny_k_units(a) / (SK_WAVES * 2 * SK_DEPTH);
     if (s > max_s) s = max_s;
     if (s > 64) s = 64;
     if (s < 1) s = 1;
@@ -299,17 +519,29 @@ size_t skinny_workspace_bytes(const Args& a, int split_k) {
     return split_k > 1 ? (size_t)split_k * (size_t)a.M * (size_t)a.N * sizeof(float) : 0;
 }
 
+namespace {
+template <bool IS_BF16>
+void launch_nt(const Args& a, dim3 grid, int split_k, float* ws, hipStream_t stream) {
+    if (a.M <= 16)
+        hipLaunchKernelGGL((skinny_nt_kernel<IS_BF16, 1>), grid, dim3(ST_WAVES * 64), 0, stream, a, split_k, ws);
+    else
+        hipLaunchKernelGGL((skinny_nt_kernel<IS_BF16, 2>), grid, dim3(ST_WAVES * 64), 0, stream, a, split_k, ws);
+}
+}  // namespace
+
 hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream_t stream) {
     const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS;
-    const int64_t steps = (a.K + 15) / 16;
+    const int64_t units = skinny_k_units(a);
     if (split_k < 1) split_k = 1;
-    if (split_k > steps) split_k = (int)steps;
+    if (split_k > units) split_k = (int)units;
     if (split_k > 1 && workspace == nullptr) return hipErrorInvalidValue;
-    const int esz = a.out_dtype == DT_F32 ? 4 : 2;
     // 8 outputs per vector store: 32 bytes of fp32 or 16 bytes of a 16-bit type
-    const int c_vec_ok = (a.ldc % 8 == 0) && ((uintptr_t)a.C % (esz == 4 ? 16 : 16) == 0);
+    const int c_vec_ok = (a.ldc % 8 == 0) && ((uintptr_t)a.C % 16 == 0);
     const dim3 grid((unsigned)groups, (unsigned)split_k), block(SK_WAVES * 64);
-    if (a.dtype == DT_BF16)
+    if (a.transB) {
+        if (a.dtype == DT_BF16) launch_nt<true>(a, grid, split_k, workspace, stream);
+        else launch_nt<false>(a, grid, split_k, workspace, stream);
+    } else if (a.dtype == DT_BF16)
         hipLaunchKernelGGL(skinny_nn_kernel<true>, grid, block, 0, stream, a, split_k, workspace, c_vec_ok);
     else
         hipLaunchKernelGGL(skinny_nn_kernel<false>, grid, block, 0, stream, a, split_k, workspace, c_vec_ok);

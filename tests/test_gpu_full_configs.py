@@ -14,9 +14,9 @@ from gpu_harness import DeviceProblem, check_sampled, decode_c, oracle_problem
 
 pytestmark = pytest.mark.gpu
 
-FULL = ["C2", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5", "X6"]
+FULL = ["C2", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5", "X6", "X7"]
 ALL = {**wl.CONFIGS, **wl.EXTRA_CONFIGS}
-SKINNY = ("C5", "X5")
+SKINNY = ("C5", "X5", "X7")
 
 
 @pytest.fixture(scope="module")

@@ -213,34 +213,43 @@ def test_small_tile_problem_single_partial_slab(handle):
     lg.gemm_set_plan(handle)
 
 
-# ------------------------------------------------------------------ skinny split-K kernel
+# ------------------------------------------------------------------ skinny split-K kernels (B row-major, B stored N x K)
 
-@pytest.mark.parametrize("M", [1, 5, 32])
-def test_skinny_gaussian_and_split_agreement(handle, M):
-    N, K = 776, 2056          # 4 column groups with a ragged last one; K % 16 = 8 leaves half a step
-    cfg = base_cfg(M, N, K, 0, 0, wl.BF16, wl.BF16, alpha=1.0, beta=1.0, a_dist=("normal", 1.0),
-                   b_dist=("normal", 0.02), c_dist=("normal", 1.0), lda=K + 8, ldb=N + 24)
-    inp = wl.make_inputs(cfg, 40 + M)
-    ref, _, mag = oracle.gemm_full(oracle_problem(cfg, inp), want_bounds=True)
-    for s in (1, 2, 3, 8):
-        print(f"skinny M={M} split={s}", flush=True)
-        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 0, s)
-        p = DeviceProblem(cfg, inp)
-        p.run(handle)
-        assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_SKINNY, 0, s)
-        assert_close(cfg, decode_c(cfg, p.result_bits()), ref, mag, f"skinny split {s}")
+@pytest.mark.parametrize("tb", [0, 1])
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 32])
+def test_skinny_gaussian_and_split_agreement(handle, M, tb):
+    # 4 column groups with a ragged last one (776 = 3*256 + 8); K % 16 = 8 and K % 32 = 8 leave a
+    # partly filled last step in either kernel; padded leading dimensions
+    N, K = 776, 2056
+    for dtype in (wl.BF16, wl.F16):
+        cfg = base_cfg(M, N, K, 0, tb, dtype, dtype, alpha=1.0, beta=1.0, a_dist=("normal", 1.0),
+                       b_dist=("normal", 0.02), c_dist=("normal", 1.0), lda=K + 8, ldb=(K if tb else N) + 24)
+        inp = wl.make_inputs(cfg, 40 + M)
+        ref, _, mag = oracle.gemm_full(oracle_problem(cfg, inp), want_bounds=True)
+        for s in (1, 2, 3, 8):
+            print(f"skinny M={M} tb={tb} dtype={dtype} split={s}", flush=True)
+            lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, -1, s)
+            p = DeviceProblem(cfg, inp)
+            p.run(handle)
+            assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_SKINNY, tb, s)
+            assert_close(cfg, decode_c(cfg, p.result_bits()), ref, mag, f"skinny tb={tb} split {s}")
+    # a variant forced against the layout of the call is refused
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 1 - tb, 1)
+    p = DeviceProblem(cfg, inp)
+    assert p.run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED
     lg.gemm_set_plan(handle)
 
 
+@pytest.mark.parametrize("tb", [0, 1])
 @pytest.mark.parametrize("out", [wl.BF16, wl.F32])
-def test_skinny_integer_exact_all_splits_equal(handle, out):
+def test_skinny_integer_exact_all_splits_equal(handle, out, tb):
     M, N, K = 19, 1032, 4104
-    cfg = base_cfg(M, N, K, 0, 0, wl.BF16, out, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.BF16,
+    cfg = base_cfg(M, N, K, 0, tb, wl.BF16, out, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.BF16,
                    ldc=N + 8)
     inp, _ = wl.make_integer_inputs(cfg, 123, -1, 1)
     want = oracle.decode(out, expected_bits_exact(cfg, inp))
     for s in (0, 1, 2, 4, 7, 16):
-        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 0, s)
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, -1, s)
         p = DeviceProblem(cfg, inp)
         p.run(handle)
         got = decode_c(cfg, p.result_bits())
@@ -251,6 +260,29 @@ def test_skinny_integer_exact_all_splits_equal(handle, out):
         p = DeviceProblem(cfg, inp)
         p.run(handle)
         assert np.array_equal(decode_c(cfg, p.result_bits()), want)
+    lg.gemm_set_plan(handle)
+
+
+@pytest.mark.parametrize("tb", [0, 1])
+def test_skinny_short_k_unaligned_c_and_stale_neighbours(handle, tb):
+    # fewer steps than pipeline stages (K = 40), a C whose rows allow no vector access (ldc = 203),
+    # bias and activation; B stored N x K is followed in memory by NaN (what lies behind the last
+    # k of a row must not reach the sums), and the padding columns of C keep their contents
+    for out in (wl.BF16, wl.F32):
+        cfg = base_cfg(7, 200, 40, 0, tb, wl.BF16, out, alpha=0.5, beta=-1.0, a_dist=("normal", 1.0), b_dist=("normal", 1.0),
+                       c_dist=("normal", 1.0), bias_dist=("normal", 1.0), bias_dtype=wl.F32, act=wl.ACT_SILU, ldc=203,
+                       lda=48, ldb=(48 if tb else 208))
+        inp = wl.make_inputs(cfg, 77)
+        nan16 = np.uint16(0x7fc0)
+        a2 = inp["A"].reshape(7, 48); a2[:, 40:] = nan16
+        b2 = inp["B"].reshape(-1, cfg.ld_b()); b2[:, (40 if tb else 200):] = nan16
+        ref, _, mag = oracle.gemm_full(oracle_problem(cfg, inp), want_bounds=True)
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, -1, 1)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        bits = p.result_bits()
+        assert_close(cfg, decode_c(cfg, bits), ref, mag, f"skinny short K tb={tb}")
+        assert np.array_equal(bits[:-1, cfg.N:], inp["C"].reshape(cfg.M, cfg.ld_c())[:-1, cfg.N:])
     lg.gemm_set_plan(handle)
 
 
@@ -278,6 +310,8 @@ def test_activations_in_every_kernel_family(handle, act):
                                    bias_dist=("normal", 2.0), bias_dtype=wl.F16, act=act), lg.GEMM_KERNEL_MFMA_TILE),
         ("skinny", base_cfg(8, 512, 1024, 0, 0, wl.BF16, wl.BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.05),
                             bias_dist=("normal", 2.0), bias_dtype=wl.BF16, act=act), lg.GEMM_KERNEL_SKINNY),
+        ("skinny nt", base_cfg(24, 512, 1024, 0, 1, wl.F16, wl.F32, a_dist=("normal", 1.0), b_dist=("normal", 0.05),
+                               bias_dist=("normal", 2.0), bias_dtype=wl.F32, act=act), lg.GEMM_KERNEL_SKINNY),
         ("general", base_cfg(37, 29, 53, 1, 0, wl.F32, wl.F32, bias_dist=("normal", 2.0), bias_dtype=wl.F32, act=act),
          lg.GEMM_KERNEL_GENERAL),
     ]

@@ -147,6 +147,9 @@ EXTRA_CONFIGS: Dict[str, Config] = {
     "X5": Config("X5", 1, 16384, 16384, 0, 0, BF16, BF16,
                  a_dist=("normal", 1.0), b_dist=("normal", 0.02),
                  note="bf16 1x16384x16384 NN: a matrix-vector product through the skinny path"),
+    "X7": Config("X7", 32, 16384, 16384, 0, 1, BF16, BF16, alpha=1.0, beta=1.0,
+                 a_dist=("normal", 1.0), b_dist=("normal", 0.02), c_dist=("normal", 1.0),
+                 note="bf16 32x16384x16384 NT skinny (B stored N x K, a weight matrix kept as [out, in]), alpha=beta=1"),
 }
 
 
