@@ -83,7 +83,7 @@ class Resident:
             if inp["C"] is not None:
                 C = wl.bits_to_torch(inp["C"], cfg.out_dtype, dev)
             else:
-                C = torch.empty(cfg.M * cfg.ld_c(), dtype=tdt, device=dev)
+                C = torch.empty(cfg.batch * cfg.M * cfg.ld_c(), dtype=tdt, device=dev)
             bias = wl.bits_to_torch(inp["bias"], cfg.bias_dtype, dev) if inp["bias"] is not None else None
             self.sets.append((A, B, C, bias))
 
@@ -91,6 +91,11 @@ class Resident:
         cfg = self.cfg
         A, B, C, bias = self.sets[i % len(self.sets)]
         epi = lg.make_epilogue(cfg.out_dtype, bias.data_ptr() if bias is not None else 0, cfg.bias_dtype, cfg.act)
+        if cfg.batch > 1:
+            lg.gemm_run_batched(handle, cfg.batch, cfg.M, cfg.N, cfg.K, cfg.transA, cfg.transB, cfg.dtype, cfg.alpha,
+                                A.data_ptr(), cfg.ld_a(), cfg.stride_a(), B.data_ptr(), cfg.ld_b(), cfg.stride_b(),
+                                cfg.beta, C.data_ptr(), cfg.ld_c(), cfg.stride_c(), epi, stream)
+            return
         lg.gemm_run(handle, cfg.M, cfg.N, cfg.K, cfg.transA, cfg.transB, cfg.dtype, cfg.alpha,
                     A.data_ptr(), cfg.ld_a(), B.data_ptr(), cfg.ld_b(), cfg.beta, C.data_ptr(), cfg.ld_c(), epi, stream)
 
@@ -157,10 +162,13 @@ def quick_verify(res: Resident, lg, handle):
     res.launch(lg, handle, 0, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     rows, cols = wl.sample_indices(cfg.M, cfg.N, 1, grid=16)
-    flat = (torch.from_numpy(rows).to(C.device) * cfg.ld_c() + torch.from_numpy(cols).to(C.device))
+    last = cfg.batch - 1                 # a batch is checked on its last matrix
+    flat = (torch.from_numpy(rows).to(C.device) * cfg.ld_c() + torch.from_numpy(cols).to(C.device)) + last * cfg.stride_c()
     got = oracle.decode(cfg.out_dtype, wl.torch_to_bits(C[flat]))
-    prob = oracle.Problem(cfg.M, cfg.N, cfg.K, cfg.transA, cfg.transB, cfg.dtype, inp["A"], cfg.ld_a(), inp["B"], cfg.ld_b(),
-                          alpha=cfg.alpha, beta=cfg.beta, C=inp["C"], ldc=cfg.ld_c(), c_dtype=cfg.out_dtype,
+    prob = oracle.Problem(cfg.M, cfg.N, cfg.K, cfg.transA, cfg.transB, cfg.dtype, inp["A"][last * cfg.stride_a():], cfg.ld_a(),
+                          inp["B"][last * cfg.stride_b():], cfg.ld_b(),
+                          alpha=cfg.alpha, beta=cfg.beta, C=None if inp["C"] is None else inp["C"][last * cfg.stride_c():],
+                          ldc=cfg.ld_c(), c_dtype=cfg.out_dtype,
                           bias=inp["bias"], bias_dtype=cfg.bias_dtype, act=cfg.act)
     ref, _, mag = oracle.gemm_at(prob, rows, cols)
     tol = (1e-5 * mag + 1e-6) if cfg.dtype == wl.F32 else (4e-3 * mag + 1e-5)
@@ -194,7 +202,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5,X6,X7",
+    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5,X6,X7,X8",
                     help="first one is the headline workload; X* are the further shapes of workloads.EXTRA_CONFIGS")
     ap.add_argument("--settle-ms", type=float, default=80.0,
                     help="the warm-up keeps launching until this much time has passed (clock ramp after idle); 0 = exactly --warmup launches")

@@ -111,6 +111,31 @@ gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_t K,
                        float beta, void* C, int64_t ldc,
                        const gemm_epilogue_t* epilogue, void* stream);
 
+/*
+ * The same product for `batch` independent problems of one shape, whose matrices lie at constant
+ * distances in memory (the shape of the per-head products of attention, which the paper names as
+ * the reason GEMM matters, Section 5.4):
+ *
+ *     C_b = act( alpha * op(A_b) * op(B_b) + beta * C_b + bias ),   b = 0 .. batch-1,
+ *     A_b = A + b*strideA,  B_b = B + b*strideB,  C_b = C + b*strideC   (strides in elements)
+ *
+ * Every other argument means what it means in gemm_run and applies to each matrix; bias is shared
+ * by the whole batch.  strideA or strideB may be 0 (one operand shared by all products);
+ * strideC must be at least (M-1)*ldc + N so that no two results overlap.  batch == 0 does
+ * nothing.  The fast kernels additionally need strideA and strideB to be multiples of 16 bytes;
+ * other strides run the general kernel.  One launch covers up to 65535 matrices; a longer batch
+ * is enqueued as consecutive launches.
+ *
+ * Errors: as gemm_run, and GEMM_ERR_INVALID_ARG for a negative batch or stride or an
+ * overlapping strideC.
+ */
+gemm_status_t gemm_run_batched(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, int64_t K,
+                               gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,
+                               float alpha, const void* A, int64_t lda, int64_t strideA,
+                               const void* B, int64_t ldb, int64_t strideB,
+                               float beta, void* C, int64_t ldc, int64_t strideC,
+                               const gemm_epilogue_t* epilogue, void* stream);
+
 /* Frees the workspace and the handle.  The caller must have synchronised the streams that used
  * it.  NULL is accepted.  Errors: GEMM_ERR_HIP if freeing device memory failed. */
 gemm_status_t gemm_destroy(gemm_handle_t h);
@@ -137,8 +162,8 @@ typedef struct {
                              * column group is cut into that many slices.  Macro-tile family: only
                              * the tiles of the last, partly filled round of workgroups (all tiles
                              * when there are fewer tiles than compute units) are cut, each into
-                             * that many shares of the k range; variants that cannot do so make
-                             * the call return GEMM_ERR_UNSUPPORTED.  Slices are added in a fixed
+                             * that many shares of the k range; variants that cannot do so, and
+                             * batched calls, make the call return GEMM_ERR_UNSUPPORTED.  Slices are added in a fixed
                              * order: results do not vary from run to run. */
 } gemm_plan_t;
 

@@ -13,7 +13,7 @@ from __future__ import annotations
 import ctypes
 import os
 import subprocess
-from dataclasses import dataclass
+from dataclasses import dataclass, replace
 from typing import Optional
 
 import numpy as np
@@ -228,3 +228,16 @@ def gemm_rows(p: Problem, row0: int, nrows: int) -> np.ndarray:
     if rc != 0:
         raise ValueError("oracle rejected the problem")
     return ref
+
+
+def gemm_strided_batched(p: Problem, batch: int, strideA: int, strideB: int, strideC: int, want_bounds: bool = False):
+    """A strided batch by its definition: problem b is `p` with every matrix taken b * stride
+    elements further into its array (bias is shared).  Returns arrays of shape (batch, M, N):
+    the reference values, and with want_bounds also sum_k|a b| and the bound magnitude."""
+    outs = []
+    for b in range(batch):
+        q = replace(p, A=p.A[b * strideA:], B=p.B[b * strideB:], C=None if p.C is None else p.C[b * strideC:])
+        outs.append(gemm_full(q, want_bounds))
+    if want_bounds:
+        return tuple(np.stack([o[i] for o in outs]) for i in range(3))
+    return np.stack(outs)

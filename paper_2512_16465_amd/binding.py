@@ -20,7 +20,7 @@ GEMM_ACT_NONE, GEMM_ACT_GELU_ERF, GEMM_ACT_RELU, GEMM_ACT_SILU, GEMM_ACT_GELU_TA
 GEMM_KERNEL_AUTO, GEMM_KERNEL_GENERAL, GEMM_KERNEL_MFMA_TILE, GEMM_KERNEL_SKINNY = 0, 1, 2, 3
 
 EXPORTED_SYMBOLS = (
-    "gemm_create", "gemm_run", "gemm_destroy", "gemm_status_string",
+    "gemm_create", "gemm_run", "gemm_run_batched", "gemm_destroy", "gemm_status_string",
     "gemm_set_plan", "gemm_get_last_plan", "gemm_variant_name",
 )
 
@@ -64,6 +64,10 @@ def load_library() -> ctypes.CDLL:
     lib.gemm_run.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                              ctypes.c_float, vp, i64, vp, i64, ctypes.c_float, vp, i64,
                              ctypes.POINTER(gemm_epilogue_t), vp]
+    lib.gemm_run_batched.restype = ctypes.c_int
+    lib.gemm_run_batched.argtypes = [vp, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                     ctypes.c_float, vp, i64, i64, vp, i64, i64, ctypes.c_float, vp, i64, i64,
+                                     ctypes.POINTER(gemm_epilogue_t), vp]
     lib.gemm_set_plan.restype = ctypes.c_int
     lib.gemm_set_plan.argtypes = [vp, ctypes.POINTER(gemm_plan_t)]
     lib.gemm_get_last_plan.restype = ctypes.c_int
@@ -105,6 +109,21 @@ def gemm_run(handle: int, M: int, N: int, K: int, transA: int, transB: int, dtyp
         ctypes.c_void_p(stream))
     if check and st != GEMM_OK:
         raise GemmError(st, "gemm_run")
+    return st
+
+
+def gemm_run_batched(handle: int, batch: int, M: int, N: int, K: int, transA: int, transB: int, dtype: int,
+                     alpha: float, A: int, lda: int, strideA: int, B: int, ldb: int, strideB: int,
+                     beta: float, C: int, ldc: int, strideC: int,
+                     epilogue: Optional[gemm_epilogue_t] = None, stream: int = 0, check: bool = True) -> int:
+    """`batch` products of one shape; matrix b of each operand starts b * stride elements after the first."""
+    st = load_library().gemm_run_batched(
+        ctypes.c_void_p(handle), batch, M, N, K, transA, transB, dtype, ctypes.c_float(alpha),
+        ctypes.c_void_p(A), lda, strideA, ctypes.c_void_p(B), ldb, strideB, ctypes.c_float(beta),
+        ctypes.c_void_p(C), ldc, strideC, ctypes.byref(epilogue) if epilogue is not None else None,
+        ctypes.c_void_p(stream))
+    if check and st != GEMM_OK:
+        raise GemmError(st, "gemm_run_batched")
     return st
 
 

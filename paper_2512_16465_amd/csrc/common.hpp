@@ -18,7 +18,31 @@ struct Args {
     const void* B; int64_t ldb;
     void* C; int64_t ldc;
     const void* bias;
+    // strided batch: matrix b of each operand starts b * stride elements after the first one;
+    // a launch covers `batch` matrices with blockIdx.y (batch == 1: strides unused)
+    int64_t strideA, strideB, strideC;
+    int32_t batch;
 };
+
+__host__ __device__ __forceinline__ int elem_bytes(int dtype) { return dtype == DT_F32 ? 4 : 2; }
+
+// First statement of every kernel that takes a batch: point the operands at the matrices of
+// this workgroup's batch entry.
+__device__ __forceinline__ void select_batch(Args& a) {
+    const int64_t b = blockIdx.y;
+    a.A = (const char*)a.A + b * a.strideA * elem_bytes(a.dtype);
+    a.B = (const char*)a.B + b * a.strideB * elem_bytes(a.dtype);
+    a.C = (char*)a.C + b * a.strideC * elem_bytes(a.out_dtype);
+}
+
+// Rows of C can be read and written with vectors of four elements (16 bytes of fp32, 8 bytes of a
+// 16-bit type) in every matrix of the batch.
+inline int c_rows_take_vec4(const Args& a) {
+    const int64_t align = a.out_dtype == DT_F32 ? 16 : 8;
+    if (a.ldc % 4 != 0 || (uintptr_t)a.C % align != 0) return 0;
+    if (a.batch > 1 && (a.strideC * elem_bytes(a.out_dtype)) % align != 0) return 0;
+    return 1;
+}
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;

@@ -22,21 +22,26 @@ using gemm::Args;
 
 bool valid_dtype(int d) { return d == GEMM_F32 || d == GEMM_F16 || d == GEMM_BF16; }
 
-// Picks a tile variant for the macro-tile family by comparing two estimates of the run time, in
-// units of "one 128x128xK block on one compute unit at the large tile's speed".  The 256x256 tile
-// (16x16x32 MFMA, direct-to-LDS) does four blocks per workgroup, one workgroup per compute unit;
-// the 128x128 tile does one block per workgroup at 0.62 of that speed per compute unit (measured
-// on 8192^3: 890 against 1440 TFLOP/s).  Rounds are counted per compute unit, so a grid that
-// leaves most of the chip idle, or a dimension of 128 that would waste half of every large tile,
-// favours the small tile.  Operands of 2 GiB or more take the register-staged siblings (the
-// direct loads mask lanes with a fixed 2 GiB - 16 offset).
+// Picks a tile variant for the macro-tile family by comparing two estimates of the run time in
+// microseconds.  A workgroup of the 256x256 tile (16x16x32 MFMA, direct-to-LDS, one workgroup per
+// compute unit) takes kLargePerK * K for its k loop plus kLargeFixed for filling the pipeline
+// and for the epilogue, which nothing overlaps; the 128x128 tile (two workgroups per compute
+// unit, each other's epilogue hidden behind the other's k loop) takes kSmallPerK * K + kSmallFixed
+// per tile and compute unit.  Measured: 8192^3 in 744 us with the large tile (4 rounds) and
+// 1235 us with the small one (16 tiles per compute unit); 32 x 2048x2048x128 in 122 us (8
+// rounds) and 83 us (32 tiles per compute unit).  So long k loops favour the large tile (2.2x
+// the flops per cycle), short ones (K below about 560) the small one, and so does a grid that
+// leaves most of the chip idle or a dimension that would waste half of every large tile.
+// Operands of 2 GiB or more take the register-staged siblings (the direct loads mask lanes with
+// a fixed 2 GiB - 16 offset).
 constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant = 5, kSmallTileFallback = 3;
-constexpr double kSmallTileRelativeSpeed = 0.62;
+constexpr double kLargePerK = 0.0209, kLargeFixed = 15.0, kSmallPerK = 0.0094, kSmallFixed = 1.4;
+constexpr double kSmallAlonePerK = 0.0055;   // a small-tile workgroup that has its compute unit to itself (512x512x4096: 23 us)
 // A last round that fills less than this fraction of the compute units is split along K (when the
 // variant can): each of its tiles goes to several workgroups, each over a share of the k slabs of
 // at least kMinSlabsPerPart, and a second kernel adds the parts.  The split costs a round trip of
-// the partial tiles through memory and a launch, estimated at kSplitOverhead blocks.
-constexpr double kSplitBelow = 0.6, kSplitOverhead = 0.5;
+// the partial tiles through memory and a launch, estimated at an eighth of a whole k loop.
+constexpr double kSplitBelow = 0.6, kSplitOverhead = 0.125;
 constexpr int kMaxParts = 16, kMinSlabsPerPart = 16;
 
 // parts per tile of the trailing `tail` tiles (1 = no split)
@@ -56,13 +61,15 @@ constexpr int64_t kF32MinTiles = 16;       // below this many 128x128 tiles the 
 TileChoice choose_tile(const Args& a, int num_cus) {
     if (a.dtype == gemm::DT_F32) return TileChoice{kF32TileVariant, 0, 1};
     const int64_t cus = num_cus > 0 ? num_cus : 256;
-    const int64_t large = ((a.M + 255) / 256) * ((a.N + 255) / 256), small = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+    // a batch multiplies the number of workgroups; its trailing round is never split along K
+    const int64_t large = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch, small = ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
     const bool large_ok = gemm::tile_variant_supports(a, kLargeTileVariant);
     const int64_t tail = large % cus;
-    const int parts = large_ok ? tail_parts(tail, cus, a.K) : 1;
-    double t_large = 4.0 * (double)(large / cus);
-    if (tail) t_large += parts > 1 ? 4.0 / parts + kSplitOverhead : 4.0;
-    const double t_small = (double)((small + cus - 1) / cus) / kSmallTileRelativeSpeed;
+    const int parts = (large_ok && a.batch == 1) ? tail_parts(tail, cus, a.K) : 1;
+    const double k = (double)a.K;
+    double t_large = (double)(large / cus) * (kLargePerK * k + kLargeFixed);
+    if (tail) t_large += parts > 1 ? kLargePerK * k * (1.0 / parts + kSplitOverhead) + kLargeFixed : kLargePerK * k + kLargeFixed;
+    const double t_small = small <= cus ? kSmallAlonePerK * k + kSmallFixed : (double)((small + cus - 1) / cus) * (kSmallPerK * k + kSmallFixed);
     if (t_large <= t_small) {
         if (!large_ok) return TileChoice{kLargeTileFallback, 0, 1};
         return TileChoice{kLargeTileVariant, (int)(large - tail), parts};
@@ -165,15 +172,21 @@ GEMM_EXPORT const char* gemm_variant_name(gemm_kernel_t kernel, int32_t variant)
     return nullptr;
 }
 
-GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_t K,
-                                   gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,
-                                   float alpha, const void* A, int64_t lda,
-                                   const void* B, int64_t ldb,
-                                   float beta, void* C, int64_t ldc,
-                                   const gemm_epilogue_t* epilogue, void* stream_) {
+namespace {
+
+// Largest number of matrices one launch takes (the y dimension of a grid).
+constexpr int64_t kMaxBatchPerLaunch = 65535;
+
+gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, int64_t K,
+                        gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,
+                        float alpha, const void* A, int64_t lda, int64_t strideA,
+                        const void* B, int64_t ldb, int64_t strideB,
+                        float beta, void* C, int64_t ldc, int64_t strideC,
+                        const gemm_epilogue_t* epilogue, void* stream_) {
     // ---- validation: nothing is launched and C is untouched on any error below ----
     if (!h) return GEMM_ERR_INVALID_ARG;
-    if (M < 0 || N < 0 || K < 0) return GEMM_ERR_INVALID_ARG;
+    if (M < 0 || N < 0 || K < 0 || batch < 0) return GEMM_ERR_INVALID_ARG;
+    if (strideA < 0 || strideB < 0 || strideC < 0) return GEMM_ERR_INVALID_ARG;
     if ((transA != GEMM_OP_N && transA != GEMM_OP_T) || (transB != GEMM_OP_N && transB != GEMM_OP_T)) return GEMM_ERR_INVALID_ARG;
     if (!valid_dtype(dtype)) return GEMM_ERR_INVALID_ARG;
     gemm_epilogue_t epi;
@@ -188,7 +201,22 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
     if (M > 0 && K > 0 && !A) return GEMM_ERR_INVALID_ARG;
     if (N > 0 && K > 0 && !B) return GEMM_ERR_INVALID_ARG;
     if (epi.out_dtype != dtype && epi.out_dtype != GEMM_F32) return GEMM_ERR_UNSUPPORTED;
-    if (M == 0 || N == 0) return GEMM_OK;
+    // the matrices of C must not overlap one another
+    if (batch > 1 && M > 0 && N > 0 && strideC < (M - 1) * ldc + N) return GEMM_ERR_INVALID_ARG;
+    if (M == 0 || N == 0 || batch == 0) return GEMM_OK;
+    if (batch > kMaxBatchPerLaunch) {
+        // more matrices than one grid holds: consecutive launches over consecutive parts of the batch
+        const int64_t ea = gemm::elem_bytes((int)dtype), ec = gemm::elem_bytes((int)epi.out_dtype);
+        for (int64_t b0 = 0; b0 < batch; b0 += kMaxBatchPerLaunch) {
+            const int64_t nb = batch - b0 < kMaxBatchPerLaunch ? batch - b0 : kMaxBatchPerLaunch;
+            const gemm_status_t st = run_batch(h, nb, M, N, K, transA, transB, dtype, alpha,
+                                               A ? (const char*)A + b0 * strideA * ea : nullptr, lda, strideA,
+                                               B ? (const char*)B + b0 * strideB * ea : nullptr, ldb, strideB, beta,
+                                               (char*)C + b0 * strideC * ec, ldc, strideC, epilogue, stream_);
+            if (st != GEMM_OK) return st;
+        }
+        return GEMM_OK;
+    }
 
     hipStream_t stream = (hipStream_t)stream_;
     Args a;
@@ -198,6 +226,11 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
     a.alpha = alpha; a.beta = beta;
     a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.C = C; a.ldc = ldc;
     a.bias = epi.bias;
+    a.batch = (int32_t)batch;
+    a.strideA = batch > 1 ? strideA : 0; a.strideB = batch > 1 ? strideB : 0; a.strideC = batch > 1 ? strideC : 0;
+    // the matrix-core kernels read 16-byte vectors: every matrix of the batch must start on a 16-byte boundary
+    const int64_t in_bytes = gemm::elem_bytes(a.dtype);
+    const bool batch_aligned = batch == 1 || ((strideA * in_bytes) % 16 == 0 && (strideB * in_bytes) % 16 == 0);
 
     // ---- plan ----
     gemm_plan_t plan{GEMM_KERNEL_GENERAL, 0, 1};
@@ -208,7 +241,7 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
     } else if (h->forced) {
         plan = h->plan;
         if (plan.kernel == GEMM_KERNEL_MFMA_TILE) {
-            if (!gemm::tile_supports(a)) return GEMM_ERR_UNSUPPORTED;
+            if (!gemm::tile_supports(a) || !batch_aligned) return GEMM_ERR_UNSUPPORTED;
             if (plan.variant < 0) {
                 const TileChoice c = choose_tile(a, h->num_cus);
                 plan.variant = c.variant;
@@ -216,7 +249,7 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
             }
             if (!gemm::tile_variant_supports(a, plan.variant)) return GEMM_ERR_UNSUPPORTED;
             if (plan.split_k < 1) plan.split_k = 1;
-            if (plan.split_k > 1 && !gemm::tile_variant_splits(plan.variant)) return GEMM_ERR_UNSUPPORTED;
+            if (plan.split_k > 1 && (!gemm::tile_variant_splits(plan.variant) || batch > 1)) return GEMM_ERR_UNSUPPORTED;
             if (plan.split_k > 1 && split_first < 0) {
                 // a forced split applies to the trailing partial round, or to every tile of a grid smaller than one round
                 const gemm::TileVariantInfo* info = gemm::tile_variant_info(plan.variant);
@@ -226,7 +259,7 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
                 if (split_first == tiles) plan.split_k = 1;
             }
         } else if (plan.kernel == GEMM_KERNEL_SKINNY) {
-            if (!gemm::skinny_supports(a)) return GEMM_ERR_UNSUPPORTED;
+            if (!gemm::skinny_supports(a) || !batch_aligned) return GEMM_ERR_UNSUPPORTED;
             if (plan.variant >= 0 && plan.variant != gemm::skinny_variant_of(a)) return GEMM_ERR_UNSUPPORTED;
             plan.variant = gemm::skinny_variant_of(a);
             if (plan.split_k == 0) plan.split_k = gemm::skinny_default_split(a, h->num_cus);
@@ -236,10 +269,10 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
     } else {
         // The paper's roofline rule (Section 4.3) in arithmetic form: few rows of C make the
         // call bandwidth-limited (stream B once, split K); otherwise it is a matrix-core problem.
-        if (gemm::skinny_supports(a) && N >= 256 && K >= 512) {
+        if (gemm::skinny_supports(a) && batch_aligned && N >= 256 && K >= 512) {
             plan = gemm_plan_t{GEMM_KERNEL_SKINNY, gemm::skinny_variant_of(a), gemm::skinny_default_split(a, h->num_cus)};
-        } else if (gemm::tile_supports(a) &&
-                   (a.dtype != gemm::DT_F32 || ((a.M + 127) / 128) * ((a.N + 127) / 128) >= kF32MinTiles)) {
+        } else if (gemm::tile_supports(a) && batch_aligned &&
+                   (a.dtype != gemm::DT_F32 || ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch >= kF32MinTiles)) {
             const TileChoice c = choose_tile(a, h->num_cus);
             plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, c.variant, c.parts};
             split_first = c.first_split_tile;
@@ -256,7 +289,15 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
             const gemm_status_t st = ensure_workspace(h, need, stream);
             if (st != GEMM_OK) return st;
         }
-        e = gemm::launch_skinny(a, plan.split_k, h->workspace, stream);
+        // one matrix per launch (the slices of a split share the workspace, in stream order)
+        Args one = a;
+        one.batch = 1;
+        for (int64_t b = 0; b < batch && e == hipSuccess; ++b) {
+            one.A = (const char*)a.A + b * a.strideA * in_bytes;
+            one.B = (const char*)a.B + b * a.strideB * in_bytes;
+            one.C = (char*)a.C + b * a.strideC * gemm::elem_bytes(a.out_dtype);
+            e = gemm::launch_skinny(one, plan.split_k, h->workspace, stream);
+        }
     } else if (plan.kernel == GEMM_KERNEL_MFMA_TILE) {
         gemm::TileSplit split{0, 1, nullptr};
         if (plan.split_k > 1) {
@@ -279,4 +320,25 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
     if (e != hipSuccess) return GEMM_ERR_HIP;
     h->last = plan;
     return GEMM_OK;
+}
+
+}  // namespace
+
+GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_t K,
+                                   gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,
+                                   float alpha, const void* A, int64_t lda,
+                                   const void* B, int64_t ldb,
+                                   float beta, void* C, int64_t ldc,
+                                   const gemm_epilogue_t* epilogue, void* stream) {
+    return run_batch(h, 1, M, N, K, transA, transB, dtype, alpha, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, epilogue, stream);
+}
+
+GEMM_EXPORT gemm_status_t gemm_run_batched(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, int64_t K,
+                                           gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,
+                                           float alpha, const void* A, int64_t lda, int64_t strideA,
+                                           const void* B, int64_t ldb, int64_t strideB,
+                                           float beta, void* C, int64_t ldc, int64_t strideC,
+                                           const gemm_epilogue_t* epilogue, void* stream) {
+    return run_batch(h, batch, M, N, K, transA, transB, dtype, alpha, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC,
+                     epilogue, stream);
 }

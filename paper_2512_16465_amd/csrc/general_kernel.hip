@@ -16,6 +16,7 @@ constexpr int GT = 16;   // 16 x 16 threads per workgroup
 __global__ __launch_bounds__(GT * GT) void general_kernel(Args a) {
     __shared__ float sa[GT][GT + 1];
     __shared__ float sb[GT][GT + 1];
+    select_batch(a);
     const int tx = threadIdx.x, ty = threadIdx.y;
     const int64_t tiles_n = (a.N + GT - 1) / GT;
     const int64_t tiles_m = (a.M + GT - 1) / GT;
@@ -62,7 +63,7 @@ hipError_t launch_general(const Args& a, hipStream_t stream) {
     const int64_t tiles = ((a.M + GT - 1) / GT) * ((a.N + GT - 1) / GT);
     if (tiles == 0) return hipSuccess;
     const int64_t grid = tiles < (1 << 20) ? tiles : (1 << 20);
-    hipLaunchKernelGGL(general_kernel, dim3((unsigned)grid), dim3(GT, GT), 0, stream, a);
+    hipLaunchKernelGGL(general_kernel, dim3((unsigned)grid, (unsigned)a.batch), dim3(GT, GT), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -127,6 +127,7 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     constexpr int RING = NS * C::STAGE;
     constexpr int LDS_BYTES = RING > EL::BYTES ? RING : EL::BYTES;
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+    select_batch(a);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -388,10 +389,10 @@ hipError_t launch_dma16_variant(const Args& a, int group_m, const TileSplit& spl
     const int tiles = tiles_m * tiles_n;
     const bool splits = split.parts > 1 && split.first_tile < tiles;
     const int split_first = splits ? split.first_tile : tiles, split_parts = splits ? split.parts : 1;
-    const dim3 grid((unsigned)(split_first + (tiles - split_first) * split_parts)), block(C::NT);
+    const dim3 grid((unsigned)(split_first + (tiles - split_first) * split_parts), (unsigned)a.batch), block(C::NT);
     const bool bf = a.dtype == DT_BF16;
     const bool akc = !a.transA, bkc = a.transB != 0;
-    const int c_vec_ok = (a.ldc % 4 == 0) && ((uintptr_t)a.C % (a.out_dtype == DT_F32 ? 16 : 8) == 0);
+    const int c_vec_ok = c_rows_take_vec4(a);
 #define GEMM_TILE_LAUNCH(BF, AKC, BKC) \
     hipLaunchKernelGGL((tile_dma16_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok, \
                        split_first, split_parts, split.partials)

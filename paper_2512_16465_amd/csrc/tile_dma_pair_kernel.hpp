@@ -30,6 +30,7 @@ __global__ __launch_bounds__(C::NT) void tile_dma_pair_kernel(Args a, int tiles_
     constexpr int RING = NS * C::STAGE;
     constexpr int LDS_BYTES = RING > EL::BYTES ? RING : EL::BYTES;
     __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+    select_batch(a);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -257,10 +258,10 @@ __global__ __launch_bounds__(C::NT) void tile_dma_pair_kernel(Args a, int tiles_
 template <class C>
 hipError_t launch_dma_pair_variant(const Args& a, int group_m, hipStream_t stream) {
     const int tiles_m = (int)((a.M + C::BM - 1) / C::BM), tiles_n = (int)((a.N + C::BN - 1) / C::BN);
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(C::NT);
+    const dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)a.batch), block(C::NT);
     const bool bf = a.dtype == DT_BF16;
     const bool akc = !a.transA, bkc = a.transB != 0;
-    const int c_vec_ok = (a.ldc % 4 == 0) && ((uintptr_t)a.C % (a.out_dtype == DT_F32 ? 16 : 8) == 0);
+    const int c_vec_ok = c_rows_take_vec4(a);
     const bool plain = plain_epilogue_applies<C>(a);
 #define GEMM_TILE_LAUNCH(BF, AKC, BKC)                                                                             \
     do {                                                                                                           \

@@ -92,6 +92,7 @@ __global__ __launch_bounds__(F32Cfg::NT, 2) void tile_f32_kernel(Args a, int til
     using EL = EpiLayout<C>;
     constexpr int LDS_BYTES = 2 * C::STAGE > EL::BYTES ? 2 * C::STAGE : EL::BYTES;
     __shared__ __attribute__((aligned(128))) char lds[LDS_BYTES];
+    select_batch(a);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -167,9 +168,9 @@ __global__ __launch_bounds__(F32Cfg::NT, 2) void tile_f32_kernel(Args a, int til
 inline hipError_t launch_f32_variant(const Args& a, int group_m, hipStream_t stream) {
     using C = F32Cfg;
     const int tiles_m = (int)((a.M + C::BM - 1) / C::BM), tiles_n = (int)((a.N + C::BN - 1) / C::BN);
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(C::NT);
+    const dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)a.batch), block(C::NT);
     const bool akc = !a.transA, bkc = a.transB != 0;
-    const int c_vec_ok = (a.ldc % 4 == 0) && ((uintptr_t)a.C % 16 == 0);
+    const int c_vec_ok = c_rows_take_vec4(a);
 #define GEMM_TILE_LAUNCH(AKC, BKC) \
     hipLaunchKernelGGL((tile_f32_kernel<AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok)
     if (akc && bkc) GEMM_TILE_LAUNCH(true, true);

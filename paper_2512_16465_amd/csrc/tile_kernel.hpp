@@ -409,6 +409,7 @@ __global__ __launch_bounds__(C::NT) void tile_kernel(Args a, int tiles_m, int ti
     using EL = EpiLayout<C>;
     constexpr int LDS_BYTES = 2 * C::STAGE > EL::BYTES ? 2 * C::STAGE : EL::BYTES;
     __shared__ __attribute__((aligned(128))) char lds[LDS_BYTES];
+    select_batch(a);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -575,11 +576,11 @@ __global__ __launch_bounds__(C::NT) void tile_kernel(Args a, int tiles_m, int ti
 template <class C>
 hipError_t launch_variant(const Args& a, int group_m, hipStream_t stream) {
     const int tiles_m = (int)((a.M + C::BM - 1) / C::BM), tiles_n = (int)((a.N + C::BN - 1) / C::BN);
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(C::NT);
+    const dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)a.batch), block(C::NT);
     const bool bf = a.dtype == DT_BF16;
     const bool akc = !a.transA, bkc = a.transB != 0;
     // vector access to C needs 16-byte (fp32) or 8-byte (16-bit types) aligned rows
-    const int c_vec_ok = (a.ldc % 4 == 0) && ((uintptr_t)a.C % (a.out_dtype == DT_F32 ? 16 : 8) == 0);
+    const int c_vec_ok = c_rows_take_vec4(a);
 #define GEMM_TILE_LAUNCH(BF, AKC, BKC)                                                                       \
     hipLaunchKernelGGL((tile_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, \
                        c_vec_ok)

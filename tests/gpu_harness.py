@@ -144,3 +144,71 @@ def expected_bits_exact(cfg: wl.Config, inputs) -> np.ndarray:
 def c_bits_as_uint(cfg: wl.Config, c_bits2d: np.ndarray) -> np.ndarray:
     x = np.ascontiguousarray(c_bits2d[:, : cfg.N])
     return x.view(np.uint32) if cfg.out_dtype == wl.F32 else x
+
+
+class BatchedDeviceProblem:
+    """A strided batch on the GPU.  `cfg` describes one product; matrix b of each operand lies
+    b * stride elements into its array (a stride of 0 shares the operand), the gaps between
+    matrices hold a sentinel (NaN in C when it is write-only)."""
+
+    def __init__(self, cfg: wl.Config, batch: int, strideA: int, strideB: int, strideC: int, seed: int, integer: bool = False):
+        self.cfg, self.batch = cfg, batch
+        self.sA, self.sB, self.sC = strideA, strideB, strideC
+        one = lambda dt, n: wl.to_bits(np.full(n, 7.0, np.float32), dt)
+        a_len = (cfg.a_shape()[0] - 1) * cfg.ld_a() + cfg.a_shape()[1]
+        b_len = (cfg.b_shape()[0] - 1) * cfg.ld_b() + cfg.b_shape()[1]
+        c_len = (cfg.M - 1) * cfg.ld_c() + cfg.N
+        A = one(cfg.dtype, (batch - 1) * strideA + a_len)
+        B = one(cfg.dtype, (batch - 1) * strideB + b_len)
+        C = one(cfg.out_dtype, (batch - 1) * strideC + c_len)
+        bias = None
+        for b in range(batch):
+            inp = wl.make_integer_inputs(cfg, seed + b, -2, 2)[0] if integer else wl.make_inputs(cfg, seed + b)
+            if strideA or b == 0:
+                A[b * strideA: b * strideA + a_len] = inp["A"][:a_len]
+            if strideB or b == 0:
+                B[b * strideB: b * strideB + b_len] = inp["B"][:b_len]
+            if inp["C"] is not None:
+                C[b * strideC: b * strideC + c_len] = inp["C"][:c_len]
+            if b == 0:
+                bias = inp["bias"]
+        self.host = {"A": A, "B": B, "C": C if cfg.beta != 0.0 else None, "bias": bias}
+        self.A, self.B = upload(A, cfg.dtype), upload(B, cfg.dtype)
+        self.bias = upload(bias, cfg.bias_dtype)
+        self.C = upload(C, cfg.out_dtype) if cfg.beta != 0.0 else nan_filled(C.size, cfg.out_dtype)
+        self.c_before = wl.torch_to_bits(self.C)
+        self.c_len = c_len
+
+    def run(self, handle, check=True):
+        cfg = self.cfg
+        epi = lg.make_epilogue(cfg.out_dtype, self.bias.data_ptr() if self.bias is not None else 0, cfg.bias_dtype, cfg.act)
+        return lg.gemm_run_batched(handle, self.batch, cfg.M, cfg.N, cfg.K, cfg.transA, cfg.transB, cfg.dtype, cfg.alpha,
+                                   self.A.data_ptr(), cfg.ld_a(), self.sA, self.B.data_ptr(), cfg.ld_b(), self.sB,
+                                   cfg.beta, self.C.data_ptr(), cfg.ld_c(), self.sC, epi, stream_ptr(), check=check)
+
+    def oracle_problem(self) -> oracle.Problem:
+        cfg, h = self.cfg, self.host
+        return oracle.Problem(cfg.M, cfg.N, cfg.K, cfg.transA, cfg.transB, cfg.dtype, h["A"], cfg.ld_a(), h["B"], cfg.ld_b(),
+                              alpha=cfg.alpha, beta=cfg.beta, C=h["C"], ldc=cfg.ld_c(), c_dtype=cfg.out_dtype,
+                              bias=h["bias"], bias_dtype=cfg.bias_dtype, act=cfg.act)
+
+    def check(self, what: str, exact: bool = False):
+        """Every matrix of the batch against the oracle; everything between the matrices untouched."""
+        torch.cuda.synchronize()
+        cfg = self.cfg
+        after = wl.torch_to_bits(self.C)
+        ref, _, mag = oracle.gemm_strided_batched(self.oracle_problem(), self.batch, self.sA, self.sB, self.sC, want_bounds=True)
+        touched = np.zeros(after.size, dtype=bool)
+        for b in range(self.batch):
+            flat = np.zeros(cfg.M * cfg.ld_c(), dtype=after.dtype)
+            flat[: self.c_len] = after[b * self.sC: b * self.sC + self.c_len]
+            got = decode_c(cfg, flat.reshape(cfg.M, cfg.ld_c()))
+            if exact:
+                want = oracle.decode(cfg.out_dtype, oracle.encode(cfg.out_dtype, ref[b]))
+                assert np.array_equal(got, want), f"{what}: matrix {b}: {np.sum(got != want)} wrong"
+            else:
+                assert_close(cfg, got, ref[b], mag[b], f"{what}: matrix {b}")
+            idx = (b * self.sC + np.arange(cfg.M)[:, None] * cfg.ld_c() + np.arange(cfg.N)[None, :]).reshape(-1)
+            touched[idx] = True
+        same = after.view(np.uint8).reshape(after.size, -1) == self.c_before.view(np.uint8).reshape(after.size, -1)
+        assert np.all(same.all(axis=1)[~touched]), f"{what}: memory between the matrices of C was written"

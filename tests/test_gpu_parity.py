@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2512_16465_amd as lg
 import workloads as wl
-from gpu_harness import (DeviceProblem, assert_close, c_bits_as_uint, check_full, decode_c,
+from gpu_harness import (BatchedDeviceProblem, DeviceProblem, assert_close, c_bits_as_uint, check_full, decode_c,
                          expected_bits_exact, oracle_problem, stream_ptr)
 
 pytestmark = pytest.mark.gpu
@@ -456,3 +456,76 @@ def test_invalid_arguments_leave_c_untouched(handle):
     assert "invalid" in lg.gemm_status_string(E)
     after = p.result_bits()
     assert np.array_equal(before.view(np.uint16), after.view(np.uint16))
+
+
+# ------------------------------------------------------------------ strided batches
+
+def test_batched_tile_variants(handle):
+    # three products of 2 x 2 ragged tiles per matrix, padded strides, beta, bias and activation
+    cfg = base_cfg(300, 264, 72, 0, 1, wl.BF16, wl.BF16, alpha=0.5, beta=1.0, a_dist=("normal", 1.0), b_dist=("normal", 0.3),
+                   c_dist=("normal", 1.0), bias_dist=("normal", 1.0), bias_dtype=wl.F32, act=wl.ACT_GELU_TANH, lda=80, ldc=272)
+    for v in tile_variants():
+        print(f"batched tile variant {v}", flush=True)
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v, 1)
+        p = BatchedDeviceProblem(cfg, 3, 300 * 80 + 16, 264 * 72 + 8, 300 * 272 + 4, seed=60)
+        p.run(handle)
+        assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_MFMA_TILE, v, 1)
+        p.check(f"batched tile variant {v}")
+    # a split of the k range is refused for a batch
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, 10, 2)
+    p = BatchedDeviceProblem(cfg, 3, 300 * 80 + 16, 264 * 72 + 8, 300 * 272 + 4, seed=60)
+    assert p.run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED
+    lg.gemm_set_plan(handle)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (1, 0), (1, 1)])
+def test_batched_layouts_shared_operand_and_automatic_choice(handle, ta, tb):
+    # B shared by the whole batch (stride 0), fp16 in and fp32 out, automatic plan
+    cfg = base_cfg(136, 520, 200, ta, tb, wl.F16, wl.F32, a_dist=("normal", 1.0), b_dist=("normal", 0.2))
+    p = BatchedDeviceProblem(cfg, 5, cfg.stride_a() + 8, 0, cfg.stride_c(), seed=70 + 2 * ta + tb)
+    p.run(handle)
+    assert lg.gemm_get_last_plan(handle)[0] == lg.GEMM_KERNEL_MFMA_TILE
+    p.check(f"batched layout {ta}{tb}")
+
+
+def test_batched_integer_exact_in_every_family(handle):
+    cases = [
+        ("tile", base_cfg(264, 136, 328, 0, 1, wl.BF16, wl.F32, alpha=1.0, beta=1.0), 4, lg.GEMM_KERNEL_MFMA_TILE),
+        ("f32 tile", base_cfg(136, 264, 52, 0, 0, wl.F32, wl.F32), 9, lg.GEMM_KERNEL_MFMA_TILE),
+        ("skinny", base_cfg(8, 512, 1024, 0, 0, wl.BF16, wl.BF16, alpha=1.0, beta=1.0), 3, lg.GEMM_KERNEL_SKINNY),
+        ("skinny nt", base_cfg(20, 512, 1024, 0, 1, wl.F16, wl.F32), 3, lg.GEMM_KERNEL_SKINNY),
+        ("general", base_cfg(37, 29, 53, 1, 0, wl.F32, wl.F32, alpha=1.0, beta=1.0), 6, lg.GEMM_KERNEL_GENERAL),
+    ]
+    for name, cfg, batch, family in cases:
+        print(f"batched integer {name}", flush=True)
+        p = BatchedDeviceProblem(cfg, batch, cfg.stride_a(), cfg.stride_b(), cfg.stride_c() + 8, seed=80, integer=True)
+        p.run(handle)
+        assert lg.gemm_get_last_plan(handle)[0] == family, name
+        p.check(f"batched integer {name}", exact=True)
+
+
+def test_batched_unaligned_strides_take_the_general_kernel(handle):
+    cfg = base_cfg(130, 72, 40, 0, 1, wl.BF16, wl.BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.5))
+    p = BatchedDeviceProblem(cfg, 3, cfg.stride_a() + 3, cfg.stride_b() + 1, cfg.stride_c() + 1, seed=90)
+    p.run(handle)
+    assert lg.gemm_get_last_plan(handle)[0] == lg.GEMM_KERNEL_GENERAL
+    p.check("batched unaligned")
+    # the tile family refuses such strides when forced
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, -1, 0)
+    assert p.run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED
+    lg.gemm_set_plan(handle)
+
+
+def test_batched_argument_errors_and_empty_batch(handle):
+    cfg = base_cfg(64, 64, 64, 0, 0, wl.BF16, wl.BF16)
+    p = BatchedDeviceProblem(cfg, 2, cfg.stride_a(), cfg.stride_b(), cfg.stride_c(), seed=1)
+    before = wl.torch_to_bits(p.C).copy()
+    args = dict(handle=handle, M=64, N=64, K=64, transA=0, transB=0, dtype=wl.BF16, alpha=1.0, A=p.A.data_ptr(), lda=64,
+                B=p.B.data_ptr(), ldb=64, beta=0.0, C=p.C.data_ptr(), ldc=64, epilogue=None, stream=stream_ptr(), check=False)
+    ok = dict(batch=2, strideA=4096, strideB=4096, strideC=4096)
+    assert lg.gemm_run_batched(**{**args, **ok, "batch": -1}) == lg.GEMM_ERR_INVALID_ARG
+    assert lg.gemm_run_batched(**{**args, **ok, "strideA": -1}) == lg.GEMM_ERR_INVALID_ARG
+    assert lg.gemm_run_batched(**{**args, **ok, "strideC": 4095}) == lg.GEMM_ERR_INVALID_ARG      # results would overlap
+    assert lg.gemm_run_batched(**{**args, **ok, "batch": 0}) == lg.GEMM_OK
+    torch.cuda.synchronize()
+    assert np.array_equal(wl.torch_to_bits(p.C).view(np.uint8), before.view(np.uint8))

@@ -392,3 +392,28 @@ def test_activation_applies_after_the_whole_affine_part():
                      bias=np.array([bias], np.float32), bias_dtype=F32, act=ACT_GELU_ERF)
     x = alpha * a * b + beta * c + bias
     assert abs(oracle.gemm_full(p)[0, 0] - 0.5 * x * (1 + math.erf(x / math.sqrt(2)))) < 1e-15
+
+
+def test_strided_batch_against_int64_einsum():
+    """A strided batch is `batch` independent products whose matrices lie b * stride elements into
+    their arrays: integer data against numpy's int64 einsum, with padded strides, a shared A
+    (stride 0), beta and bias."""
+    rng = np.random.default_rng(5)
+    batch, M, N, K = 5, 3, 4, 6
+    lda, ldb, ldc = K + 2, N + 1, N + 3
+    sB, sC = K * ldb + 7, M * ldc + 5
+    A = rng.integers(-3, 4, size=(M, K))
+    B = rng.integers(-3, 4, size=(batch, K, N))
+    C0 = rng.integers(-3, 4, size=(batch, M, N))
+    bias = rng.integers(-2, 3, size=N)
+    a_st = np.full(M * lda, 9.0, np.float32); a_st.reshape(M, lda)[:, :K] = A
+    b_st = np.full(batch * sB, 9.0, np.float32)
+    c_st = np.full(batch * sC, 9.0, np.float32)
+    for b in range(batch):
+        b_st[b * sB: b * sB + K * ldb].reshape(K, ldb)[:, :N] = B[b]
+        c_st[b * sC: b * sC + M * ldc].reshape(M, ldc)[:, :N] = C0[b]
+    prob = oracle.Problem(M, N, K, 0, 0, oracle.F32, a_st, lda, b_st, ldb, alpha=2.0, beta=-1.0, C=c_st, ldc=ldc,
+                          c_dtype=oracle.F32, bias=bias.astype(np.float32), bias_dtype=oracle.F32)
+    got = oracle.gemm_strided_batched(prob, batch, 0, sB, sC)
+    want = 2 * np.einsum("mk,bkn->bmn", A, B) - C0 + bias[None, None, :]
+    assert got.shape == (batch, M, N) and np.array_equal(got, want.astype(np.float64))

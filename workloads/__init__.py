@@ -81,6 +81,7 @@ class Config:
     lda: int = 0               # 0 = minimal
     ldb: int = 0
     ldc: int = 0
+    batch: int = 1             # > 1: a strided batch, the matrices of each operand packed one after the other
     note: str = ""
 
     # stored shapes (rows, cols) of each operand
@@ -89,9 +90,13 @@ class Config:
     def ld_a(self): return self.lda or self.a_shape()[1]
     def ld_b(self): return self.ldb or self.b_shape()[1]
     def ld_c(self): return self.ldc or self.N
+    # elements from one matrix of the batch to the next
+    def stride_a(self): return self.a_shape()[0] * self.ld_a()
+    def stride_b(self): return self.b_shape()[0] * self.ld_b()
+    def stride_c(self): return self.M * self.ld_c()
 
     def flops(self) -> int:
-        return 2 * self.M * self.N * self.K
+        return 2 * self.M * self.N * self.K * self.batch
 
     def algorithmic_bytes(self) -> int:
         """Each operand once; C_in only when beta != 0; bias when present."""
@@ -99,6 +104,7 @@ class Config:
         n += self.M * self.N * itemsize(self.out_dtype)
         if self.beta != 0.0:
             n += self.M * self.N * itemsize(self.out_dtype)
+        n *= self.batch
         if self.bias_dist is not None:
             n += self.N * itemsize(self.bias_dtype)
         return n
@@ -150,6 +156,9 @@ EXTRA_CONFIGS: Dict[str, Config] = {
     "X7": Config("X7", 32, 16384, 16384, 0, 1, BF16, BF16, alpha=1.0, beta=1.0,
                  a_dist=("normal", 1.0), b_dist=("normal", 0.02), c_dist=("normal", 1.0),
                  note="bf16 32x16384x16384 NT skinny (B stored N x K, a weight matrix kept as [out, in]), alpha=beta=1"),
+    "X8": Config("X8", 2048, 2048, 128, 0, 1, BF16, BF16, batch=32,
+                 a_dist=("normal", 1.0), b_dist=("normal", 128 ** -0.5),
+                 note="bf16 strided batch of 32 products 2048x2048x128 NT (the per-head score products of attention), bf16 out"),
 }
 
 
@@ -187,10 +196,14 @@ def _store(x: np.ndarray, ld: int, dtype: int) -> np.ndarray:
 def make_inputs(cfg: Config, seed: int = DEFAULT_SEED) -> Dict[str, Optional[np.ndarray]]:
     """Operands of cfg as 1-D storage arrays: keys A, B, C (None when beta == 0), bias (or None)."""
     out: Dict[str, Optional[np.ndarray]] = {}
-    out["A"] = _store(_draw(np.random.default_rng([seed, 1]), cfg.a_dist, cfg.a_shape()), cfg.ld_a(), cfg.dtype)
-    out["B"] = _store(_draw(np.random.default_rng([seed, 2]), cfg.b_dist, cfg.b_shape()), cfg.ld_b(), cfg.dtype)
+    # a batch is drawn as one tall matrix: with the dense strides of Config its storage is the
+    # matrices of the batch one after the other
+    nb = cfg.batch
+    tall = lambda shape: (nb * shape[0], shape[1])
+    out["A"] = _store(_draw(np.random.default_rng([seed, 1]), cfg.a_dist, tall(cfg.a_shape())), cfg.ld_a(), cfg.dtype)
+    out["B"] = _store(_draw(np.random.default_rng([seed, 2]), cfg.b_dist, tall(cfg.b_shape())), cfg.ld_b(), cfg.dtype)
     if cfg.beta != 0.0:
-        out["C"] = _store(_draw(np.random.default_rng([seed, 3]), cfg.c_dist, (cfg.M, cfg.N)), cfg.ld_c(), cfg.out_dtype)
+        out["C"] = _store(_draw(np.random.default_rng([seed, 3]), cfg.c_dist, tall((cfg.M, cfg.N))), cfg.ld_c(), cfg.out_dtype)
     else:
         out["C"] = None
     if cfg.bias_dist is not None:
@@ -209,12 +222,14 @@ def make_integer_inputs(cfg: Config, seed: int = DEFAULT_SEED, lo: int = -1, hi:
     def draw(stream, shape):
         return np.random.default_rng([seed, stream]).integers(lo, hi + 1, size=shape, dtype=np.int64)
 
-    vals["A"] = draw(11, cfg.a_shape())
-    vals["B"] = draw(12, cfg.b_shape())
+    nb = cfg.batch                      # a batch: tall matrices, batch entry b in rows [b*rows, (b+1)*rows)
+    tall = lambda shape: (nb * shape[0], shape[1])
+    vals["A"] = draw(11, tall(cfg.a_shape()))
+    vals["B"] = draw(12, tall(cfg.b_shape()))
     out["A"] = _store(vals["A"].astype(np.float32), cfg.ld_a(), cfg.dtype)
     out["B"] = _store(vals["B"].astype(np.float32), cfg.ld_b(), cfg.dtype)
     if cfg.beta != 0.0:
-        vals["C"] = draw(13, (cfg.M, cfg.N))
+        vals["C"] = draw(13, tall((cfg.M, cfg.N)))
         out["C"] = _store(vals["C"].astype(np.float32), cfg.ld_c(), cfg.out_dtype)
     else:
         vals["C"], out["C"] = None, None
