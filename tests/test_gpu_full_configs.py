@@ -93,3 +93,39 @@ def test_all_ones_gives_k(handle, name):
     exact = cfg.alpha * cfg.K + (cfg.beta if cfg.beta != 0.0 else 0.0)
     want = oracle.decode(cfg.out_dtype, oracle.encode(cfg.out_dtype, np.array([exact])))[0]   # e.g. 16385 -> 16384 in bf16
     assert np.all(got == want), f"{name}: {np.sum(got != want)} elements differ from {want}"
+
+
+def test_operand_beyond_two_gib(handle):
+    """Maximum sizes: an A of more than 2 GiB (16392 x 65536 bf16), where 32-bit byte offsets into
+    the operand end.  The operand is drawn on the device (integers in {-1, 0, 1}, exact in bf16);
+    the rows on both sides of the 2 GiB line, the first and the last rows are copied back and the
+    oracle computes exactly those rows of C, which must match bit for bit (every sum is an
+    integer below 2^24)."""
+    M, N, K = 16392, 264, 65536
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    print("2 GiB operand: drawing", flush=True)
+    A = torch.randint(-1, 2, (M, K), generator=gen, device=dev, dtype=torch.int8).to(torch.bfloat16)
+    B = torch.randint(-1, 2, (N, K), generator=gen, device=dev, dtype=torch.int8).to(torch.bfloat16)       # stored N x K
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device=dev)
+    assert A.numel() * 2 > 2 ** 31
+    epi = lg.make_epilogue(wl.F32)
+    print("2 GiB operand: running", flush=True)
+    lg.gemm_run(handle, M, N, K, 0, 1, wl.BF16, 1.0, A.data_ptr(), K, B.data_ptr(), K, 0.0, C.data_ptr(), N, epi,
+                torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    kernel, variant, _ = lg.gemm_get_last_plan(handle)
+    name = lg.gemm_variant_name(kernel, variant)
+    print(f"2 GiB operand: ran {name}", flush=True)
+    assert kernel == lg.GEMM_KERNEL_MFMA_TILE and not name.startswith("dma"), name      # the direct-to-LDS kernels stop at 2 GiB
+    line = 2 ** 31 // (2 * K)                                                            # first row wholly past 2 GiB
+    rows = np.unique(np.concatenate([np.arange(0, 3), np.arange(line - 4, line + 4), np.arange(M - 9, M),
+                                     np.random.default_rng(3).integers(0, M, 40)]))
+    a_rows = wl.torch_to_bits(A[torch.from_numpy(rows).to(dev)].reshape(-1))
+    prob = oracle.Problem(len(rows), N, K, 0, 1, wl.BF16, a_rows, K, wl.torch_to_bits(B.reshape(-1)), K, c_dtype=wl.F32)
+    ref = oracle.gemm_full(prob)
+    got = C[torch.from_numpy(rows).to(dev)].cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, ref), f"{np.sum(got != ref)} elements differ in the sampled rows"
+    # every element is a finite integer (no row or tile was skipped)
+    assert bool(torch.all(C == torch.round(C)))
