@@ -218,7 +218,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library is single-GPU by design; run with --gpus 1 "
-              "(sharding over several GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+              "(one GPU computes the whole product; nothing here shards it)", file=sys.stderr)
         sys.exit(2)
 
     import torch
