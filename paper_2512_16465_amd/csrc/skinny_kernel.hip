@@ -22,6 +22,7 @@ namespace {
 constexpr int SK_COLS = 256;     // columns per workgroup
 constexpr int SK_WAVES = 4;      // waves per workgroup (one per SIMD), each a slice of the workgroup's k range
 constexpr int SK_DEPTH = 3;      // steps of 16 k-rows in flight per wave (8 KiB each)
+constexpr uint32_t SK_MASKED = 0x7ffffff0u;   // an offset past the end of any operand: the load returns zero
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t sk_rsrc(const void* base, int64_t bytes) {
     const int64_t cap = 0xffffffffll;
@@ -146,10 +147,10 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int sp
 
     auto load = [&](SkStage& st, int step) {
         const int k = step * 16 + 8 * lhi;
-        // A: 8 consecutive k of row a_row; K % 8 == 0, so the chunk is inside or outside as a whole
-        const int ka = k < K ? k : K - 8;
-        st.a = __builtin_amdgcn_raw_buffer_load_b128(ra, a_row_off + (uint32_t)ka * 2, 0, 0);
-        if (k >= K) st.a = u32x4{0u, 0u, 0u, 0u};
+        // A: 8 consecutive k of row a_row; K % 8 == 0, so the chunk is inside or outside as a whole.
+        // Outside, the lane asks for an offset past the end of A and gets zeros (clearing the
+        // register after the load would be a write behind a load in flight, which waits for it).
+        st.a = __builtin_amdgcn_raw_buffer_load_b128(ra, k < K ? a_row_off + (uint32_t)k * 2 : SK_MASKED, 0, 0);
         uint32_t off = (uint32_t)k * ldb_b + (uint32_t)col_ld * 2;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -260,7 +261,7 @@ constexpr int ST_RUN = 8;                        // MFMA steps (32 along k) per 
 constexpr int ST_DEPTH = 4;                      // visits in flight per wave
 constexpr int ST_CHUNK = ST_RUN * 32;            // k per chunk
 constexpr int ST_VISIT_BYTES = 16 * ST_RUN * 64; // 8 KiB
-constexpr uint32_t ST_MASKED = 0x7ffffff0u;      // an offset past the end of any operand: the load returns zero
+constexpr uint32_t ST_MASKED = SK_MASKED;
 
 template <bool IS_BF16>
 __device__ __forceinline__ f32x4 st_mfma(u32x4 a, u32x4 b, f32x4 c) {
