@@ -150,7 +150,7 @@ typedef enum {
     GEMM_KERNEL_AUTO = 0,      /* let the library choose (default) */
     GEMM_KERNEL_GENERAL = 1,   /* one thread per output element, any shape/alignment */
     GEMM_KERNEL_MFMA_TILE = 2, /* LDS-staged macro-tile kernel on MFMA */
-    GEMM_KERNEL_SKINNY = 3     /* small-M streaming kernels with split-K: variant 0 for a row-major
+    GEMM_KERNEL_SKINNY = 3     /* small-M (M <= 64) streaming kernels with split-K: variant 0 for a row-major
                                   B (K x N), variant 1 for B stored N x K; the layout of the call
                                   decides, a variant forced against it is GEMM_ERR_UNSUPPORTED */
 } gemm_kernel_t;

@@ -1,4 +1,4 @@
-// The skinny kernel: M <= 32 rows of C, bf16 / fp16 operands, A row-major (k contiguous) and
+// The skinny kernels: M <= 64 rows of C, bf16 / fp16 operands, A row-major (k contiguous) and
 // B row-major K x N (n contiguous) -- the decode-shaped product whose cost is reading B once.
 // By the paper's roofline rule (Section 4.3) such a call sits left of the matrix-core ridge, so
 // the objective is memory throughput, not matrix-core occupancy: B streams HBM -> registers
@@ -22,6 +22,7 @@ namespace {
 constexpr int SK_COLS = 256;     // columns per workgroup
 constexpr int SK_WAVES = 4;      // waves per workgroup (one per SIMD), each a slice of the workgroup's k range
 constexpr int SK_DEPTH = 3;      // steps of 16 k-rows in flight per wave (8 KiB each)
+constexpr int SK_MAX_ROWS = 64;  // rows of C the skinny kernels take
 constexpr uint32_t SK_MASKED = 0x7ffffff0u;   // an offset past the end of any operand: the load returns zero
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t sk_rsrc(const void* base, int64_t bytes) {
@@ -38,8 +39,9 @@ __device__ __forceinline__ f32x16 sk_mfma(u32x4 a, u32x4 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
+template <int MB>
 struct SkStage {
-    u32x4 a;
+    u32x4 a[MB];
     u32x4 b[8];
 };
 
@@ -109,11 +111,14 @@ __device__ __forceinline__ void sk_store_row(const Args& a, int64_t row, int64_t
     }
 }
 
-template <bool IS_BF16>
+// MB = number of 32-row blocks of C: 1 serves M <= 32, 2 serves M <= 64 (every piece of B that a
+// wave has transposed then feeds two MFMAs instead of one; B is still read once).
+template <bool IS_BF16, int MB>
 __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int split_k, float* ws, int c_vec_ok) {
-    // partial accumulators of the upper half of the waves, [wave][register quad][lane]
-    __shared__ f32x4 red[(SK_WAVES / 2) * 32 * 64];
+    // partial accumulators of the upper half of the waves, [wave][row block][register quad][lane]
+    __shared__ f32x4 red[(SK_WAVES / 2) * MB * 32 * 64];
 
+    constexpr int DEPTH = MB == 1 ? SK_DEPTH : 2;        // steps in flight per wave; two row blocks leave registers for two
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, lhi = lane >> 5;
     const int M = (int)a.M, K = (int)a.K;
@@ -132,25 +137,33 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int sp
     const int64_t col0 = (int64_t)blockIdx.x * SK_COLS + 8 * l32;       // first of this lane's 8 columns
     const bool col_ok = col0 < N;                                        // N % 8 == 0: all 8 or none
     const int64_t col_ld = col_ok ? col0 : N - 8;                        // loads stay inside the matrix
-    const int a_row = l32 < M ? l32 : M - 1;                             // rows >= M are computed from a valid row, never stored
 
     const __amdgpu_buffer_rsrc_t rb = sk_rsrc(a.B, ((int64_t)(K - 1) * a.ldb + N) * 2);   // rows >= K read as zero
     const __amdgpu_buffer_rsrc_t ra = sk_rsrc(a.A, ((int64_t)(M - 1) * a.lda + K) * 2);
     const uint32_t ldb_b = (uint32_t)a.ldb * 2;
-    const uint32_t a_row_off = (uint32_t)(a_row * a.lda * 2);
-
-    f32x16 acc[8];
+    uint32_t a_row_off[MB];
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+    for (int mb = 0; mb < MB; ++mb) {
+        const int r = 32 * mb + l32;
+        a_row_off[mb] = (uint32_t)((r < M ? r : M - 1) * a.lda * 2);     // rows >= M are computed from a valid row, never stored
+    }
 
-    auto load = [&](SkStage& st, int step) {
+    f32x16 acc[MB][8];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][j][v] = 0.0f;
+
+    auto load = [&](SkStage<MB>& st, int step) {
         const int k = step * 16 + 8 * lhi;
         // A: 8 consecutive k of row a_row; K % 8 == 0, so the chunk is inside or outside as a whole.
         // Outside, the lane asks for an offset past the end of A and gets zeros (clearing the
         // register after the load would be a write behind a load in flight, which waits for it).
-        st.a = __builtin_amdgcn_raw_buffer_load_b128(ra, k < K ? a_row_off + (uint32_t)k * 2 : SK_MASKED, 0, 0);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+            st.a[mb] = __builtin_amdgcn_raw_buffer_load_b128(ra, k < K ? a_row_off[mb] + (uint32_t)k * 2 : SK_MASKED, 0, 0);
         uint32_t off = (uint32_t)k * ldb_b + (uint32_t)col_ld * 2;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -161,7 +174,7 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int sp
     // One step: transpose the stage's 8x8 blocks, then at once refill the stage with the step two
     // ahead (so that the loads are not held up behind the MFMAs, which issue slowly while the
     // other wave of the SIMD owns the matrix pipe), then the eight MFMAs.
-    auto process = [&](SkStage& st, int refill_step, bool refill) {
+    auto process = [&](SkStage<MB>& st, int refill_step, bool refill) {
         u32x4 o[8];
 #pragma unroll
         for (int n = 0; n < 8; ++n) {
@@ -170,43 +183,56 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int sp
             for (int kp = 0; kp < 4; ++kp)
                 o[n][kp] = __builtin_amdgcn_perm(st.b[2 * kp + 1][n >> 1], st.b[2 * kp][n >> 1], sel);
         }
-        const u32x4 a_cur = st.a;
+        u32x4 a_cur[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) a_cur[mb] = st.a[mb];
         if (refill) load(st, refill_step);
 #pragma unroll
-        for (int n = 0; n < 8; ++n) acc[n] = sk_mfma<IS_BF16>(a_cur, o[n], acc[n]);
+        for (int n = 0; n < 8; ++n)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) acc[mb][n] = sk_mfma<IS_BF16>(a_cur[mb], o[n], acc[mb][n]);
     };
 
-    SkStage st[SK_DEPTH];
+    SkStage<MB> st[DEPTH];
 #pragma unroll
-    for (int d = 0; d < SK_DEPTH; ++d)
+    for (int d = 0; d < DEPTH; ++d)
         if (my_beg + d < my_end) load(st[d], my_beg + d);
-    for (int s = my_beg; s < my_end; s += SK_DEPTH) {
+    for (int s = my_beg; s < my_end; s += DEPTH) {
 #pragma unroll
-        for (int d = 0; d < SK_DEPTH; ++d)
-            if (s + d < my_end) process(st[d], s + d + SK_DEPTH, s + d + SK_DEPTH < my_end);
+        for (int d = 0; d < DEPTH; ++d)
+            if (s + d < my_end) process(st[d], s + d + DEPTH, s + d + DEPTH < my_end);
     }
 
     // fold the waves' partial sums pairwise through LDS: (0..3)+=(4..7), (0,1)+=(2,3), 0+=1
 #pragma unroll
     for (int half = SK_WAVES / 2; half >= 1; half >>= 1) {
         if (wave >= half && wave < 2 * half) {
-            f32x4* dst = red + (wave - half) * 32 * 64 + lane;
+            f32x4* dst = red + (wave - half) * MB * 32 * 64 + lane;
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    dst[(j * 4 + c) * 64] = f32x4{acc[j][4 * c], acc[j][4 * c + 1], acc[j][4 * c + 2], acc[j][4 * c + 3]};
+                for (int j = 0; j < 8; ++j) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        dst[((mb * 8 + j) * 4 + c) * 64] =
+                            f32x4{acc[mb][j][4 * c], acc[mb][j][4 * c + 1], acc[mb][j][4 * c + 2], acc[mb][j][4 * c + 3]};
+                    asm volatile("" ::: "memory");      // one accumulator at a time: no need to hold them all in vector registers
+                }
         }
         __syncthreads();
         if (wave < half) {
-            const f32x4* src = red + wave * 32 * 64 + lane;
+            const f32x4* src = red + wave * MB * 32 * 64 + lane;
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const f32x4 t = src[(j * 4 + c) * 64];
+                for (int j = 0; j < 8; ++j) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[j][4 * c + e] += t[e];
+                    for (int c = 0; c < 4; ++c) {
+                        const f32x4 t = src[((mb * 8 + j) * 4 + c) * 64];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[mb][j][4 * c + e] += t[e];
+                    }
+                    asm volatile("" ::: "memory");
                 }
         }
         __syncthreads();
@@ -214,12 +240,14 @@ __global__ __launch_bounds__(SK_WAVES * 64) void skinny_nn_kernel(Args a, int sp
 
     if (wave == 0 && col_ok) {
 #pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int row = 8 * (v >> 2) + 4 * lhi + (v & 3);
+            const int row = 32 * mb + 8 * (v >> 2) + 4 * lhi + (v & 3);
             if (row < M) {
                 float x[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) x[j] = acc[j][v];
+                for (int j = 0; j < 8; ++j) x[j] = acc[mb][j][v];
                 if (split_k > 1) {
                     float* p = ws + ((int64_t)blockIdx.y * M + row) * N + col0;
                     *(f32x4*)p = f32x4{x[0], x[1], x[2], x[3]};
@@ -286,7 +314,7 @@ __device__ __forceinline__ void st_load_to_lds(__amdgpu_buffer_rsrc_t rsrc, char
 template <int N>
 __device__ __forceinline__ void st_wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-// H = 1 serves M <= 16, H = 2 serves M <= 32.
+// H = number of 16-row blocks of C: 1 serves M <= 16, 2 serves M <= 32, 4 serves M <= 64.
 template <bool IS_BF16, int H>
 __global__ __launch_bounds__(ST_WAVES * 64) void skinny_nt_kernel(Args a, int split_k, float* ws) {
     static_assert(ST_DEPTH == 4 && ST_RUN == 8, "the visit loop and the load counts below are written for a ring of four visits of eight steps");
@@ -477,7 +505,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(Args a, int split_k,
 bool skinny_supports(const Args& a) {
     if (a.dtype != DT_BF16 && a.dtype != DT_F16) return false;
     if (a.transA) return false;
-    if (a.M < 1 || a.M > 32 || a.N < 8 || a.K < 8) return false;
+    if (a.M < 1 || a.M > SK_MAX_ROWS || a.N < 8 || a.K < 8) return false;
     if ((a.N & 7) || (a.K & 7) || (a.lda & 7) || (a.ldb & 7)) return false;
     if (((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15)) return false;
     // 32-bit byte offsets into A and B (row-major B: with room for the rows past K that read as
@@ -525,8 +553,10 @@ template <bool IS_BF16>
 void launch_nt(const Args& a, dim3 grid, int split_k, float* ws, hipStream_t stream) {
     if (a.M <= 16)
         hipLaunchKernelGGL((skinny_nt_kernel<IS_BF16, 1>), grid, dim3(ST_WAVES * 64), 0, stream, a, split_k, ws);
-    else
+    else if (a.M <= 32)
         hipLaunchKernelGGL((skinny_nt_kernel<IS_BF16, 2>), grid, dim3(ST_WAVES * 64), 0, stream, a, split_k, ws);
+    else
+        hipLaunchKernelGGL((skinny_nt_kernel<IS_BF16, 4>), grid, dim3(ST_WAVES * 64), 0, stream, a, split_k, ws);
 }
 }  // namespace
 
@@ -542,10 +572,13 @@ hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream
     if (a.transB) {
         if (a.dtype == DT_BF16) launch_nt<true>(a, grid, split_k, workspace, stream);
         else launch_nt<false>(a, grid, split_k, workspace, stream);
-    } else if (a.dtype == DT_BF16)
-        hipLaunchKernelGGL(skinny_nn_kernel<true>, grid, block, 0, stream, a, split_k, workspace, c_vec_ok);
-    else
-        hipLaunchKernelGGL(skinny_nn_kernel<false>, grid, block, 0, stream, a, split_k, workspace, c_vec_ok);
+    } else if (a.dtype == DT_BF16) {
+        if (a.M <= 32) hipLaunchKernelGGL((skinny_nn_kernel<true, 1>), grid, block, 0, stream, a, split_k, workspace, c_vec_ok);
+        else hipLaunchKernelGGL((skinny_nn_kernel<true, 2>), grid, block, 0, stream, a, split_k, workspace, c_vec_ok);
+    } else {
+        if (a.M <= 32) hipLaunchKernelGGL((skinny_nn_kernel<false, 1>), grid, block, 0, stream, a, split_k, workspace, c_vec_ok);
+        else hipLaunchKernelGGL((skinny_nn_kernel<false, 2>), grid, block, 0, stream, a, split_k, workspace, c_vec_ok);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split_k == 1) return e;
     const int64_t threads = a.M * (a.N / 8);

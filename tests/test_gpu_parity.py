@@ -216,7 +216,7 @@ def test_small_tile_problem_single_partial_slab(handle):
 # ------------------------------------------------------------------ skinny split-K kernels (B row-major, B stored N x K)
 
 @pytest.mark.parametrize("tb", [0, 1])
-@pytest.mark.parametrize("M", [1, 5, 16, 17, 32])
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 32, 33, 49, 64])
 def test_skinny_gaussian_and_split_agreement(handle, M, tb):
     # 4 column groups with a ragged last one (776 = 3*256 + 8); K % 16 = 8 and K % 32 = 8 leave a
     # partly filled last step in either kernel; padded leading dimensions
@@ -242,8 +242,9 @@ def test_skinny_gaussian_and_split_agreement(handle, M, tb):
 
 @pytest.mark.parametrize("tb", [0, 1])
 @pytest.mark.parametrize("out", [wl.BF16, wl.F32])
-def test_skinny_integer_exact_all_splits_equal(handle, out, tb):
-    M, N, K = 19, 1032, 4104
+@pytest.mark.parametrize("M", [19, 57])
+def test_skinny_integer_exact_all_splits_equal(handle, out, tb, M):
+    N, K = 1032, 4104
     cfg = base_cfg(M, N, K, 0, tb, wl.BF16, out, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.BF16,
                    ldc=N + 8)
     inp, _ = wl.make_integer_inputs(cfg, 123, -1, 1)
