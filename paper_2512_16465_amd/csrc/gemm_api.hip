@@ -40,7 +40,11 @@ constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant 
 constexpr int kSmallTileShortK = 12;
 constexpr int64_t kShortK = 512;
 constexpr double kLargePerK = 0.0209, kLargeFixed = 15.0, kSmallPerK = 0.0094, kSmallFixed = 1.4;
-constexpr double kSmallAlonePerK = 0.0055;   // a small-tile workgroup that has its compute unit to itself (512x512x4096: 23 us)
+constexpr double kSmallAlonePerK = 0.0055;   // a small-tile workgroup that has its compute unit to itself (512x512x4096: 23 us) ...
+constexpr double kSmallStreamPerK = 0.0122;  // ... and when its operands come from HBM rather than from the caches: its ring keeps
+                                             // 48 KiB in flight against the large tile's 128 KiB (128x16384x16384: 200 us, and 118 us
+                                             // on the large tile with its 64 tiles cut in four)
+constexpr int64_t kCacheResidentBytes = (int64_t)128 << 20;
 // A last round that fills less than this fraction of the compute units is split along K (when the
 // variant can): each of its tiles goes to several workgroups, each over a share of the k slabs of
 // at least kMinSlabsPerPart, and a second kernel adds the parts.  The split costs a round trip of
@@ -73,7 +77,9 @@ TileChoice choose_tile(const Args& a, int num_cus) {
     const double k = (double)a.K;
     double t_large = (double)(large / cus) * (kLargePerK * k + kLargeFixed);
     if (tail) t_large += parts > 1 ? kLargePerK * k * (1.0 / parts + kSplitOverhead) + kLargeFixed : kLargePerK * k + kLargeFixed;
-    const double t_small = small <= cus ? kSmallAlonePerK * k + kSmallFixed : (double)((small + cus - 1) / cus) * (kSmallPerK * k + kSmallFixed);
+    const bool streams = (a.M + a.N) * a.K * 2 * a.batch > kCacheResidentBytes;
+    const double t_small = small <= cus ? (streams ? kSmallStreamPerK : kSmallAlonePerK) * k + kSmallFixed
+                                        : (double)((small + cus - 1) / cus) * (kSmallPerK * k + kSmallFixed);
     if (t_large <= t_small) {
         if (!large_ok) return TileChoice{kLargeTileFallback, 0, 1};
         return TileChoice{kLargeTileVariant, (int)(large - tail), parts};
