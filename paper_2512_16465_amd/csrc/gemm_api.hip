@@ -63,12 +63,18 @@ int tail_parts(int64_t tail, int64_t cus, int64_t K) {
 }
 
 struct TileChoice { int variant; int first_split_tile; int parts; };
-constexpr int kF32TileVariant = 11;
-constexpr int64_t kF32MinTiles = 16;       // below this many 128x128 tiles the general kernel's finer grid wins
+// fp32: the 128x128 tile when its tiles fill three quarters of the compute units, else the 64x64
+// tile (four times the workgroups: 1024^3 in 80 us on 64 large tiles); below kF32MinTiles small
+// tiles the general kernel's finer grid wins (256^3: 10 us).
+constexpr int kF32TileVariant = 11, kF32SmallTileVariant = 13;
+constexpr int64_t kF32MinTiles = 32;
 
 TileChoice choose_tile(const Args& a, int num_cus) {
-    if (a.dtype == gemm::DT_F32) return TileChoice{kF32TileVariant, 0, 1};
     const int64_t cus = num_cus > 0 ? num_cus : 256;
+    if (a.dtype == gemm::DT_F32) {
+        const int64_t t128 = ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
+        return TileChoice{t128 * 4 >= cus * 3 ? kF32TileVariant : kF32SmallTileVariant, 0, 1};
+    }
     // a batch multiplies the number of workgroups; its trailing round is never split along K
     const int64_t large = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch, small = ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
     const bool large_ok = gemm::tile_variant_supports(a, kLargeTileVariant);
@@ -283,7 +289,7 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
         if (gemm::skinny_supports(a) && batch_aligned && N >= 256 && K >= 512) {
             plan = gemm_plan_t{GEMM_KERNEL_SKINNY, gemm::skinny_variant_of(a), gemm::skinny_default_split(a, h->num_cus)};
         } else if (gemm::tile_supports(a) && batch_aligned &&
-                   (a.dtype != gemm::DT_F32 || ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch >= kF32MinTiles)) {
+                   (a.dtype != gemm::DT_F32 || ((a.M + 63) / 64) * ((a.N + 63) / 64) * a.batch >= kF32MinTiles)) {
             const TileChoice c = choose_tile(a, h->num_cus);
             plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, c.variant, c.parts};
             split_first = c.first_split_tile;

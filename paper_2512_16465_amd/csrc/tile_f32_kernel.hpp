@@ -21,23 +21,30 @@
 namespace gemm {
 namespace tile {
 
-struct F32Cfg {
-    static constexpr int BM = 128, BN = 128, BK = 32, WM = 2, WN = 2;
+// SIDE = rows and columns of the workgroup tile: 128 (four waves of 64x64) or 64 (four waves of
+// 32x32, for problems with too few 128x128 tiles to fill the chip).
+template <int SIDE>
+struct F32CfgT {
+    static_assert(SIDE == 128 || SIDE == 64, "two tile sizes");
+    static constexpr int BM = SIDE, BN = SIDE, BK = 32, WM = 2, WN = 2;
     static constexpr int NT = WM * WN * 64;
     static constexpr int WTM = BM / WM, WTN = BN / WN;
     static constexpr int TM = WTM / 32, TN = WTN / 32;
     static constexpr int KC_STRIDE = BK + 4;          // floats per row of a k-contiguous slab in LDS
-    static constexpr int MC_STRIDE = 128 + 8;         // floats per k-row of an m/n-contiguous slab: the two lane halves read k-rows
-                                                      // four apart, 4 * 136 floats = 32 banks (mod 64) from each other
-    static constexpr int OPERAND_BYTES = 128 * KC_STRIDE * 4 > BK * MC_STRIDE * 4 ? 128 * KC_STRIDE * 4 : BK * MC_STRIDE * 4;
+    static constexpr int MC_STRIDE = SIDE + 8;        // floats per k-row of an m/n-contiguous slab: the two lane halves read k-rows
+                                                      // four apart, 4 * (SIDE + 8) floats = 32 banks (mod 64) from each other
+    static constexpr int OPERAND_BYTES = SIDE * KC_STRIDE * 4 > BK * MC_STRIDE * 4 ? SIDE * KC_STRIDE * 4 : BK * MC_STRIDE * 4;
     static constexpr int STAGE = 2 * OPERAND_BYTES;
+    static constexpr int WGS_PER_CU = SIDE == 128 ? 2 : 4;
 };
+using F32Cfg = F32CfgT<128>;
 
-// One operand's slab: 128 rows x BK k, L 16-byte chunks per thread.
-template <bool KC>
+// One operand's slab: SIDE rows x BK k, L 16-byte chunks per thread.
+template <bool KC, class F32Cfg>
 struct F32Mover {
-    static constexpr int L = 128 * F32Cfg::BK / 4 / F32Cfg::NT;     // chunks per thread
+    static constexpr int L = F32Cfg::BM * F32Cfg::BK / 4 / F32Cfg::NT;   // chunks per thread
     static constexpr int CPR = F32Cfg::BK / 4;                      // 16-byte chunks per row of a k-contiguous slab
+    static constexpr int CPK = F32Cfg::BM / 4;                      // 16-byte chunks per k-row of an m/n-contiguous slab
     uint32_t goff[L];      // byte offset of the chunk from the slab's first byte
     uint32_t loff[L];      // byte offset in the operand's LDS region
     u32x4 r[L];
@@ -52,7 +59,7 @@ struct F32Mover {
                 goff[i] = (uint32_t)((row * ld + c * 4) * 4);
                 loff[i] = (row * F32Cfg::KC_STRIDE + c * 4) * 4;
             } else {
-                const uint32_t k = q / 32, c = q % 32;                 // 32 chunks cover a k-row's 128 columns
+                const uint32_t k = q / CPK, c = q % CPK;               // CPK chunks cover a k-row's columns
                 goff[i] = (uint32_t)((k * ld + c * 4) * 4);
                 loff[i] = (k * F32Cfg::MC_STRIDE + c * 4) * 4;
             }
@@ -96,9 +103,8 @@ struct F32Mover {
     }
 };
 
-template <bool A_KC, bool B_KC>
-__global__ __launch_bounds__(F32Cfg::NT, 2) void tile_f32_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok) {
-    using C = F32Cfg;
+template <class C, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(C::NT, C::WGS_PER_CU) void tile_f32_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok) {
     using EL = EpiLayout<C>;
     constexpr int LDS_BYTES = 2 * C::STAGE > EL::BYTES ? 2 * C::STAGE : EL::BYTES;
     __shared__ __attribute__((aligned(128))) char lds[LDS_BYTES];
@@ -114,15 +120,15 @@ __global__ __launch_bounds__(F32Cfg::NT, 2) void tile_f32_kernel(Args a, int til
     const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
     const int K = (int)a.K;
 
-    F32Mover<A_KC> la;
-    F32Mover<B_KC> lb;
+    F32Mover<A_KC, C> la;
+    F32Mover<B_KC, C> lb;
     la.init(tid, a.lda);
     lb.init(tid, a.ldb);
-    const char* pa = F32Mover<A_KC>::tile_base(a.A, m0, a.lda);
-    const char* pb = F32Mover<B_KC>::tile_base(a.B, n0, a.ldb);
-    const int64_t a_step = F32Mover<A_KC>::k_step_bytes(a.lda), b_step = F32Mover<B_KC>::k_step_bytes(a.ldb);
-    const int64_t a_bytes = F32Mover<A_KC>::total_bytes(a.M, a.K, a.lda) - (pa - (const char*)a.A);
-    const int64_t b_bytes = F32Mover<B_KC>::total_bytes(a.N, a.K, a.ldb) - (pb - (const char*)a.B);
+    const char* pa = F32Mover<A_KC, C>::tile_base(a.A, m0, a.lda);
+    const char* pb = F32Mover<B_KC, C>::tile_base(a.B, n0, a.ldb);
+    const int64_t a_step = F32Mover<A_KC, C>::k_step_bytes(a.lda), b_step = F32Mover<B_KC, C>::k_step_bytes(a.ldb);
+    const int64_t a_bytes = F32Mover<A_KC, C>::total_bytes(a.M, a.K, a.lda) - (pa - (const char*)a.A);
+    const int64_t b_bytes = F32Mover<B_KC, C>::total_bytes(a.N, a.K, a.ldb) - (pb - (const char*)a.B);
 
     f32x16 acc[C::TM][C::TN];
 #pragma unroll
@@ -154,9 +160,9 @@ __global__ __launch_bounds__(F32Cfg::NT, 2) void tile_f32_kernel(Args a, int til
     f32x4 fa[2][C::TM], fb[2][C::TN];
     auto read_frags = [&](int buf, const char* stage, int g) {
 #pragma unroll
-        for (int i = 0; i < C::TM; ++i) fa[buf][i] = F32Mover<A_KC>::frag(stage, wm * C::WTM + i * 32 + l32, g, lhi);
+        for (int i = 0; i < C::TM; ++i) fa[buf][i] = F32Mover<A_KC, C>::frag(stage, wm * C::WTM + i * 32 + l32, g, lhi);
 #pragma unroll
-        for (int j = 0; j < C::TN; ++j) fb[buf][j] = F32Mover<B_KC>::frag(stage + C::OPERAND_BYTES, wn * C::WTN + j * 32 + l32, g, lhi);
+        for (int j = 0; j < C::TN; ++j) fb[buf][j] = F32Mover<B_KC, C>::frag(stage + C::OPERAND_BYTES, wn * C::WTN + j * 32 + l32, g, lhi);
     };
     if (k_tiles > 0) {
         gload(0);
@@ -193,14 +199,14 @@ __global__ __launch_bounds__(F32Cfg::NT, 2) void tile_f32_kernel(Args a, int til
     tile_epilogue<C>(acc, lds, a, m0, n0, c_vec_ok);
 }
 
+template <class C>
 inline hipError_t launch_f32_variant(const Args& a, int group_m, hipStream_t stream) {
-    using C = F32Cfg;
     const int tiles_m = (int)((a.M + C::BM - 1) / C::BM), tiles_n = (int)((a.N + C::BN - 1) / C::BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)a.batch), block(C::NT);
     const bool akc = !a.transA, bkc = a.transB != 0;
     const int c_vec_ok = c_rows_take_vec4(a);
 #define GEMM_TILE_LAUNCH(AKC, BKC) \
-    hipLaunchKernelGGL((tile_f32_kernel<AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok)
+    hipLaunchKernelGGL((tile_f32_kernel<C, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok)
     if (akc && bkc) GEMM_TILE_LAUNCH(true, true);
     else if (akc && !bkc) GEMM_TILE_LAUNCH(true, false);
     else if (!akc && bkc) GEMM_TILE_LAUNCH(false, true);
