@@ -63,17 +63,22 @@ int tail_parts(int64_t tail, int64_t cus, int64_t K) {
 }
 
 struct TileChoice { int variant; int first_split_tile; int parts; };
-// fp32: the 128x128 tile when its tiles fill three quarters of the compute units, else the 64x64
-// tile (four times the workgroups: 1024^3 in 80 us on 64 large tiles); below kF32MinTiles small
-// tiles the general kernel's finer grid wins (256^3: 10 us).
+// fp32: the 128x128 or the 64x64 tile, whichever leaves the busiest compute unit less to do (see
+// choose_tile); below kF32MinTiles small tiles the general kernel's finer grid wins (256^3: 10 us).
 constexpr int kF32TileVariant = 11, kF32SmallTileVariant = 13;
 constexpr int64_t kF32MinTiles = 32;
 
 TileChoice choose_tile(const Args& a, int num_cus) {
     const int64_t cus = num_cus > 0 ? num_cus : 256;
     if (a.dtype == gemm::DT_F32) {
-        const int64_t t128 = ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
-        return TileChoice{t128 * 4 >= cus * 3 ? kF32TileVariant : kF32SmallTileVariant, 0, 1};
+        // tiles per compute unit (the busiest one) times the cost of a tile, in units of a 64x64 tile: a
+        // 128x128 tile costs 3.88 of them (4096^3: 1070 against 1105 us); a compute unit that holds fewer
+        // workgroups than fit on it (2 large, 4 small) runs them 20 % / 10 % slower.  3072^3: 9 small
+        // tiles per unit against 3 large ones, 515 against 615 us.
+        const int64_t n128 = (((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch + cus - 1) / cus;
+        const int64_t n64 = (((a.M + 63) / 64) * ((a.N + 63) / 64) * a.batch + cus - 1) / cus;
+        const double t128 = (double)n128 * 3.88 * (n128 < 2 ? 1.2 : 1.0), t64 = (double)n64 * (n64 < 4 ? 1.1 : 1.0);
+        return TileChoice{t128 <= t64 ? kF32TileVariant : kF32SmallTileVariant, 0, 1};
     }
     // a batch multiplies the number of workgroups; its trailing round is never split along K
     const int64_t large = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch, small = ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
