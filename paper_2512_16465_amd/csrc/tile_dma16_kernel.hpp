@@ -116,7 +116,7 @@ __device__ __forceinline__ void wait_raw8(Frag16Raw (&r)[8]) {
 // unscaled, as an fp32 tile in `partials`.
 template <class C, bool IS_BF16, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok,
-                                                           int split_first, int split_parts, float* partials) {
+                                                           int split_first, int split_parts, float* partials, int rotate) {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NT, NS = C::NS;
     constexpr int TM = C::WTM / 16, TN = C::WTN / 16;        // 16x16 accumulators per wave
     static_assert(TM == 8 && TN == 8, "the slot plan below is written for a 128x128 wave sub-block");
@@ -182,6 +182,15 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
 
     const int k_tiles = slab1 - slab0;
     const int full_tiles = K / BK < k_tiles ? K / BK : k_tiles;
+    // Rotation of the k walk (`rotate`, set by the host for streaming calls whose k-contiguous
+    // operand has rows a large power of two apart): at a given k every row of such an operand
+    // lies on the same memory channel, so workgroups that walked k in step would queue on a few
+    // channels.  This workgroup takes its slabs in the order rot, rot+1, ..., k_tiles-1, 0, ...,
+    // rot-1 (rot even, so that pairs of slabs still cover whole cache lines); the sum over k is
+    // taken in that order, a fixed function of the tile.  Needs whole slabs and an even count.
+    const int rot = (rotate && k_tiles == full_tiles && (k_tiles & 1) == 0 && k_tiles >= 2 * NS)
+                        ? 2 * (int)((unsigned)(pid * 5 + (part > 0 ? part : 0) * 3) % (unsigned)(k_tiles / 2)) : 0;
+    auto physical = [&](int t) { const int p = t + rot; return p >= k_tiles ? p - k_tiles : p; };   // slab in memory of step t
     constexpr int NM = TM * TN, NR = TM + TN;     // MFMAs and fragments per step
     constexpr int LPT = LA::L + LB::L;            // loads per thread and slab (= per half of a pair)
 
@@ -252,14 +261,15 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
         const int t = kt_even + 4 + p.which;
         if (t >= k_tiles) return;
         char* stage = lds + (t % NS) * C::STAGE;
+        const int pt = physical(t);
         if (p.is_a) {
-            const __amdgpu_buffer_rsrc_t r = make_rsrc(pa + t * a_step, a_bytes - t * a_step);
-            if (t < full_tiles) la.issue(false, p.i, r, stage, wave, tid, t * BK, K);
-            else la.issue(true, p.i, r, stage, wave, tid, t * BK, K);
+            const __amdgpu_buffer_rsrc_t r = make_rsrc(pa + pt * a_step, a_bytes - pt * a_step);
+            if (pt < full_tiles) la.issue(false, p.i, r, stage, wave, tid, pt * BK, K);
+            else la.issue(true, p.i, r, stage, wave, tid, pt * BK, K);
         } else {
-            const __amdgpu_buffer_rsrc_t r = make_rsrc(pb + t * b_step, b_bytes - t * b_step);
-            if (t < full_tiles) lb.issue(false, p.i, r, stage + C::A_BYTES, wave, tid, t * BK, K);
-            else lb.issue(true, p.i, r, stage + C::A_BYTES, wave, tid, t * BK, K);
+            const __amdgpu_buffer_rsrc_t r = make_rsrc(pb + pt * b_step, b_bytes - pt * b_step);
+            if (pt < full_tiles) lb.issue(false, p.i, r, stage + C::A_BYTES, wave, tid, pt * BK, K);
+            else lb.issue(true, p.i, r, stage + C::A_BYTES, wave, tid, pt * BK, K);
         }
     };
 
@@ -281,6 +291,7 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     auto advance2 = [](uint32_t off) { const uint32_t n = off + 2 * C::STAGE; return n >= (uint32_t)RING ? n - RING : n; };
     const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(pa, a_bytes), rb0 = make_rsrc(pb, b_bytes);
     char* const wave_lds = lds + wave * 1024;
+    const uint32_t span_a = (uint32_t)(k_tiles * a_step), span_b = (uint32_t)(k_tiles * b_step);   // bytes of the whole k walk
 
     // Steady state: every slab requested exists and lies wholly inside K; the k advance is the
     // loads' scalar offset, which the range check ignores (see load_to_lds_b128).
@@ -311,6 +322,11 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
                     if constexpr (m == TAIL_FIRST + 6) s.w1 = advance2(s.w1);
                     if constexpr (m == TAIL_FIRST + 8) { s.sa0 += (uint32_t)(2 * a_step); s.sa1 += (uint32_t)(2 * a_step); }
                     if constexpr (m == TAIL_FIRST + 9) { s.sb0 += (uint32_t)(2 * b_step); s.sb1 += (uint32_t)(2 * b_step); }
+                    // a rotated walk wraps around the end of the k range (never reached without rotation)
+                    if constexpr (m == TAIL_FIRST + 10) s.sa0 = s.sa0 >= span_a ? s.sa0 - span_a : s.sa0;
+                    if constexpr (m == TAIL_FIRST + 11) s.sa1 = s.sa1 >= span_a ? s.sa1 - span_a : s.sa1;
+                    if constexpr (m == TAIL_FIRST + 12) s.sb0 = s.sb0 >= span_b ? s.sb0 - span_b : s.sb0;
+                    if constexpr (m == TAIL_FIRST + 13) s.sb1 = s.sb1 >= span_b ? s.sb1 - span_b : s.sb1;
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -343,8 +359,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
         read_all(0, 0);
         __builtin_amdgcn_sched_barrier(0);
         int kt = 0;
-        Sched s{stage_off(1), stage_off(2), stage_off(4), stage_off(5), (uint32_t)(4 * a_step), (uint32_t)(5 * a_step),
-                (uint32_t)(4 * b_step), (uint32_t)(5 * b_step)};
+        Sched s{stage_off(1), stage_off(2), stage_off(4), stage_off(5), (uint32_t)(physical(4) * a_step), (uint32_t)(physical(5) * a_step),
+                (uint32_t)(physical(4) * b_step), (uint32_t)(physical(5) * b_step)};
         for (; kt + 1 + NS < full_tiles; kt += 2) {      // the two steps request slabs up to kt + 5
             step_hot(s, Even{});
             step_hot(s, Odd{});
@@ -393,9 +409,13 @@ hipError_t launch_dma16_variant(const Args& a, int group_m, const TileSplit& spl
     const bool bf = a.dtype == DT_BF16;
     const bool akc = !a.transA, bkc = a.transB != 0;
     const int c_vec_ok = c_rows_take_vec4(a);
+    // A split call streams its operands (few tiles, long k): rotate the k walk when a k-contiguous
+    // operand has its rows a multiple of 4 KiB apart (see the kernel).
+    const bool a_aliases = akc && (a.lda * 2) % 4096 == 0, b_aliases = bkc && (a.ldb * 2) % 4096 == 0;
+    const int rotate = splits && (a_aliases || b_aliases);
 #define GEMM_TILE_LAUNCH(BF, AKC, BKC) \
     hipLaunchKernelGGL((tile_dma16_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok, \
-                       split_first, split_parts, split.partials)
+                       split_first, split_parts, split.partials, rotate)
     if (bf) {
         if (akc && bkc) GEMM_TILE_LAUNCH(true, true, true);
         else if (akc && !bkc) GEMM_TILE_LAUNCH(true, true, false);

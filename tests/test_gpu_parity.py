@@ -144,6 +144,34 @@ def test_tile_split_of_the_trailing_round(handle, ta, tb):
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0), (1, 1), (1, 0)])
+def test_tile_split_with_rotated_k_walk(handle, ta, tb):
+    # K = 2048 in whole slabs and rows of the k-contiguous operands 4096 bytes apart: a split call
+    # then walks k from a different slab in every workgroup and wraps around.  Integer data -> the
+    # order of the sum does not show, every element is exact; Gaussian data within the bounds.
+    M, N, K = 520, 584, 2048
+    cfg = base_cfg(M, N, K, ta, tb, wl.BF16, wl.F32, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.F32)
+    inp, _ = wl.make_integer_inputs(cfg, 79, -2, 2)
+    want = oracle.decode(wl.F32, expected_bits_exact(cfg, inp))
+    gcfg = base_cfg(M, N, K, ta, tb, wl.BF16, wl.BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.05))
+    ginp = wl.make_inputs(gcfg, 80)
+    gref, _, gmag = oracle.gemm_full(oracle_problem(gcfg, ginp), want_bounds=True)
+    splitting = [v for v in tile_variants() if "dma16" in lg.gemm_variant_name(lg.GEMM_KERNEL_MFMA_TILE, v)]
+    for v in splitting:
+        for parts in (2, 3, 4, 7):       # 3 and 7: odd slab counts in some shares (those walk unrotated)
+            print(f"rotated split variant {v} parts {parts} ta={ta} tb={tb}", flush=True)
+            lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v, parts)
+            p = DeviceProblem(cfg, inp)
+            p.run(handle)
+            assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_MFMA_TILE, v, parts)
+            got = decode_c(cfg, p.result_bits())
+            assert np.array_equal(got, want), f"variant {v} parts {parts}: {np.sum(got != want)} wrong elements"
+            g = DeviceProblem(gcfg, ginp)
+            g.run(handle)
+            assert_close(gcfg, decode_c(gcfg, g.result_bits()), gref, gmag, f"rotated split variant {v} parts {parts}")
+    lg.gemm_set_plan(handle)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0), (1, 1), (1, 0)])
 def test_f32_tile_variants(handle, ta, tb):
     # fp32 operands on the fp32 matrix instruction: 3 x 5 tiles of 128 with ragged tails, K leaves a partial slab
     # (K % 16 = 12); Gaussian data to the fp32 tolerance, integer data exactly; wrong operand type is refused
