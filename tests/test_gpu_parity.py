@@ -479,7 +479,7 @@ def test_invalid_arguments_leave_c_untouched(handle):
     assert run(handle, 64, 64, 64, 0, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, C, 64, f16_out, s) == lg.GEMM_ERR_UNSUPPORTED
     # a forced plan that cannot run the call is refused, not silently replaced
     lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 0, 2)
-    assert run(handle, 64, 64, 64, 0, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, C, 64, None, s) == lg.GEMM_ERR_UNSUPPORTED
+    assert run(handle, 64, 64, 64, 1, 0, wl.BF16, 1.0, A, 64, B, 64, 0.0, C, 64, None, s) == lg.GEMM_ERR_UNSUPPORTED   # A stored K x M
     lg.gemm_set_plan(handle)
     assert lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, 99, 0, check=False) == E
     assert "invalid" in lg.gemm_status_string(E)
