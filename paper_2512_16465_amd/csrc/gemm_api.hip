@@ -67,9 +67,10 @@ int tail_parts(int64_t tail, int64_t cus, int64_t K) {
 
 struct TileChoice { int variant; int first_split_tile; int parts; };
 // fp32: the 128x128 or the 64x64 tile, whichever leaves the busiest compute unit less to do (see
-// choose_tile); below kF32MinTiles small tiles the general kernel's finer grid wins (256^3: 10 us).
+// choose_tile).  The small tile is at least as fast as the general kernel down to a single tile
+// (256^3: 9.0 against 10.2 us, 64^3: 5.8 against 5.9), so every aligned fp32 call takes a tile kernel.
 constexpr int kF32TileVariant = 11, kF32SmallTileVariant = 13;
-constexpr int64_t kF32MinTiles = 32;
+constexpr int64_t kF32MinTiles = 1;
 
 TileChoice choose_tile(const Args& a, int num_cus) {
     const int64_t cus = num_cus > 0 ? num_cus : 256;

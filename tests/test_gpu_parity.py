@@ -203,11 +203,13 @@ def test_f32_tile_variants(handle, ta, tb):
 
 
 def test_f32_automatic_choice(handle):
-    # enough 128x128 tiles -> fp32 tile kernel; few tiles or unaligned -> general kernel
+    # aligned -> an fp32 tile kernel, whatever the size; unaligned -> general kernel
     big = base_cfg(512, 640, 64, 0, 0, wl.F32, wl.F32)
     small = base_cfg(256, 256, 256, 0, 0, wl.F32, wl.F32)
+    tiny = base_cfg(24, 40, 12, 0, 1, wl.F32, wl.F32)
     odd = base_cfg(512, 642, 64, 0, 0, wl.F32, wl.F32)
-    for cfg, family in ((big, lg.GEMM_KERNEL_MFMA_TILE), (small, lg.GEMM_KERNEL_GENERAL), (odd, lg.GEMM_KERNEL_GENERAL)):
+    for cfg, family in ((big, lg.GEMM_KERNEL_MFMA_TILE), (small, lg.GEMM_KERNEL_MFMA_TILE), (tiny, lg.GEMM_KERNEL_MFMA_TILE),
+                        (odd, lg.GEMM_KERNEL_GENERAL)):
         inp = wl.make_inputs(cfg, 8)
         p = DeviceProblem(cfg, inp)
         p.run(handle)
