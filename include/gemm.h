@@ -69,7 +69,8 @@ typedef struct {
 
 /*
  * Creates a handle on the current HIP device.  The handle owns only a split-K workspace
- * (allocated on first need, grown on demand, freed by gemm_destroy).
+ * (allocated on first need, grown on demand, freed by gemm_destroy).  Calls that use the handle
+ * must be made with the same device current; otherwise they return GEMM_ERR_INVALID_ARG.
  * Errors: GEMM_ERR_INVALID_ARG if out is NULL; GEMM_ERR_HIP if no device is usable.
  */
 gemm_status_t gemm_create(gemm_handle_t* out);
@@ -95,7 +96,8 @@ gemm_status_t gemm_create(gemm_handle_t* out);
  *
  * Errors (C is untouched in every error case detected before launch):
  *   GEMM_ERR_INVALID_ARG  null handle; negative size; ld smaller than the stored row; a null
- *                         matrix pointer for a non-empty operand; an enum value out of range.
+ *                         matrix pointer for a non-empty operand; an enum value out of range; a
+ *                         current device other than the handle's.
  *   GEMM_ERR_UNSUPPORTED  out_dtype neither the input type nor GEMM_F32.
  *   GEMM_ERR_ALLOC        the split-K workspace could not be allocated.
  *   GEMM_ERR_HIP          a launch failed (the HIP error is consumed).

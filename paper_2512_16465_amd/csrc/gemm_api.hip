@@ -230,6 +230,11 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
     // the matrices of C must not overlap one another
     if (batch > 1 && M > 0 && N > 0 && strideC < (M - 1) * ldc + N) return GEMM_ERR_INVALID_ARG;
     if (M == 0 || N == 0 || batch == 0) return GEMM_OK;
+    {   // the handle (its workspace, its compute-unit count) belongs to the device it was created on
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_HIP; }
+        if (dev != h->device) return GEMM_ERR_INVALID_ARG;
+    }
     if (batch > kMaxBatchPerLaunch) {
         // more matrices than one grid holds: consecutive launches over consecutive parts of the batch
         const int64_t ea = gemm::elem_bytes((int)dtype), ec = gemm::elem_bytes((int)epi.out_dtype);
