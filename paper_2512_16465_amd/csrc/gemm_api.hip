@@ -47,22 +47,38 @@ constexpr double kSmallStreamPerK = 0.0122;  // ... and when its operands come f
 constexpr int64_t kCacheResidentBytes = (int64_t)128 << 20;
 // A last round that fills less than this fraction of the compute units is split along K (when the
 // variant can): each of its tiles goes to several workgroups, each over a share of the k slabs of
-// at least kMinSlabsPerPart, and a second kernel adds the parts.  The split costs a round trip of
-// the partial tiles through memory and a launch, estimated at an eighth of a whole k loop.
-constexpr double kSplitBelow = 0.6, kSplitOverhead = 0.125;
-constexpr int kMaxParts = 16, kMinSlabsPerPart = 16;
+// at least kMinSlabsPerPart, and a second kernel adds the parts.  The number of parts minimises
+// k loop / parts + the cost of the second kernel, which moves parts x tiles partial tiles of
+// 256 KiB (0.2 us each, write and read) and adds them one after the other (0.3 us per part).
+// Measured: 512x512x65536 (4 tiles) 89 / 67 / 86 us with 16 / 32 / 64 parts, 256x256x131072
+// (1 tile) 147 / 94 / 78 us, 1024x1024x16384 (16 tiles) 67 us with 16 parts.
+constexpr double kSplitBelow = 0.6, kReducePerPartTile = 0.2, kReducePerPart = 0.3, kReduceLaunch = 3.0;
+constexpr int kMinSlabsPerPart = 16;
+constexpr int kPartChoices[] = {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
 // Tile rows per band of the workgroup -> tile map: the 32 workgroups resident on an XCD then cover 4 x 8
 // tiles (8 x 4 with bands of 8 measured 0.5 % slower on 8192^3 and 8192x28672x8192, bands of 16 3 % slower).
 constexpr int kTileBandRows = 4;
 
+// time of the k loops of a round whose tiles are cut in `parts`, plus the second kernel (us)
+double split_round_time(int64_t tail, int parts, int64_t K) {
+    const double loop = kLargePerK * (double)K / parts;
+    if (parts <= 1) return loop;
+    const double move = kReducePerPartTile * parts * (double)tail, add = kReducePerPart * parts;
+    return loop + (move > add ? move : add) + kReduceLaunch;
+}
+
 // parts per tile of the trailing `tail` tiles (1 = no split)
 int tail_parts(int64_t tail, int64_t cus, int64_t K) {
     if (tail <= 0 || (double)tail >= kSplitBelow * (double)cus) return 1;
-    int64_t parts = cus / tail;
     const int64_t slabs = (K + 31) / 32;
-    if (parts > slabs / kMinSlabsPerPart) parts = slabs / kMinSlabsPerPart;
-    if (parts > kMaxParts) parts = kMaxParts;
-    return parts < 2 ? 1 : (int)parts;
+    int best = 1;
+    double best_t = split_round_time(tail, 1, K);
+    for (int parts : kPartChoices) {
+        if (parts * tail > cus || slabs / parts < kMinSlabsPerPart) break;
+        const double t = split_round_time(tail, parts, K);
+        if (t < best_t) { best_t = t; best = parts; }
+    }
+    return best;
 }
 
 struct TileChoice { int variant; int first_split_tile; int parts; };
@@ -91,7 +107,7 @@ TileChoice choose_tile(const Args& a, int num_cus) {
     const int parts = (large_ok && a.batch == 1) ? tail_parts(tail, cus, a.K) : 1;
     const double k = (double)a.K;
     double t_large = (double)(large / cus) * (kLargePerK * k + kLargeFixed);
-    if (tail) t_large += parts > 1 ? kLargePerK * k * (1.0 / parts + kSplitOverhead) + kLargeFixed : kLargePerK * k + kLargeFixed;
+    if (tail) t_large += split_round_time(tail, parts, a.K) + kLargeFixed;
     const bool streams = (a.M + a.N) * a.K * 2 * a.batch > kCacheResidentBytes;
     const double t_small = small <= cus ? (streams ? kSmallStreamPerK : kSmallAlonePerK) * k + kSmallFixed
                                         : (double)((small + cus - 1) / cus) * (kSmallPerK * k + kSmallFixed);
