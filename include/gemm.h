@@ -161,12 +161,16 @@ typedef struct {
     gemm_kernel_t kernel;   /* which family */
     int32_t variant;        /* tile variant index within the family; -1 = automatic */
     int32_t split_k;        /* number of K slices; 0 = automatic, 1 = none.  Skinny family: every
-                             * column group is cut into that many slices.  Macro-tile family: only
-                             * the tiles of the last, partly filled round of workgroups (all tiles
-                             * when there are fewer tiles than compute units) are cut, each into
-                             * that many shares of the k range; variants that cannot do so, and
-                             * batched calls, make the call return GEMM_ERR_UNSUPPORTED.  Slices are added in a fixed
-                             * order: results do not vary from run to run. */
+                             * column group is cut into that many slices.  Macro-tile family, the
+                             * 256x256 tiles on the 16x16x32 MFMA: only the tiles of the last, partly
+                             * filled round of workgroups (all tiles when there are fewer tiles than
+                             * compute units) are cut, each into that many shares of the k range.
+                             * Every other tile variant: the whole product is cut into that many
+                             * ranges of K (whole 32-element slabs; fewer if K has not enough of
+                             * them), computed side by side into fp32 partial results and added by a
+                             * second kernel; this needs N to be a multiple of 8.  Batched calls, and
+                             * calls that miss that condition, return GEMM_ERR_UNSUPPORTED.  Slices
+                             * are added in a fixed order: results do not vary from run to run. */
 } gemm_plan_t;
 
 /* Forces the plan used by later gemm_run calls on this handle; a NULL plan restores automatic

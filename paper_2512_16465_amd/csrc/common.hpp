@@ -22,6 +22,9 @@ struct Args {
     // a launch covers `batch` matrices with blockIdx.y (batch == 1: strides unused)
     int64_t strideA, strideB, strideC;
     int32_t batch;
+    // k slices: when nonzero, the batch entries are consecutive ranges of K elements of one product
+    // whose k extent is k_total (the last range may be shorter); the strides step along k
+    int64_t k_total;
 };
 
 __host__ __device__ __forceinline__ int elem_bytes(int dtype) { return dtype == DT_F32 ? 4 : 2; }
@@ -33,6 +36,10 @@ __device__ __forceinline__ void select_batch(Args& a) {
     a.A = (const char*)a.A + b * a.strideA * elem_bytes(a.dtype);
     a.B = (const char*)a.B + b * a.strideB * elem_bytes(a.dtype);
     a.C = (char*)a.C + b * a.strideC * elem_bytes(a.out_dtype);
+    if (a.k_total) {
+        const int64_t left = a.k_total - b * a.K;
+        a.K = left < a.K ? left : a.K;
+    }
 }
 
 // Rows of C can be read and written with vectors of four elements (16 bytes of fp32, 8 bytes of a
@@ -181,6 +188,10 @@ bool tile_variant_supports(const Args& a, int variant);
 // (or of the only one).
 struct TileSplit { int first_tile; int parts; float* partials; };
 bool tile_variant_splits(int variant);
+// Variants without that split can still divide K: the launch runs `slices` consecutive k ranges of
+// the product as a strided batch (Args::k_total) into fp32 partial results, and
+// launch_splitk_reduce adds them.
+bool tile_variant_slices(int variant);
 hipError_t launch_tile(const Args& a, int variant, int group_m, const TileSplit& split, hipStream_t stream);
 hipError_t launch_tile_split_reduce(const Args& a, int variant, int group_m, const TileSplit& split, hipStream_t stream);
 
@@ -193,6 +204,9 @@ int skinny_max_split(const Args& a);
 size_t skinny_workspace_bytes(const Args& a, int split_k);
 int skinny_default_split(const Args& a, int num_cus);
 hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream_t stream);
+// Adds `split_k` fp32 partial results `partials[s][M][N]` (rows N apart) in the order of s and applies
+// the epilogue of `a` into C.  N must be a multiple of 8.
+hipError_t launch_splitk_reduce(const Args& a, int split_k, const float* partials, hipStream_t stream);
 
 hipError_t launch_general(const Args& a, hipStream_t stream);
 

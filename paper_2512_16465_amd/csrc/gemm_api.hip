@@ -40,11 +40,6 @@ constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant 
 constexpr int kSmallTileShortK = 12;
 constexpr int64_t kShortK = 512;
 constexpr double kLargePerK = 0.0209, kLargeFixed = 15.0, kSmallPerK = 0.0094, kSmallFixed = 1.4;
-constexpr double kSmallAlonePerK = 0.0055;   // a small-tile workgroup that has its compute unit to itself (512x512x4096: 23 us) ...
-constexpr double kSmallStreamPerK = 0.0122;  // ... and when its operands come from HBM rather than from the caches: its ring keeps
-                                             // 48 KiB in flight against the large tile's 128 KiB (128x16384x16384: 200 us, and 118 us
-                                             // on the large tile with its 64 tiles cut in four)
-constexpr int64_t kCacheResidentBytes = (int64_t)128 << 20;
 // A last round that fills less than this fraction of the compute units is split along K (when the
 // variant can): each of its tiles goes to several workgroups, each over a share of the k slabs of
 // at least kMinSlabsPerPart, and a second kernel adds the parts.  The number of parts minimises
@@ -81,6 +76,44 @@ int tail_parts(int64_t tail, int64_t cus, int64_t K) {
     return best;
 }
 
+// The 128x128 tile has no such split; a grid of it that leaves compute units idle is cut in k
+// slices instead (a strided batch over k ranges into fp32 partial results, added by the reduce
+// kernel of the skinny family).  Time of the small tile with `slices` (1 = none), us.  A workgroup
+// that has its compute unit to itself walks k at a rate set by where its operands come from:
+// 0.0055 us per k for a handful of workgroups out of the L2 (512x512x4096: 23 us), 0.008 with 64
+// or more (1024x1024x4096: 31 us, 512x8192x8192: 72), 0.0122 when the operands exceed the
+// last-level cache and come from HBM (128 ... 256 x 16384 x 16384: 186 to 200 us) - its ring keeps
+// 48 KiB in flight against the large tile's 128 KiB.  Two workgroups per unit: kSmallPerK per round.
+// The whole call is not faster than HBM delivers (4.7 TB/s reached by the sliced small tile).
+// Slices add the second kernel: launch + the partial results written and read once.
+constexpr double kSmallAloneFew = 0.0055, kSmallAloneMany = 0.008, kSmallAloneHbm = 0.0122;
+constexpr double kSmallHbmRate = 4.7e6, kLargeHbmRate = 4.4e6, kSliceMoveRate = 4.5e6;      // bytes per us
+constexpr int kSliceChoices[] = {2, 4, 8, 16};
+constexpr int64_t kMinSliceK = 256;
+// Operands beyond the last-level cache stream from HBM on every call; there the large tile with its split
+// stays ahead of the sliced small tile (128x16384x16384: 114 against 125 us, 128x8192x28672: 104
+// against 119), so slices are considered only below this size (96...256 x 8192 x 8192, 134 to 138 MB:
+// 33 to 44 us sliced against 46 to 56 on the large tile).
+constexpr int64_t kLastLevelCacheBytes = (int64_t)256 << 20;
+
+double small_tile_time(const Args& a, int64_t tiles, int slices, int64_t cus) {
+    const double k = (double)a.K / slices;
+    const int64_t wgs = tiles * slices, rounds = (wgs + cus - 1) / cus;
+    const double bytes = (double)(a.M + a.N) * (double)a.K * 2.0 * (double)a.batch;
+    const bool hbm = bytes > (double)kLastLevelCacheBytes;
+    double loop;
+    if (wgs <= cus) {
+        const double crowd = wgs >= 64 ? 1.0 : (double)wgs / 64.0;
+        loop = (hbm ? kSmallAloneHbm : kSmallAloneFew + (kSmallAloneMany - kSmallAloneFew) * crowd) * k;
+    } else {
+        loop = (double)rounds * kSmallPerK * k;
+    }
+    if (hbm && bytes / kSmallHbmRate > loop) loop = bytes / kSmallHbmRate;
+    double t = loop + (double)rounds * kSmallFixed;
+    if (slices > 1) t += kReduceLaunch + (double)slices * (double)(a.M * a.N) * 8.0 / kSliceMoveRate;
+    return t;
+}
+
 struct TileChoice { int variant; int first_split_tile; int parts; };
 // fp32: the 128x128 or the 64x64 tile, whichever leaves the busiest compute unit less to do (see
 // choose_tile).  The small tile is at least as fast as the general kernel down to a single tile
@@ -108,15 +141,25 @@ TileChoice choose_tile(const Args& a, int num_cus) {
     const double k = (double)a.K;
     double t_large = (double)(large / cus) * (kLargePerK * k + kLargeFixed);
     if (tail) t_large += split_round_time(tail, parts, a.K) + kLargeFixed;
-    const bool streams = (a.M + a.N) * a.K * 2 * a.batch > kCacheResidentBytes;
-    const double t_small = small <= cus ? (streams ? kSmallStreamPerK : kSmallAlonePerK) * k + kSmallFixed
-                                        : (double)((small + cus - 1) / cus) * (kSmallPerK * k + kSmallFixed);
+    // operands that stream from HBM: not faster than the large tile pulls them (65536x128x4096: 146 us)
+    const double bytes = (double)(a.M + a.N) * k * 2.0 * (double)a.batch;
+    if (bytes > (double)kLastLevelCacheBytes && bytes / kLargeHbmRate + kLargeFixed > t_large) t_large = bytes / kLargeHbmRate + kLargeFixed;
+    const bool small_ok = gemm::tile_variant_supports(a, kSmallTileVariant);
+    double t_small = small_tile_time(a, small, 1, cus);
+    int slices = 1;
+    if (small_ok && a.batch == 1 && a.N % 8 == 0 && (a.M + a.N) * a.K * 2 <= kLastLevelCacheBytes) {
+        for (int sl : kSliceChoices) {
+            if (a.K / sl < kMinSliceK || small * sl > 2 * cus) break;
+            const double t = small_tile_time(a, small, sl, cus);
+            if (t < t_small) { t_small = t; slices = sl; }
+        }
+    }
     if (t_large <= t_small) {
         if (!large_ok) return TileChoice{kLargeTileFallback, 0, 1};
         return TileChoice{kLargeTileVariant, (int)(large - tail), parts};
     }
-    if (!gemm::tile_variant_supports(a, kSmallTileVariant)) return TileChoice{kSmallTileFallback, 0, 1};
-    return TileChoice{a.K <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, 1};
+    if (!small_ok) return TileChoice{kSmallTileFallback, 0, 1};
+    return TileChoice{a.K / slices <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, slices};
 }
 
 gemm_status_t ensure_workspace(gemm_handle_s* h, size_t bytes, hipStream_t stream) {
@@ -274,6 +317,7 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
     a.A = A; a.lda = lda; a.B = B; a.ldb = ldb; a.C = C; a.ldc = ldc;
     a.bias = epi.bias;
     a.batch = (int32_t)batch;
+    a.k_total = 0;
     a.strideA = batch > 1 ? strideA : 0; a.strideB = batch > 1 ? strideB : 0; a.strideC = batch > 1 ? strideC : 0;
     // the matrix-core kernels read 16-byte vectors: every matrix of the batch must start on a 16-byte boundary
     const int64_t in_bytes = gemm::elem_bytes(a.dtype);
@@ -296,8 +340,9 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
             }
             if (!gemm::tile_variant_supports(a, plan.variant)) return GEMM_ERR_UNSUPPORTED;
             if (plan.split_k < 1) plan.split_k = 1;
-            if (plan.split_k > 1 && (!gemm::tile_variant_splits(plan.variant) || batch > 1)) return GEMM_ERR_UNSUPPORTED;
-            if (plan.split_k > 1 && split_first < 0) {
+            if (plan.split_k > 1 && batch > 1) return GEMM_ERR_UNSUPPORTED;
+            if (plan.split_k > 1 && !gemm::tile_variant_splits(plan.variant) && N % 8 != 0) return GEMM_ERR_UNSUPPORTED;
+            if (plan.split_k > 1 && gemm::tile_variant_splits(plan.variant) && split_first < 0) {
                 // a forced split applies to the trailing partial round, or to every tile of a grid smaller than one round
                 const gemm::TileVariantInfo* info = gemm::tile_variant_info(plan.variant);
                 const int64_t tiles = ((a.M + info->BM - 1) / info->BM) * ((a.N + info->BN - 1) / info->BN);
@@ -351,16 +396,38 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
             const int64_t slabs = (K + 31) / 32;
             if (plan.split_k > slabs) plan.split_k = (int)slabs;
         }
-        if (plan.split_k > 1) {
+        int64_t slice_len = 0;
+        if (plan.split_k > 1 && !gemm::tile_variant_splits(plan.variant)) {
+            // k slices: ranges of whole 32-element slabs, all of one length but the last
+            const int64_t slabs = (K + 31) / 32;
+            slice_len = ((slabs + plan.split_k - 1) / plan.split_k) * 32;
+            plan.split_k = (int)((K + slice_len - 1) / slice_len);
+        }
+        if (plan.split_k > 1 && slice_len > 0) {
+            const int64_t len = slice_len;
+            const gemm_status_t st = ensure_workspace(h, (size_t)plan.split_k * (size_t)M * (size_t)N * sizeof(float), stream);
+            if (st != GEMM_OK) return st;
+            Args p = a;
+            p.K = len; p.k_total = K;
+            p.batch = plan.split_k;
+            p.strideA = a.transA ? len * a.lda : len;
+            p.strideB = a.transB ? len : len * a.ldb;
+            p.C = h->workspace; p.ldc = N; p.strideC = M * N;
+            p.out_dtype = gemm::DT_F32; p.alpha = 1.0f; p.beta = 0.0f; p.bias = nullptr; p.act = gemm::ACT_NONE;
+            e = gemm::launch_tile(p, plan.variant, kTileBandRows, split, stream);
+            if (e == hipSuccess) e = gemm::launch_splitk_reduce(a, plan.split_k, h->workspace, stream);
+        } else if (plan.split_k > 1) {
             const gemm::TileVariantInfo* info = gemm::tile_variant_info(plan.variant);
             const int64_t tiles = ((a.M + info->BM - 1) / info->BM) * ((a.N + info->BN - 1) / info->BN);
             const size_t need = (size_t)(tiles - split_first) * plan.split_k * info->BM * info->BN * sizeof(float);
             const gemm_status_t st = ensure_workspace(h, need, stream);
             if (st != GEMM_OK) return st;
             split = gemm::TileSplit{split_first, plan.split_k, h->workspace};
+            e = gemm::launch_tile(a, plan.variant, kTileBandRows, split, stream);
+            if (e == hipSuccess) e = gemm::launch_tile_split_reduce(a, plan.variant, kTileBandRows, split, stream);
+        } else {
+            e = gemm::launch_tile(a, plan.variant, kTileBandRows, split, stream);
         }
-        e = gemm::launch_tile(a, plan.variant, kTileBandRows, split, stream);
-        if (e == hipSuccess && split.parts > 1) e = gemm::launch_tile_split_reduce(a, plan.variant, kTileBandRows, split, stream);
     } else {
         e = gemm::launch_general(a, stream);
     }

@@ -581,13 +581,19 @@ hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split_k == 1) return e;
+    return launch_splitk_reduce(a, split_k, workspace, stream);
+}
+
+hipError_t launch_splitk_reduce(const Args& a, int split_k, const float* partials, hipStream_t stream) {
+    if (split_k < 1 || partials == nullptr || (a.N & 7)) return hipErrorInvalidValue;
+    const int c_vec_ok = (a.ldc % 8 == 0) && ((uintptr_t)a.C % 16 == 0);
     const int64_t threads = a.M * (a.N / 8);
     const dim3 rgrid((unsigned)((threads + 255) / 256)), rblock(256);
-    const float* partials = workspace;
     switch (split_k) {
         case 2: hipLaunchKernelGGL(splitk_reduce_kernel<2>, rgrid, rblock, 0, stream, a, split_k, partials, c_vec_ok); break;
         case 4: hipLaunchKernelGGL(splitk_reduce_kernel<4>, rgrid, rblock, 0, stream, a, split_k, partials, c_vec_ok); break;
         case 8: hipLaunchKernelGGL(splitk_reduce_kernel<8>, rgrid, rblock, 0, stream, a, split_k, partials, c_vec_ok); break;
+        case 16: hipLaunchKernelGGL(splitk_reduce_kernel<16>, rgrid, rblock, 0, stream, a, split_k, partials, c_vec_ok); break;
         default: hipLaunchKernelGGL(splitk_reduce_kernel<0>, rgrid, rblock, 0, stream, a, split_k, partials, c_vec_ok); break;
     }
     return hipGetLastError();

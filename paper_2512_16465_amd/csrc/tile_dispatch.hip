@@ -63,6 +63,7 @@ bool tile_variant_supports(const Args& a, int variant) {
 }
 
 bool tile_variant_splits(int variant) { return variant >= 0 && variant < kNum && kInfo[variant].kind == 3; }
+bool tile_variant_slices(int variant) { return variant >= 0 && variant < kNum && kInfo[variant].kind != 3; }
 
 hipError_t launch_tile(const Args& a, int variant, int group_m, const TileSplit& split, hipStream_t stream) {
     if (variant < 0 || variant >= kNum) return hipErrorInvalidValue;

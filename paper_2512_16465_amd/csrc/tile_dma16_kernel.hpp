@@ -188,8 +188,11 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     // channels.  This workgroup takes its slabs in the order rot, rot+1, ..., k_tiles-1, 0, ...,
     // rot-1 (rot even, so that pairs of slabs still cover whole cache lines); the sum over k is
     // taken in that order, a fixed function of the tile.  Needs whole slabs and an even count.
+    // The start depends on the tile's index along the longer side of C only: tiles that share a
+    // panel of the larger operand keep walking it in step, so one fetch still serves them all.
+    const int rot_key = a.N >= a.M ? tn : tm;
     const int rot = (rotate && k_tiles == full_tiles && (k_tiles & 1) == 0 && k_tiles >= 2 * NS)
-                        ? 2 * (int)((unsigned)(pid * 5 + (part > 0 ? part : 0) * 3) % (unsigned)(k_tiles / 2)) : 0;
+                        ? 2 * (int)((unsigned)(rot_key * 5 + (part > 0 ? part : 0) * 3) % (unsigned)(k_tiles / 2)) : 0;
     auto physical = [&](int t) { const int p = t + rot; return p >= k_tiles ? p - k_tiles : p; };   // slab in memory of step t
     constexpr int NM = TM * TN, NR = TM + TN;     // MFMAs and fragments per step
     constexpr int LPT = LA::L + LB::L;            // loads per thread and slab (= per half of a pair)
@@ -409,10 +412,12 @@ hipError_t launch_dma16_variant(const Args& a, int group_m, const TileSplit& spl
     const bool bf = a.dtype == DT_BF16;
     const bool akc = !a.transA, bkc = a.transB != 0;
     const int c_vec_ok = c_rows_take_vec4(a);
-    // A split call streams its operands (few tiles, long k): rotate the k walk when a k-contiguous
+    // A split call streams its operands (few tiles, long k), and so does a single row or column of
+    // tiles whose operands exceed the last-level cache: rotate the k walk when a k-contiguous
     // operand has its rows a multiple of 4 KiB apart (see the kernel).
     const bool a_aliases = akc && (a.lda * 2) % 4096 == 0, b_aliases = bkc && (a.ldb * 2) % 4096 == 0;
-    const int rotate = splits && (a_aliases || b_aliases);
+    const bool one_panel_each = (tiles_m == 1 || tiles_n == 1) && (a.M + a.N) * a.K * 2 > ((int64_t)256 << 20);
+    const int rotate = (splits || one_panel_each) && (a_aliases || b_aliases);
 #define GEMM_TILE_LAUNCH(BF, AKC, BKC) \
     hipLaunchKernelGGL((tile_dma16_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok, \
                        split_first, split_parts, split.partials, rotate)

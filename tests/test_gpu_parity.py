@@ -136,11 +136,80 @@ def test_tile_split_of_the_trailing_round(handle, ta, tb):
             assert np.array_equal(got, want), f"variant {v} parts {parts}: {np.sum(got != want)} wrong elements"
             pad_got = p.result_bits()[:-1, cfg.N:]
             assert np.array_equal(pad_got, inp["C"].reshape(M, cfg.ld_c())[:-1, cfg.N:])
-    # a variant that cannot split refuses
-    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, 4, 2)
+    lg.gemm_set_plan(handle)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0), (1, 1), (1, 0)])
+def test_tile_k_slices(handle, ta, tb):
+    # Every tile variant without the split above cuts K into slices instead: consecutive ranges of whole
+    # slabs, computed side by side into fp32 partial results that a second kernel adds in order before the
+    # epilogue.  Integer data -> exact.  K = 1096: 35 slabs, the last one partial; 3 slices of 12 / 12 / 11
+    # slabs, 16 slices of 3 / ... / 2 (12 ranges in all), 64 -> one slab each (35).  Edge tiles in both
+    # directions, padded ldc whose padding must stay untouched.
+    M, N, K = 392, 328, 1096
+    cfg = base_cfg(M, N, K, ta, tb, wl.BF16, wl.BF16, alpha=2.0, beta=-1.0, bias_dist=("normal", 1.0), bias_dtype=wl.F32,
+                   act=wl.ACT_RELU, ldc=N + 5)
+    inp, _ = wl.make_integer_inputs(cfg, 81, -2, 2)
+    want = oracle.decode(wl.BF16, expected_bits_exact(cfg, inp))
+    slicing = [v for v in tile_variants() if "dma16" not in lg.gemm_variant_name(lg.GEMM_KERNEL_MFMA_TILE, v)]
+    assert slicing
+    for v in slicing:
+        for slices, used_want in ((3, 3), (16, 12), (64, 35)):
+            print(f"k slices variant {v} slices {slices} ta={ta} tb={tb}", flush=True)
+            lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v, slices)
+            p = DeviceProblem(cfg, inp)
+            p.run(handle)
+            assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_MFMA_TILE, v, used_want)
+            got = decode_c(cfg, p.result_bits())
+            assert np.array_equal(got, want), f"variant {v} slices {slices}: {np.sum(got != want)} wrong elements"
+            pad_got = p.result_bits()[:-1, cfg.N:]
+            assert np.array_equal(pad_got, inp["C"].reshape(M, cfg.ld_c())[:-1, cfg.N:])
+    lg.gemm_set_plan(handle)
+
+
+def test_tile_k_slices_fp32_refusals_and_automatic_choice(handle):
+    # fp32 tile kernels slice the same way (Gaussian data to the fp32 tolerance, integer data exactly)
+    for v in tile_variants(f32=True):
+        cfg = base_cfg(200, 264, 1000, 0, 1, wl.F32, wl.F32, alpha=0.5, beta=2.0, a_dist=("normal", 1.0), b_dist=("normal", 0.5),
+                       c_dist=("normal", 1.0), bias_dist=("normal", 1.0), bias_dtype=wl.F32, act=wl.ACT_GELU_TANH)
+        inp = wl.make_inputs(cfg, 82)
+        ref, _, mag = oracle.gemm_full(oracle_problem(cfg, inp), want_bounds=True)
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v, 5)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_MFMA_TILE, v, 5)
+        assert_close(cfg, decode_c(cfg, p.result_bits()), ref, mag, f"fp32 k slices variant {v}")
+    # slices need N to be a multiple of 8 (the adding kernel works on groups of 8 columns), and one matrix
+    cfg = base_cfg(256, 132, 1024, 0, 1, wl.BF16, wl.F32, beta=1.0)
+    inp, _ = wl.make_integer_inputs(cfg, 83, -2, 2)
+    before = inp["C"].copy()
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, 5, 4)
     p = DeviceProblem(cfg, inp)
     assert p.run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED
+    assert np.array_equal(p.result_bits().reshape(-1), before.reshape(-1))
     lg.gemm_set_plan(handle)
+    # automatic choice: 16 tiles of 128 x 128 with a long k loop are sliced; exact on integer data,
+    # within the bounds on Gaussian data, the same bits on a second run
+    cfg = base_cfg(512, 512, 4096, 0, 0, wl.BF16, wl.BF16, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.BF16)
+    inp, _ = wl.make_integer_inputs(cfg, 84, -1, 1)
+    want = oracle.decode(wl.BF16, expected_bits_exact(cfg, inp))
+    p = DeviceProblem(cfg, inp)
+    p.run(handle)
+    kernel, variant, slices = lg.gemm_get_last_plan(handle)
+    assert kernel == lg.GEMM_KERNEL_MFMA_TILE and slices > 1
+    assert "dma16" not in lg.gemm_variant_name(kernel, variant)
+    assert np.array_equal(decode_c(cfg, p.result_bits()), want)
+    gcfg = base_cfg(512, 512, 4096, 0, 1, wl.BF16, wl.BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.05))
+    ginp = wl.make_inputs(gcfg, 85)
+    gref, _, gmag = oracle.gemm_full(oracle_problem(gcfg, ginp), want_bounds=True)
+    g = DeviceProblem(gcfg, ginp)
+    g.run(handle)
+    first = g.result_bits().copy()
+    assert lg.gemm_get_last_plan(handle)[2] > 1
+    assert_close(gcfg, decode_c(gcfg, first), gref, gmag, "automatic k slices")
+    g2 = DeviceProblem(gcfg, ginp)
+    g2.run(handle)
+    assert np.array_equal(first, g2.result_bits())
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0), (1, 1), (1, 0)])
