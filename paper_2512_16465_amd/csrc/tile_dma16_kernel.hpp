@@ -380,6 +380,7 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     // a share of a split tile goes, as it is, to its fp32 tile among the partials
     Args e = a;
     int64_t em0 = m0, en0 = n0;
+    const int64_t live_rows = a.M - m0;       // rows of the tile inside C: bands below them are not stored (nor read back)
     if (part >= 0) {
         e.C = partials + ((size_t)(pid - split_first) * split_parts + part) * (BM * BN);
         e.ldc = BN; e.M = BM; e.N = BN;
@@ -399,7 +400,7 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
                     for (int v = 0; v < 4; ++v)
                         *(float*)(region + ((16 * i2 + 4 * g4 + v) * EL::RS + j * 16 + c16) * 4) = acc[2 * b + i2][j][v];
         },
-        lds, e, em0, en0, c_vec_ok);
+        lds, e, em0, en0, c_vec_ok, live_rows);
 }
 
 template <class C>

@@ -244,7 +244,8 @@ struct EpiLayout {
 // that wave's accumulators, to region[(row * EL::RS + column) * 4]; `band` is an
 // std::integral_constant, so the accumulator registers it names are static.
 template <class C, class Dump>
-__device__ __forceinline__ void tile_epilogue_bands(Dump dump, char* lds, const Args& a, int64_t m0, int64_t n0, int c_vec_ok) {
+__device__ __forceinline__ void tile_epilogue_bands(Dump dump, char* lds, const Args& a, int64_t m0, int64_t n0, int c_vec_ok,
+                                                    int64_t live_rows = INT64_MAX) {
     constexpr int TM = C::TM;
     using EL = EpiLayout<C>;
     const int tid = threadIdx.x;
@@ -274,6 +275,9 @@ __device__ __forceinline__ void tile_epilogue_bands(Dump dump, char* lds, const 
         typename OV::elem* Cp = (typename OV::elem*)a.C;
 #pragma unroll 1
         for (int i = 0; i < TM; ++i) {
+            // this band and the ones below it lie under the last row of C (`live_rows`: the same for a caller that
+            // stores a whole tile somewhere else)
+            if (m0 + wm * C::WTM + i * 32 >= a.M || wm * C::WTM + i * 32 >= live_rows) break;
             // one case per band; the distinct marker at the end of each case keeps the optimiser from
             // merging the cases into an indexed (scratch-memory) access to the accumulators
             switch (i) {
