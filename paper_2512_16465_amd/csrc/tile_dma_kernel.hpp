@@ -207,7 +207,7 @@ __device__ __forceinline__ void wait_raw(u32x4 (&)[2]) {}
 __device__ __forceinline__ void wait_raw(u32x4 (&)[4]) {}
 
 template <class C, bool IS_BF16, bool A_KC, bool B_KC, bool PLAIN>
-__global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok) {
+__global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok, int rotate) {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NT, TM = C::TM, TN = C::TN, NS = C::NS;
     using EL = EpiLayout<C>;
     constexpr int RING = NS * C::STAGE;
@@ -254,6 +254,14 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
 
     const int k_tiles = (K + BK - 1) / BK;
     const int full_tiles = K / BK;
+    // Rotation of the k walk (`rotate`, set by the host for calls that stream from HBM an operand
+    // whose rows lie a multiple of 4 KiB apart: at a given k all its rows sit on one memory channel,
+    // and workgroups walking k in step would queue there).  Step t takes the slab (t + rot) mod
+    // k_tiles; rot depends on the tile's index along the longer side of C, so that the tiles
+    // sharing a panel of the larger operand still walk it together.  Whole slabs only.
+    const int rot = (rotate && k_tiles == full_tiles && k_tiles >= 2 * NS)
+                        ? (int)((unsigned)((a.N >= a.M ? tn : tm) * 10) % (unsigned)k_tiles) : 0;
+    auto physical = [&](int t) { const int p = t + rot; return p >= k_tiles ? p - k_tiles : p; };
     constexpr int NKS = BK / 16;
     constexpr int NM = TM * TN, NR = TM + TN;
     constexpr int LPT = LA::L + LB::L;            // direct-to-LDS loads per thread and slab
@@ -292,11 +300,12 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
         else lb.issue(M, q - LA::L, rb, stage + C::A_BYTES, wave, tid, k0, K, soff_b);
     };
     auto issue_tile = [&](int t, auto masked) {
-        const __amdgpu_buffer_rsrc_t ra = make_rsrc(pa + t * a_step, a_bytes - t * a_step);
-        const __amdgpu_buffer_rsrc_t rb = make_rsrc(pb + t * b_step, b_bytes - t * b_step);
+        const int p = physical(t);
+        const __amdgpu_buffer_rsrc_t ra = make_rsrc(pa + p * a_step, a_bytes - p * a_step);
+        const __amdgpu_buffer_rsrc_t rb = make_rsrc(pb + p * b_step, b_bytes - p * b_step);
         char* stage = lds + (t % NS) * C::STAGE;
 #pragma unroll
-        for (int q = 0; q < LPT; ++q) issue_one(q, ra, rb, stage, t * BK, masked);
+        for (int q = 0; q < LPT; ++q) issue_one(q, ra, rb, stage, p * BK, masked);
     };
 
     // The barrier of a k step: this wave's share of slab kt+1 has landed once at most `pending`
@@ -320,8 +329,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
     const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(pa, a_bytes), rb0 = make_rsrc(pb, b_bytes);
     auto step_hot = [&](int kt) {
         const int stage = kt % NS, next = (kt + 1) % NS;
-        const int t = kt + D;
-        const uint32_t soff_a = (uint32_t)(t * a_step), soff_b = (uint32_t)(t * b_step);
+        const int t = kt + D, p = physical(t);
+        const uint32_t soff_a = (uint32_t)(p * a_step), soff_b = (uint32_t)(p * b_step);
         char* dst = lds + (t % NS) * C::STAGE;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
@@ -347,7 +356,7 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
                 if (slot < LOAD_SLOTS) {
 #pragma unroll
                     for (int q = (slot * LPT) / LOAD_SLOTS; q < ((slot + 1) * LPT) / LOAD_SLOTS; ++q)
-                        issue_one(q, ra0, rb0, dst, t * BK, std::false_type{}, soff_a, soff_b);
+                        issue_one(q, ra0, rb0, dst, p * BK, std::false_type{}, soff_a, soff_b);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -403,14 +412,20 @@ hipError_t launch_dma_variant(const Args& a, int group_m, hipStream_t stream) {
     const bool akc = !a.transA, bkc = a.transB != 0;
     const int c_vec_ok = c_rows_take_vec4(a);
     const bool plain = plain_epilogue_applies<C>(a);
+    // a single row or column of tiles, operands beyond the last-level cache, one of them k-contiguous with
+    // rows a multiple of 4 KiB apart (65536x128x4096: 125 -> 119 us, 128x28672x8192 with B stored N x K:
+    // 123 -> 105; grids with several tiles in both directions did not gain)
+    const bool a_aliases = akc && (a.lda * 2) % 4096 == 0, b_aliases = bkc && (a.ldb * 2) % 4096 == 0;
+    const int rotate = (a_aliases || b_aliases) && a.k_total == 0 && (tiles_m == 1 || tiles_n == 1) &&
+                       (a.M + a.N) * a.K * 2 > ((int64_t)256 << 20);
 #define GEMM_TILE_LAUNCH(BF, AKC, BKC)                                                                         \
     do {                                                                                                       \
         if (plain)                                                                                             \
             hipLaunchKernelGGL((tile_dma_kernel<C, BF, AKC, BKC, true>), grid, block, 0, stream, a, tiles_m,   \
-                               tiles_n, group_m, c_vec_ok);                                                    \
+                               tiles_n, group_m, c_vec_ok, rotate);                                            \
         else                                                                                                   \
             hipLaunchKernelGGL((tile_dma_kernel<C, BF, AKC, BKC, false>), grid, block, 0, stream, a, tiles_m,  \
-                               tiles_n, group_m, c_vec_ok);                                                    \
+                               tiles_n, group_m, c_vec_ok, rotate);                                            \
     } while (0)
     if (bf) {
         if (akc && bkc) GEMM_TILE_LAUNCH(true, true, true);
