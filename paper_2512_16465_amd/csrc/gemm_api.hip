@@ -24,7 +24,7 @@ bool valid_dtype(int d) { return d == GEMM_F32 || d == GEMM_F16 || d == GEMM_BF1
 
 // Picks a tile variant for the macro-tile family by comparing two estimates of the run time in
 // microseconds.  A workgroup of the 256x256 tile (16x16x32 MFMA, direct-to-LDS, one workgroup per
-// compute unit) takes kLargePerK * K for its k loop plus kLargeFixed for filling the pipeline
+// compute unit) takes 0.0209 us * K for its k loop plus 15 us for filling the pipeline
 // and for the epilogue, which nothing overlaps; the 128x128 tile (two workgroups per compute
 // unit, each other's epilogue hidden behind the other's k loop) takes kSmallPerK * K + kSmallFixed
 // per tile and compute unit.  Measured: 8192^3 in 744 us with the large tile (4 rounds) and
@@ -39,7 +39,7 @@ constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant 
 // compute unit instead of two; 3 to 15 % faster for K <= 512, slower beyond)
 constexpr int kSmallTileShortK = 12;
 constexpr int64_t kShortK = 512;
-constexpr double kLargePerK = 0.0209, kLargeFixed = 15.0, kSmallPerK = 0.0094, kSmallFixed = 1.4;
+constexpr double kSmallPerK = 0.0094, kSmallFixed = 1.4;     // (the large tile's 0.0209 us per k and 15 us fixed: kFullTile below)
 // A last round that fills less than this fraction of the compute units is split along K (when the
 // variant can): each of its tiles goes to several workgroups, each over a share of the k slabs of
 // at least kMinSlabsPerPart, and a second kernel adds the parts.  The number of parts minimises
@@ -54,26 +54,52 @@ constexpr int kPartChoices[] = {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
 // tiles (8 x 4 with bands of 8 measured 0.5 % slower on 8192^3 and 8192x28672x8192, bands of 16 3 % slower).
 constexpr int kTileBandRows = 4;
 
+// The 16x16x32 kernel with its tile halved along one side (256x128, 128x256): half the MFMAs per
+// slab and 12 instead of 16 fragment reads, so LDS rather than the matrix pipe bounds it
+// (4096^3: 116 us on either against 94 on the full tile = 0.0117 us per k and tile, 10 us fixed).
+// It pays where the full tile would be half empty: 65536x128x4096 100 us against 120 on the
+// 128x128 tile and 146 on the full tile, 32768x256x4096 75 against 87.
+struct Dma16Tile { int variant; int bm, bn; double per_k, fixed, hbm_rate; };
+constexpr Dma16Tile kFullTile{10, 256, 256, 0.0209, 15.0, 4.4e6};
+constexpr Dma16Tile kTallTile{14, 256, 128, 0.0117, 10.0, 5.8e6};
+constexpr Dma16Tile kWideTile{15, 128, 256, 0.0117, 10.0, 5.8e6};
+
 // time of the k loops of a round whose tiles are cut in `parts`, plus the second kernel (us)
-double split_round_time(int64_t tail, int parts, int64_t K) {
-    const double loop = kLargePerK * (double)K / parts;
+double split_round_time(const Dma16Tile& t, int64_t tail, int parts, int64_t K) {
+    const double loop = t.per_k * (double)K / parts;
     if (parts <= 1) return loop;
-    const double move = kReducePerPartTile * parts * (double)tail, add = kReducePerPart * parts;
+    const double area = (double)(t.bm * t.bn) / 65536.0;
+    const double move = kReducePerPartTile * area * parts * (double)tail, add = kReducePerPart * parts;
     return loop + (move > add ? move : add) + kReduceLaunch;
 }
 
 // parts per tile of the trailing `tail` tiles (1 = no split)
-int tail_parts(int64_t tail, int64_t cus, int64_t K) {
+int tail_parts(const Dma16Tile& t, int64_t tail, int64_t cus, int64_t K) {
     if (tail <= 0 || (double)tail >= kSplitBelow * (double)cus) return 1;
     const int64_t slabs = (K + 31) / 32;
     int best = 1;
-    double best_t = split_round_time(tail, 1, K);
+    double best_t = split_round_time(t, tail, 1, K);
     for (int parts : kPartChoices) {
         if (parts * tail > cus || slabs / parts < kMinSlabsPerPart) break;
-        const double t = split_round_time(tail, parts, K);
-        if (t < best_t) { best_t = t; best = parts; }
+        const double tt = split_round_time(t, tail, parts, K);
+        if (tt < best_t) { best_t = tt; best = parts; }
     }
     return best;
+}
+
+// whole call on one of the 16x16x32 tiles: full rounds, then the trailing round with its split
+double dma16_time(const Dma16Tile& t, const Args& a, int64_t cus, bool may_split, int* parts_out, int64_t* first_split) {
+    const int64_t tiles = ((a.M + t.bm - 1) / t.bm) * ((a.N + t.bn - 1) / t.bn) * a.batch;
+    const int64_t tail = tiles % cus;
+    const int parts = may_split ? tail_parts(t, tail, cus, a.K) : 1;
+    double time = (double)(tiles / cus) * (t.per_k * (double)a.K + t.fixed);
+    if (tail) time += split_round_time(t, tail, parts, a.K) + t.fixed;
+    // operands that stream from HBM: not faster than this tile pulls them
+    const double bytes = (double)(a.M + a.N) * (double)a.K * 2.0 * (double)a.batch;
+    if (bytes > (double)((int64_t)256 << 20) && bytes / t.hbm_rate + t.fixed > time) time = bytes / t.hbm_rate + t.fixed;
+    *parts_out = parts;
+    *first_split = tiles - tail;
+    return time;
 }
 
 // The 128x128 tile has no such split; a grid of it that leaves compute units idle is cut in k
@@ -87,7 +113,7 @@ int tail_parts(int64_t tail, int64_t cus, int64_t K) {
 // The whole call is not faster than HBM delivers (4.7 TB/s reached by the sliced small tile).
 // Slices add the second kernel: launch + the partial results written and read once.
 constexpr double kSmallAloneFew = 0.0055, kSmallAloneMany = 0.008, kSmallAloneHbm = 0.0122;
-constexpr double kSmallHbmRate = 4.7e6, kLargeHbmRate = 4.4e6, kSliceMoveRate = 4.5e6;      // bytes per us
+constexpr double kSmallHbmRate = 4.7e6, kSliceMoveRate = 4.5e6;      // bytes per us
 constexpr int kSliceChoices[] = {2, 4, 8, 16};
 constexpr int64_t kMinSliceK = 256;
 // Operands beyond the last-level cache stream from HBM on every call; there the large tile with its split
@@ -134,16 +160,25 @@ TileChoice choose_tile(const Args& a, int num_cus) {
         return TileChoice{t128 <= t64 ? kF32TileVariant : kF32SmallTileVariant, 0, 1};
     }
     // a batch multiplies the number of workgroups; its trailing round is never split along K
-    const int64_t large = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch, small = ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
+    const int64_t small = ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
     const bool large_ok = gemm::tile_variant_supports(a, kLargeTileVariant);
-    const int64_t tail = large % cus;
-    const int parts = (large_ok && a.batch == 1) ? tail_parts(tail, cus, a.K) : 1;
-    const double k = (double)a.K;
-    double t_large = (double)(large / cus) * (kLargePerK * k + kLargeFixed);
-    if (tail) t_large += split_round_time(tail, parts, a.K) + kLargeFixed;
-    // operands that stream from HBM: not faster than the large tile pulls them (65536x128x4096: 146 us)
-    const double bytes = (double)(a.M + a.N) * k * 2.0 * (double)a.batch;
-    if (bytes > (double)kLastLevelCacheBytes && bytes / kLargeHbmRate + kLargeFixed > t_large) t_large = bytes / kLargeHbmRate + kLargeFixed;
+    const Dma16Tile* best_tile = &kFullTile;
+    int parts = 1;
+    int64_t first_split = 0;
+    double t_large = dma16_time(kFullTile, a, cus, large_ok && a.batch == 1, &parts, &first_split);
+    if (large_ok) {
+        // a half tile where every full tile would be at least half empty (N <= 128 or M <= 128); with more
+        // rows or columns of tiles only the last one gains, and the estimates are not sharp enough to
+        // pick that up (4096x4224x4096: 131 us on the full tile, 145 to 170 on 256x128)
+        for (const Dma16Tile* t : {&kTallTile, &kWideTile}) {
+            const int64_t halves = t == &kTallTile ? (a.N + 127) / 128 : (a.M + 127) / 128;
+            if (halves != 1) continue;
+            int p = 1;
+            int64_t f = 0;
+            const double tt = dma16_time(*t, a, cus, a.batch == 1, &p, &f);
+            if (tt < t_large) { t_large = tt; best_tile = t; parts = p; first_split = f; }
+        }
+    }
     const bool small_ok = gemm::tile_variant_supports(a, kSmallTileVariant);
     double t_small = small_tile_time(a, small, 1, cus);
     int slices = 1;
@@ -156,7 +191,7 @@ TileChoice choose_tile(const Args& a, int num_cus) {
     }
     if (t_large <= t_small) {
         if (!large_ok) return TileChoice{kLargeTileFallback, 0, 1};
-        return TileChoice{kLargeTileVariant, (int)(large - tail), parts};
+        return TileChoice{best_tile->variant, (int)first_split, parts};
     }
     if (!small_ok) return TileChoice{kSmallTileFallback, 0, 1};
     return TileChoice{a.K / slices <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, slices};

@@ -87,6 +87,10 @@ struct Frag16MC {
     }
 };
 
+__device__ __forceinline__ void wait_raw8(Frag16Raw (&r)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(r[0].lo), "+v"(r[0].hi), "+v"(r[1].lo), "+v"(r[1].hi), "+v"(r[2].lo), "+v"(r[2].hi), "+v"(r[3].lo), "+v"(r[3].hi));
+}
 __device__ __forceinline__ void wait_raw8(Frag16Raw (&r)[8]) {
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+v"(r[0].lo), "+v"(r[0].hi), "+v"(r[1].lo), "+v"(r[1].hi), "+v"(r[2].lo), "+v"(r[2].hi), "+v"(r[3].lo), "+v"(r[3].hi),
@@ -119,7 +123,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
                                                            int split_first, int split_parts, float* partials, int rotate) {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NT, NS = C::NS;
     constexpr int TM = C::WTM / 16, TN = C::WTN / 16;        // 16x16 accumulators per wave
-    static_assert(TM == 8 && TN == 8, "the slot plan below is written for a 128x128 wave sub-block");
+    static_assert((TM == 8 || TM == 4) && (TN == 8 || TN == 4) && TM + TN >= 12,
+                  "the slot plan below is written for a 128x128 wave sub-block, or half of one");
     static_assert(BK == 32, "one 32-wide k block per slab");
     static_assert(NS == 4 || NS == 5, "ring of 4, or ring of 5 with paired requests");
     constexpr bool PAIRED = NS == 5;
@@ -281,8 +286,16 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     // Slot plan of a step: barrier before MFMA BAR_SLOT; fragment q of the next slab after MFMA
     // BAR_SLOT + 2q; load q after MFMA LOAD_FIRST + 4q (odd slots); the scalars of the next pair
     // of steps from slot TAIL_FIRST on.
-    constexpr int BAR_SLOT = 4, LOAD_FIRST = BAR_SLOT + 1, LOAD_EVERY = 4, TAIL_FIRST = 40;
-    static_assert(BAR_SLOT + 2 * NR <= TAIL_FIRST && LOAD_FIRST + (LPT - 1) * LOAD_EVERY < TAIL_FIRST, "reads and loads end before the tail");
+    // The scalar updates change what the loads of the step use, so they come after the last load.
+    // A half-size wave sub-block has 32 MFMAs per step: its updates go two to a slot, next to the
+    // last fragment reads (which use a copy of their stage offset taken at the start of the step).
+    constexpr int BAR_SLOT = 4, LOAD_FIRST = BAR_SLOT + 1, LOAD_EVERY = 4;
+    constexpr int LAST_LOAD = LOAD_FIRST + (LPT - 1) * LOAD_EVERY;
+    constexpr int TAIL_FIRST = NM == 64 ? 40 : LAST_LOAD + 1;
+    // slot of scalar update u (0 .. 9)
+    auto tail_slot = [](int u) { constexpr int wide[10] = {0, 2, 4, 6, 8, 9, 10, 11, 12, 13}; return TAIL_FIRST + (NM == 64 ? wide[u] : u / 2); };
+    static_assert(BAR_SLOT + 2 * NR <= NM && LAST_LOAD < TAIL_FIRST, "reads end inside the step, loads before the tail");
+    static_assert(TAIL_FIRST + (NM == 64 ? 13 : 4) < NM, "the scalar updates fit the step");
     // loads that may still be in flight when slab kt+1 must have landed
     constexpr int PENDING_EVEN = PAIRED ? 2 * LPT : (NS - 2) * LPT, PENDING_ODD = PAIRED ? LPT : (NS - 2) * LPT;
 
@@ -319,17 +332,17 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
                     else lb.issue_at(p.i, rb0, dst + C::A_BYTES, p.which ? s.sb1 : s.sb0);
                 }
                 if constexpr (!EVEN) {      // next pair of steps: everything moves on by two slabs
-                    if constexpr (m == TAIL_FIRST) s.r1 = advance2(s.r1);
-                    if constexpr (m == TAIL_FIRST + 2) s.r2 = advance2(s.r2);
-                    if constexpr (m == TAIL_FIRST + 4) s.w0 = advance2(s.w0);
-                    if constexpr (m == TAIL_FIRST + 6) s.w1 = advance2(s.w1);
-                    if constexpr (m == TAIL_FIRST + 8) { s.sa0 += (uint32_t)(2 * a_step); s.sa1 += (uint32_t)(2 * a_step); }
-                    if constexpr (m == TAIL_FIRST + 9) { s.sb0 += (uint32_t)(2 * b_step); s.sb1 += (uint32_t)(2 * b_step); }
+                    if constexpr (m == tail_slot(0)) s.r1 = advance2(s.r1);
+                    if constexpr (m == tail_slot(1)) s.r2 = advance2(s.r2);
+                    if constexpr (m == tail_slot(2)) s.w0 = advance2(s.w0);
+                    if constexpr (m == tail_slot(3)) s.w1 = advance2(s.w1);
+                    if constexpr (m == tail_slot(4)) { s.sa0 += (uint32_t)(2 * a_step); s.sa1 += (uint32_t)(2 * a_step); }
+                    if constexpr (m == tail_slot(5)) { s.sb0 += (uint32_t)(2 * b_step); s.sb1 += (uint32_t)(2 * b_step); }
                     // a rotated walk wraps around the end of the k range (never reached without rotation)
-                    if constexpr (m == TAIL_FIRST + 10) s.sa0 = s.sa0 >= span_a ? s.sa0 - span_a : s.sa0;
-                    if constexpr (m == TAIL_FIRST + 11) s.sa1 = s.sa1 >= span_a ? s.sa1 - span_a : s.sa1;
-                    if constexpr (m == TAIL_FIRST + 12) s.sb0 = s.sb0 >= span_b ? s.sb0 - span_b : s.sb0;
-                    if constexpr (m == TAIL_FIRST + 13) s.sb1 = s.sb1 >= span_b ? s.sb1 - span_b : s.sb1;
+                    if constexpr (m == tail_slot(6)) s.sa0 = s.sa0 >= span_a ? s.sa0 - span_a : s.sa0;
+                    if constexpr (m == tail_slot(7)) s.sa1 = s.sa1 >= span_a ? s.sa1 - span_a : s.sa1;
+                    if constexpr (m == tail_slot(8)) s.sb0 = s.sb0 >= span_b ? s.sb0 - span_b : s.sb0;
+                    if constexpr (m == tail_slot(9)) s.sb1 = s.sb1 >= span_b ? s.sb1 - span_b : s.sb1;
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }

@@ -112,7 +112,7 @@ def assert_close(cfg: wl.Config, got: np.ndarray, ref: np.ndarray, mag: np.ndarr
     else:
         contractual = 4e-3 * mag + 1e-5
     bad = err > contractual
-    assert not bad.any(), f"{what}: {bad.sum()} elements beyond the contractual bound; worst {err.max()} vs {contractual[err.argmax()]}"
+    assert not bad.any(), f"{what}: {bad.sum()} elements beyond the contractual bound; worst {err.max()} vs {contractual.flat[err.argmax()]}"
     diag = U_OUT[cfg.out_dtype] * np.abs(ref) + 1e-5 * mag + 1e-30
     if cfg.dtype == wl.F32:
         diag = contractual
