@@ -53,6 +53,8 @@ constexpr int kPartChoices[] = {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
 // Tile rows per band of the workgroup -> tile map: the 32 workgroups resident on an XCD then cover 4 x 8
 // tiles (8 x 4 with bands of 8 measured 0.5 % slower on 8192^3 and 8192x28672x8192, bands of 16 3 % slower).
 constexpr int kTileBandRows = 4;
+// most rows of C for which the automatic choice takes the skinny family
+constexpr int64_t kSkinnyAutoRows = 32, kSkinnyAutoBytes = (int64_t)128 << 20;
 
 // The 16x16x32 kernel with its tile halved along one side (256x128, 128x256): half the MFMAs per
 // slab and 12 instead of 16 fragment reads, so LDS rather than the matrix pipe bounds it
@@ -396,7 +398,13 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
     } else {
         // The paper's roofline rule (Section 4.3) in arithmetic form: few rows of C make the
         // call bandwidth-limited (stream B once, split K); otherwise it is a matrix-core problem.
-        if (gemm::skinny_supports(a) && batch_aligned && N >= 256 && K >= 512) {
+        // The skinny kernels are ahead where B is a long stream: up to 32 rows, B of 128 MiB or more,
+        // K >= 4096 (32x16384x16384: 94 against 99 us on the 128x256 tile with a K split,
+        // 16x28672x8192 with B stored N x K: 79 against 92).  Smaller weights run as fast or faster as
+        // sliced 128x128 tiles (32x2048x2048: 19 to 21 against 15 to 20 us, 32x256x512: 18 to 26 against
+        // 10 to 13), and with 33 to 64 rows the 128x256 tile wins everywhere (64x16384x16384: 107
+        // against 112 / 126 us, 64x28672x8192: 100 against 152 / 158).
+        if (gemm::skinny_supports(a) && batch_aligned && M <= kSkinnyAutoRows && N * K * 2 >= kSkinnyAutoBytes && K >= 4096) {
             plan = gemm_plan_t{GEMM_KERNEL_SKINNY, gemm::skinny_variant_of(a), gemm::skinny_default_split(a, h->num_cus)};
         } else if (gemm::tile_supports(a) && batch_aligned &&
                    (a.dtype != gemm::DT_F32 || ((a.M + 63) / 64) * ((a.N + 63) / 64) * a.batch >= kF32MinTiles)) {

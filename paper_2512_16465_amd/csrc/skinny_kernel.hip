@@ -533,15 +533,28 @@ int skinny_max_split(const Args& a) {
 }
 
 int skinny_default_split(const Args& a, int num_cus) {
-    const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS;
-    int64_t s = (num_cus + groups - 1) / groups;          // about one workgroup per compute unit
+    const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS, cus = num_cus > 0 ? num_cus : 256;
     // keep the pipeline of every wave filled a few times over (row-major B: the waves of a
     // workgroup share its k range; B stored N x K: every wave walks all of it, four visits per chunk)
-    const int64_t max_s = a.transB ? skinny_k_units(a) / 4 : skinny_k_units(a) / (SK_WAVES * 2 * SK_DEPTH);
-    if (s > max_s) s = max_s;
-    if (s > 64) s = 64;
-    if (s < 1) s = 1;
-    return (int)s;
+    int64_t max_s = a.transB ? skinny_k_units(a) / 4 : skinny_k_units(a) / (SK_WAVES * 2 * SK_DEPTH);
+    if (max_s > 64) max_s = 64;
+    if (max_s < 1) max_s = 1;
+    // One workgroup per compute unit is resident; groups x slices workgroups run in whole rounds
+    // of them, and a partly filled round streams at a fraction of the memory rate.  Time in us:
+    // B at 6.1 TB/s stretched by the unfilled part of the rounds, 5 us per round for filling and
+    // draining a workgroup's pipelines, plus the second kernel (launch + the partial sums written
+    // and read once at 4.5 TB/s).  28672 columns = 112 groups: 2 slices fill 224 of 256 units in
+    // one round (32x28672x8192: 91 to 93 us); "one workgroup per unit" rounded up gave 3 slices =
+    // two rounds at 66 % (113 to 117 us), and 9 slices fill four rounds but pay for them (101 to 104).
+    const double stream = (double)a.N * (double)a.K * 2.0 / 6.1e6, part = (double)a.M * (double)a.N * 8.0 / 4.5e6;
+    int64_t best = 1;
+    double best_t = 0.0;
+    for (int64_t s = 1; s <= max_s; ++s) {
+        const int64_t wgs = groups * s, rounds = (wgs + cus - 1) / cus;
+        const double t = stream * (double)(rounds * cus) / (double)wgs + 5.0 * (double)rounds + (s > 1 ? 3.0 + part * (double)s : 0.0);
+        if (s == 1 || t < best_t) { best_t = t; best = s; }
+    }
+    return (int)best;
 }
 
 size_t skinny_workspace_bytes(const Args& a, int split_k) {

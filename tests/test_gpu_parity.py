@@ -390,10 +390,25 @@ def test_skinny_fp16_gelu(handle):
     cfg = base_cfg(8, 512, 1024, 0, 0, wl.F16, wl.F16, a_dist=("normal", 1.0), b_dist=("normal", 0.05),
                    bias_dist=("normal", 0.5), bias_dtype=wl.F16, act=wl.ACT_GELU_ERF)
     inp = wl.make_inputs(cfg, 3)
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, -1, 0)      # a weight this small goes to the tile family by itself
     p = DeviceProblem(cfg, inp)
     p.run(handle)
     assert lg.gemm_get_last_plan(handle)[0] == lg.GEMM_KERNEL_SKINNY
+    lg.gemm_set_plan(handle)
     check_full(cfg, inp, p.result_bits(), "skinny fp16 gelu")
+
+
+@pytest.mark.parametrize("M,N,K,tb", [(8, 512, 1024, 0), (24, 512, 1024, 1), (32, 2048, 2048, 1), (40, 768, 2048, 1), (64, 1024, 4096, 0)])
+def test_few_rows_small_weight_automatic_choice(handle, M, N, K, tb):
+    # the streaming kernels are for weights of 128 MiB and more; below that, and above 32 rows, the call goes
+    # to the tile family (sliced along K where that fills the chip).  Integer data -> exact.
+    cfg = base_cfg(M, N, K, 0, tb, wl.BF16, wl.BF16, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.F32)
+    inp, _ = wl.make_integer_inputs(cfg, 86, -2, 2)
+    want = oracle.decode(wl.BF16, expected_bits_exact(cfg, inp))
+    p = DeviceProblem(cfg, inp)
+    p.run(handle)
+    assert lg.gemm_get_last_plan(handle)[0] == lg.GEMM_KERNEL_MFMA_TILE
+    assert np.array_equal(decode_c(cfg, p.result_bits()), want)
 
 
 # ------------------------------------------------------------------ every activation through every kernel family
@@ -417,8 +432,11 @@ def test_activations_in_every_kernel_family(handle, act):
     ]
     for name, cfg, family in cases:
         inp = wl.make_inputs(cfg, 40 + act)
+        if family == lg.GEMM_KERNEL_SKINNY:
+            lg.gemm_set_plan(handle, family, -1, 0)      # small weights: forced, the automatic choice is the tile family
         p = DeviceProblem(cfg, inp)
         p.run(handle)
+        lg.gemm_set_plan(handle)
         assert lg.gemm_get_last_plan(handle)[0] == family, name
         check_full(cfg, inp, p.result_bits(), f"{name} act {act}")
 
@@ -599,7 +617,10 @@ def test_batched_integer_exact_in_every_family(handle):
     for name, cfg, batch, family in cases:
         print(f"batched integer {name}", flush=True)
         p = BatchedDeviceProblem(cfg, batch, cfg.stride_a(), cfg.stride_b(), cfg.stride_c() + 8, seed=80, integer=True)
+        if family == lg.GEMM_KERNEL_SKINNY:
+            lg.gemm_set_plan(handle, family, -1, 0)
         p.run(handle)
+        lg.gemm_set_plan(handle)
         assert lg.gemm_get_last_plan(handle)[0] == family, name
         p.check(f"batched integer {name}", exact=True)
 
