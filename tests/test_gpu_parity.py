@@ -111,6 +111,29 @@ def test_tile_variants_every_small_slab_count(handle, ta, tb):
     lg.gemm_set_plan(handle)
 
 
+@pytest.mark.parametrize("ta,tb", [(0, 1), (1, 0)])
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F16])
+def test_whole_tiles_without_epilogue_terms(handle, ta, tb, dtype):
+    # C = alpha * A * B on whole tiles (beta = 0, no bias, no activation): the direct-to-LDS kernels with the
+    # 32x32x16 MFMA then store straight from the accumulator layout, 16-bit results two to a 32-bit word after
+    # a trade between neighbouring lanes.  Integer data -> every element exact, in each output type; a C whose
+    # rows start on odd elements takes the staged epilogue instead and must agree.
+    M, N, K = 512, 768, 200
+    for out in (dtype, wl.F32):
+        for ldc in (N, N + 6, N + 3):
+            cfg = base_cfg(M, N, K, ta, tb, dtype, out, alpha=-3.0, ldc=ldc)
+            inp, _ = wl.make_integer_inputs(cfg, 87, -3, 3)
+            want = oracle.decode(out, expected_bits_exact(cfg, inp))
+            for v in tile_variants():
+                print(f"whole tiles variant {v} ta={ta} tb={tb} dtype={dtype} out={out} ldc={ldc}", flush=True)
+                lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, v)
+                p = DeviceProblem(cfg, inp)
+                p.run(handle)
+                got = decode_c(cfg, p.result_bits())
+                assert np.array_equal(got, want), f"variant {v}: {np.sum(got != want)} wrong elements"
+    lg.gemm_set_plan(handle)
+
+
 @pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0), (1, 1), (1, 0)])
 def test_tile_split_of_the_trailing_round(handle, ta, tb):
     # nine 256x256 tiles, fewer than compute units: a forced split cuts every tile's k range into shares
