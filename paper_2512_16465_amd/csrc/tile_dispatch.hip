@@ -74,7 +74,10 @@ hipError_t launch_tile(const Args& a, int variant, int group_m, const TileSplit&
 namespace {
 
 // Adds the partial tiles of a split in the order of their k shares and applies the epilogue:
-// one thread per four consecutive columns of a tile row.
+// one thread per four consecutive columns of a tile row.  The kernel is one round trip to memory
+// long, so the loads of all shares (P > 0: their number is fixed at compile time; P == 0: any
+// number, four at a time) and of C_in and bias are issued before the first use.
+template <int P>
 __global__ __launch_bounds__(256) void tile_split_reduce_kernel(Args a, int tiles_m, int tiles_n, int group_m, int first_tile,
                                                                 int parts, const float* partials, int BM, int BN) {
     int tm, tn;
@@ -83,16 +86,43 @@ __global__ __launch_bounds__(256) void tile_split_reduce_kernel(Args a, int tile
     const int r = idx / (BN / 4), c = (idx % (BN / 4)) * 4;
     const int64_t row = (int64_t)tm * BM + r, col = (int64_t)tn * BN + c;
     if (row >= a.M || col >= a.N) return;
-    const float* p = partials + ((size_t)blockIdx.x * parts) * BM * BN + (size_t)r * BN + c;
-    f32x4 s = *(const f32x4*)p;
-    for (int q = 1; q < parts; ++q) s += *(const f32x4*)(p + (size_t)q * BM * BN);
+    const size_t tile_floats = (size_t)BM * BN;
+    const float* p = partials + ((size_t)blockIdx.x * parts) * tile_floats + (size_t)r * BN + c;
+    float c_in[4] = {0.0f, 0.0f, 0.0f, 0.0f}, bj[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    auto load_inputs = [&]() {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (col + e >= a.N) break;
+            if (a.beta != 0.0f) c_in[e] = load_elem(a.C, a.out_dtype, row * a.ldc + col + e);
+            if (a.bias) bj[e] = load_elem(a.bias, a.bias_dtype, col + e);
+        }
+    };
+    f32x4 s;
+    if constexpr (P > 0) {
+        f32x4 v[P];
+#pragma unroll
+        for (int q = 0; q < P; ++q) v[q] = *(const f32x4*)(p + (size_t)q * tile_floats);
+        load_inputs();
+        s = v[0];
+#pragma unroll
+        for (int q = 1; q < P; ++q) s += v[q];
+    } else {
+        load_inputs();
+        s = *(const f32x4*)p;
+        int q = 1;
+        for (; q + 4 <= parts; q += 4) {
+            f32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = *(const f32x4*)(p + (size_t)(q + u) * tile_floats);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s += v[u];
+        }
+        for (; q < parts; ++q) s += *(const f32x4*)(p + (size_t)q * tile_floats);
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         if (col + e >= a.N) break;
-        const int64_t ci = row * a.ldc + col + e;
-        const float c_in = a.beta != 0.0f ? load_elem(a.C, a.out_dtype, ci) : 0.0f;
-        const float bj = a.bias ? load_elem(a.bias, a.bias_dtype, col + e) : 0.0f;
-        store_elem(a.C, a.out_dtype, ci, epilogue_value(s[e], a.alpha, a.beta, c_in, bj, a.act));
+        store_elem(a.C, a.out_dtype, row * a.ldc + col + e, epilogue_value(s[e], a.alpha, a.beta, c_in[e], bj[e], a.act));
     }
 }
 
@@ -104,8 +134,20 @@ hipError_t launch_tile_split_reduce(const Args& a, int variant, int group_m, con
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const int tail = tiles_m * tiles_n - split.first_tile;
     if (tail <= 0) return hipSuccess;
-    hipLaunchKernelGGL(tile_split_reduce_kernel, dim3((unsigned)tail, (unsigned)(BM * BN / 4 / 256)), dim3(256), 0, stream, a,
-                       tiles_m, tiles_n, group_m < 1 ? 1 : group_m, split.first_tile, split.parts, (const float*)split.partials, BM, BN);
+    const dim3 grid((unsigned)tail, (unsigned)(BM * BN / 4 / 256)), block(256);
+    const int gm = group_m < 1 ? 1 : group_m;
+#define GEMM_REDUCE_LAUNCH(P)                                                                                       \
+    hipLaunchKernelGGL(tile_split_reduce_kernel<P>, grid, block, 0, stream, a, tiles_m, tiles_n, gm, split.first_tile, \
+                       split.parts, (const float*)split.partials, BM, BN)
+    switch (split.parts) {
+        case 2: GEMM_REDUCE_LAUNCH(2); break;
+        case 3: GEMM_REDUCE_LAUNCH(3); break;
+        case 4: GEMM_REDUCE_LAUNCH(4); break;
+        case 6: GEMM_REDUCE_LAUNCH(6); break;
+        case 8: GEMM_REDUCE_LAUNCH(8); break;
+        default: GEMM_REDUCE_LAUNCH(0); break;
+    }
+#undef GEMM_REDUCE_LAUNCH
     return hipGetLastError();
 }
 
