@@ -178,7 +178,9 @@ typedef struct {
  * GEMM_ERR_UNSUPPORTED.  Errors: GEMM_ERR_INVALID_ARG for a null handle or out-of-range fields. */
 gemm_status_t gemm_set_plan(gemm_handle_t h, const gemm_plan_t* plan);
 
-/* Reports the plan the most recent successful gemm_run on this handle used.
+/* Reports the plan the most recent successful gemm_run on this handle used.  (An automatic plan may
+ * run a C with a thin last strip of columns or rows as two products, the whole tiles and the strip;
+ * the plan of the whole tiles is the one reported.)
  * Errors: GEMM_ERR_INVALID_ARG for null arguments. */
 gemm_status_t gemm_get_last_plan(gemm_handle_t h, gemm_plan_t* out);
 

@@ -142,7 +142,7 @@ double small_tile_time(const Args& a, int64_t tiles, int slices, int64_t cus) {
     return t;
 }
 
-struct TileChoice { int variant; int first_split_tile; int parts; };
+struct TileChoice { int variant; int first_split_tile; int parts; double time; };   // time: the estimate behind the choice, us (0: none)
 // fp32: the 128x128 or the 64x64 tile, whichever leaves the busiest compute unit less to do (see
 // choose_tile).  The small tile is at least as fast as the general kernel down to a single tile
 // (256^3: 9.0 against 10.2 us, 64^3: 5.8 against 5.9), so every aligned fp32 call takes a tile kernel.
@@ -159,7 +159,7 @@ TileChoice choose_tile(const Args& a, int num_cus) {
         const int64_t n128 = (((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch + cus - 1) / cus;
         const int64_t n64 = (((a.M + 63) / 64) * ((a.N + 63) / 64) * a.batch + cus - 1) / cus;
         const double t128 = (double)n128 * 3.88 * (n128 < 2 ? 1.2 : 1.0), t64 = (double)n64 * (n64 < 4 ? 1.1 : 1.0);
-        return TileChoice{t128 <= t64 ? kF32TileVariant : kF32SmallTileVariant, 0, 1};
+        return TileChoice{t128 <= t64 ? kF32TileVariant : kF32SmallTileVariant, 0, 1, 0.0};
     }
     // a batch multiplies the number of workgroups; its trailing round is never split along K
     const int64_t small = ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
@@ -192,11 +192,11 @@ TileChoice choose_tile(const Args& a, int num_cus) {
         }
     }
     if (t_large <= t_small) {
-        if (!large_ok) return TileChoice{kLargeTileFallback, 0, 1};
-        return TileChoice{best_tile->variant, (int)first_split, parts};
+        if (!large_ok) return TileChoice{kLargeTileFallback, 0, 1, 0.0};
+        return TileChoice{best_tile->variant, (int)first_split, parts, t_large};
     }
-    if (!small_ok) return TileChoice{kSmallTileFallback, 0, 1};
-    return TileChoice{a.K / slices <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, slices};
+    if (!small_ok) return TileChoice{kSmallTileFallback, 0, 1, 0.0};
+    return TileChoice{a.K / slices <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, slices, t_small};
 }
 
 gemm_status_t ensure_workspace(gemm_handle_s* h, size_t bytes, hipStream_t stream) {
@@ -295,6 +295,113 @@ GEMM_EXPORT const char* gemm_variant_name(gemm_kernel_t kernel, int32_t variant)
 }
 
 namespace {
+
+// Launches the kernels of a plan for the (validated) call `a`; may lower plan.split_k to what the
+// call can take.  split_first: first tile of a split trailing round (macro-tile family).
+// allocate_only: stop after making the workspace large enough for the plan.
+gemm_status_t launch_plan(gemm_handle_s* h, const Args& a, gemm_plan_t& plan, int split_first, hipStream_t stream,
+                          bool allocate_only = false) {
+    const int64_t M = a.M, N = a.N, K = a.K, batch = a.batch;
+    const int64_t in_bytes = gemm::elem_bytes(a.dtype);
+    hipError_t e = hipSuccess;
+    if (plan.kernel == GEMM_KERNEL_SKINNY) {
+        const int max_split = gemm::skinny_max_split(a);
+        if (plan.split_k > max_split) plan.split_k = max_split;
+        const size_t need = gemm::skinny_workspace_bytes(a, plan.split_k);
+        if (need) {
+            const gemm_status_t st = ensure_workspace(h, need, stream);
+            if (st != GEMM_OK) return st;
+        }
+        // one matrix per launch (the slices of a split share the workspace, in stream order)
+        Args one = a;
+        one.batch = 1;
+        for (int64_t b = 0; b < batch && e == hipSuccess && !allocate_only; ++b) {
+            one.A = (const char*)a.A + b * a.strideA * in_bytes;
+            one.B = (const char*)a.B + b * a.strideB * in_bytes;
+            one.C = (char*)a.C + b * a.strideC * gemm::elem_bytes(a.out_dtype);
+            e = gemm::launch_skinny(one, plan.split_k, h->workspace, stream);
+        }
+    } else if (plan.kernel == GEMM_KERNEL_MFMA_TILE) {
+        gemm::TileSplit split{0, 1, nullptr};
+        if (plan.split_k > 1) {
+            const int64_t slabs = (K + 31) / 32;
+            if (plan.split_k > slabs) plan.split_k = (int)slabs;
+        }
+        int64_t slice_len = 0;
+        if (plan.split_k > 1 && !gemm::tile_variant_splits(plan.variant)) {
+            // k slices: ranges of whole 32-element slabs, all of one length but the last
+            const int64_t slabs = (K + 31) / 32;
+            slice_len = ((slabs + plan.split_k - 1) / plan.split_k) * 32;
+            plan.split_k = (int)((K + slice_len - 1) / slice_len);
+        }
+        if (plan.split_k > 1 && slice_len > 0) {
+            const int64_t len = slice_len;
+            const gemm_status_t st = ensure_workspace(h, (size_t)plan.split_k * (size_t)M * (size_t)N * sizeof(float), stream);
+            if (st != GEMM_OK) return st;
+            Args p = a;
+            p.K = len; p.k_total = K;
+            p.batch = plan.split_k;
+            p.strideA = a.transA ? len * a.lda : len;
+            p.strideB = a.transB ? len : len * a.ldb;
+            p.C = h->workspace; p.ldc = N; p.strideC = M * N;
+            p.out_dtype = gemm::DT_F32; p.alpha = 1.0f; p.beta = 0.0f; p.bias = nullptr; p.act = gemm::ACT_NONE;
+            if (!allocate_only) e = gemm::launch_tile(p, plan.variant, kTileBandRows, split, stream);
+            if (!allocate_only && e == hipSuccess) e = gemm::launch_splitk_reduce(a, plan.split_k, h->workspace, stream);
+        } else if (plan.split_k > 1) {
+            const gemm::TileVariantInfo* info = gemm::tile_variant_info(plan.variant);
+            const int64_t tiles = ((a.M + info->BM - 1) / info->BM) * ((a.N + info->BN - 1) / info->BN);
+            const size_t need = (size_t)(tiles - split_first) * plan.split_k * info->BM * info->BN * sizeof(float);
+            const gemm_status_t st = ensure_workspace(h, need, stream);
+            if (st != GEMM_OK) return st;
+            split = gemm::TileSplit{split_first, plan.split_k, h->workspace};
+            if (!allocate_only) e = gemm::launch_tile(a, plan.variant, kTileBandRows, split, stream);
+            if (!allocate_only && e == hipSuccess) e = gemm::launch_tile_split_reduce(a, plan.variant, kTileBandRows, split, stream);
+        } else if (!allocate_only) {
+            e = gemm::launch_tile(a, plan.variant, kTileBandRows, split, stream);
+        }
+    } else if (!allocate_only) {
+        e = gemm::launch_general(a, stream);
+    }
+    return e == hipSuccess ? GEMM_OK : GEMM_ERR_HIP;
+}
+
+// Remainder peeling.  A C whose last column (or row) of 256-wide tiles is nearly empty pays a whole
+// tile's k loop for a few columns there, and that column of tiles can cost a round of its own
+// (8000x8200x8136: 33 tile columns for 8 columns of C, 1056 tiles = four rounds and 32 tiles).  The
+// call is then made in two: the whole tiles, and the remaining thin strip as a call of its own, which
+// the choice above sends to small tiles cut along K.  Taken when the two estimates together are 5 %
+// below the estimate for the whole; a strip is at most 64 wide.  `rest` starts where `main_part` ends.
+constexpr int64_t kPeelWidest = 64;
+constexpr double kPeelGain = 0.95, kSecondLaunch = 3.0;
+
+bool peel_remainder(const Args& a, int num_cus, double whole_time, Args* main_part, Args* rest, TileChoice* main_choice,
+                    TileChoice* rest_choice) {
+    if (a.batch != 1 || whole_time <= 0.0) return false;
+    const int64_t in_bytes = gemm::elem_bytes(a.dtype), out_bytes = gemm::elem_bytes(a.out_dtype);
+    bool found = false;
+    double best = kPeelGain * whole_time;
+    for (int side = 0; side < 2; ++side) {                  // 0: columns, 1: rows
+        const int64_t extent = side == 0 ? a.N : a.M, whole = (extent / 256) * 256, strip = extent - whole;
+        if (whole < 256 || strip <= 0 || strip > kPeelWidest) continue;
+        Args m = a, r = a;
+        if (side == 0) {
+            m.N = whole; r.N = strip;
+            r.B = (const char*)a.B + (a.transB ? whole * a.ldb : whole) * in_bytes;
+            r.C = (char*)a.C + whole * out_bytes;
+            if (a.bias) r.bias = (const char*)a.bias + whole * gemm::elem_bytes(a.bias_dtype);
+        } else {
+            m.M = whole; r.M = strip;
+            r.A = (const char*)a.A + (a.transA ? whole : whole * a.lda) * in_bytes;
+            r.C = (char*)a.C + whole * a.ldc * out_bytes;
+        }
+        if (!gemm::tile_supports(m) || !gemm::tile_supports(r)) continue;
+        const TileChoice cm = choose_tile(m, num_cus), cr = choose_tile(r, num_cus);
+        if (cm.time <= 0.0 || cr.time <= 0.0) continue;
+        const double t = cm.time + cr.time + kSecondLaunch;
+        if (t < best) { best = t; found = true; *main_part = m; *rest = r; *main_choice = cm; *rest_choice = cr; }
+    }
+    return found;
+}
 
 // Largest number of matrices one launch takes (the y dimension of a grid).
 constexpr int64_t kMaxBatchPerLaunch = 65535;
@@ -411,70 +518,26 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
             const TileChoice c = choose_tile(a, h->num_cus);
             plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, c.variant, c.parts};
             split_first = c.first_split_tile;
+            Args main_part, rest;
+            TileChoice cm, cr;
+            if (peel_remainder(a, h->num_cus, c.time, &main_part, &rest, &cm, &cr)) {
+                gemm_plan_t pm{GEMM_KERNEL_MFMA_TILE, cm.variant, cm.parts}, pr{GEMM_KERNEL_MFMA_TILE, cr.variant, cr.parts};
+                // the workspace of both parts first: a failed allocation must leave C untouched
+                gemm_status_t st = launch_plan(h, main_part, pm, cm.first_split_tile, stream, true);
+                if (st == GEMM_OK) st = launch_plan(h, rest, pr, cr.first_split_tile, stream, true);
+                if (st != GEMM_OK) return st;
+                st = launch_plan(h, main_part, pm, cm.first_split_tile, stream);
+                if (st == GEMM_OK) st = launch_plan(h, rest, pr, cr.first_split_tile, stream);
+                if (st != GEMM_OK) return st;
+                h->last = pm;         // the plan of the whole tiles
+                return GEMM_OK;
+            }
         }
     }
 
     // ---- launch ----
-    hipError_t e = hipSuccess;
-    if (plan.kernel == GEMM_KERNEL_SKINNY) {
-        const int max_split = gemm::skinny_max_split(a);
-        if (plan.split_k > max_split) plan.split_k = max_split;
-        const size_t need = gemm::skinny_workspace_bytes(a, plan.split_k);
-        if (need) {
-            const gemm_status_t st = ensure_workspace(h, need, stream);
-            if (st != GEMM_OK) return st;
-        }
-        // one matrix per launch (the slices of a split share the workspace, in stream order)
-        Args one = a;
-        one.batch = 1;
-        for (int64_t b = 0; b < batch && e == hipSuccess; ++b) {
-            one.A = (const char*)a.A + b * a.strideA * in_bytes;
-            one.B = (const char*)a.B + b * a.strideB * in_bytes;
-            one.C = (char*)a.C + b * a.strideC * gemm::elem_bytes(a.out_dtype);
-            e = gemm::launch_skinny(one, plan.split_k, h->workspace, stream);
-        }
-    } else if (plan.kernel == GEMM_KERNEL_MFMA_TILE) {
-        gemm::TileSplit split{0, 1, nullptr};
-        if (plan.split_k > 1) {
-            const int64_t slabs = (K + 31) / 32;
-            if (plan.split_k > slabs) plan.split_k = (int)slabs;
-        }
-        int64_t slice_len = 0;
-        if (plan.split_k > 1 && !gemm::tile_variant_splits(plan.variant)) {
-            // k slices: ranges of whole 32-element slabs, all of one length but the last
-            const int64_t slabs = (K + 31) / 32;
-            slice_len = ((slabs + plan.split_k - 1) / plan.split_k) * 32;
-            plan.split_k = (int)((K + slice_len - 1) / slice_len);
-        }
-        if (plan.split_k > 1 && slice_len > 0) {
-            const int64_t len = slice_len;
-            const gemm_status_t st = ensure_workspace(h, (size_t)plan.split_k * (size_t)M * (size_t)N * sizeof(float), stream);
-            if (st != GEMM_OK) return st;
-            Args p = a;
-            p.K = len; p.k_total = K;
-            p.batch = plan.split_k;
-            p.strideA = a.transA ? len * a.lda : len;
-            p.strideB = a.transB ? len : len * a.ldb;
-            p.C = h->workspace; p.ldc = N; p.strideC = M * N;
-            p.out_dtype = gemm::DT_F32; p.alpha = 1.0f; p.beta = 0.0f; p.bias = nullptr; p.act = gemm::ACT_NONE;
-            e = gemm::launch_tile(p, plan.variant, kTileBandRows, split, stream);
-            if (e == hipSuccess) e = gemm::launch_splitk_reduce(a, plan.split_k, h->workspace, stream);
-        } else if (plan.split_k > 1) {
-            const gemm::TileVariantInfo* info = gemm::tile_variant_info(plan.variant);
-            const int64_t tiles = ((a.M + info->BM - 1) / info->BM) * ((a.N + info->BN - 1) / info->BN);
-            const size_t need = (size_t)(tiles - split_first) * plan.split_k * info->BM * info->BN * sizeof(float);
-            const gemm_status_t st = ensure_workspace(h, need, stream);
-            if (st != GEMM_OK) return st;
-            split = gemm::TileSplit{split_first, plan.split_k, h->workspace};
-            e = gemm::launch_tile(a, plan.variant, kTileBandRows, split, stream);
-            if (e == hipSuccess) e = gemm::launch_tile_split_reduce(a, plan.variant, kTileBandRows, split, stream);
-        } else {
-            e = gemm::launch_tile(a, plan.variant, kTileBandRows, split, stream);
-        }
-    } else {
-        e = gemm::launch_general(a, stream);
-    }
-    if (e != hipSuccess) return GEMM_ERR_HIP;
+    const gemm_status_t st = launch_plan(h, a, plan, split_first, stream);
+    if (st != GEMM_OK) return st;
     h->last = plan;
     return GEMM_OK;
 }

@@ -159,6 +159,13 @@ EXTRA_CONFIGS: Dict[str, Config] = {
     "X8": Config("X8", 2048, 2048, 128, 0, 1, BF16, BF16, batch=32,
                  a_dist=("normal", 1.0), b_dist=("normal", 128 ** -0.5),
                  note="bf16 strided batch of 32 products 2048x2048x128 NT (the per-head score products of attention), bf16 out"),
+    "X9": Config("X9", 4096, 4104, 4096, 0, 0, BF16, BF16, alpha=1.0, beta=1.0,
+                 a_dist=("normal", 1.0), b_dist=("normal", 4096 ** -0.5), c_dist=("normal", 1.0),
+                 bias_dist=("normal", 0.5), bias_dtype=BF16, act=ACT_RELU,
+                 note="bf16 4096x4104x4096 NN + C + bias + ReLU: 16 whole tile columns and a strip of 8 columns"),
+    "X10": Config("X10", 4120, 4096, 4096, 1, 1, F16, F32,
+                  a_dist=("normal", 1.0), b_dist=("normal", 4096 ** -0.5),
+                  note="fp16 4120x4096x4096 TT, fp32 out: 16 whole tile rows and a strip of 24 rows"),
 }
 
 
