@@ -36,9 +36,10 @@ bool valid_dtype(int d) { return d == GEMM_F32 || d == GEMM_F16 || d == GEMM_BF1
 // a fixed 2 GiB - 16 offset).
 constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant = 5, kSmallTileFallback = 3;
 // short k loops: the small tile with a ring of three stages (48 KiB of LDS: three workgroups per
-// compute unit instead of two; 3 to 15 % faster for K <= 512, slower beyond)
+// compute unit instead of two; faster up to K = 256 - 8192x8192x256: 53 against 63 us - slower from
+// K = 512 on: 4096x4096x512 27 against 25, 256x4096x512 7.4 against 6.7; slices take the ring of four)
 constexpr int kSmallTileShortK = 12;
-constexpr int64_t kShortK = 512;
+constexpr int64_t kShortK = 256;
 constexpr double kSmallPerK = 0.0094, kSmallFixed = 1.4;     // (the large tile's 0.0209 us per k and 15 us fixed: kFullTile below)
 // A last round that fills less than this fraction of the compute units is split along K (when the
 // variant can): each of its tiles goes to several workgroups, each over a share of the k slabs of
@@ -47,7 +48,7 @@ constexpr double kSmallPerK = 0.0094, kSmallFixed = 1.4;     // (the large tile'
 // 256 KiB (0.2 us each, write and read) and adds them one after the other (0.3 us per part).
 // Measured: 512x512x65536 (4 tiles) 89 / 67 / 86 us with 16 / 32 / 64 parts, 256x256x131072
 // (1 tile) 147 / 94 / 78 us, 1024x1024x16384 (16 tiles) 67 us with 16 parts.
-constexpr double kSplitBelow = 0.6, kReducePerPartTile = 0.2, kReducePerPart = 0.3, kReduceLaunch = 3.0;
+constexpr double kSplitBelow = 0.6, kReducePerPartTile = 0.1, kReducePerPart = 0.3, kReduceLaunch = 3.0;
 constexpr int kMinSlabsPerPart = 16;
 constexpr int kPartChoices[] = {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
 // Tile rows per band of the workgroup -> tile map: the 32 workgroups resident on an XCD then cover 4 x 8
@@ -65,6 +66,7 @@ struct Dma16Tile { int variant; int bm, bn; double per_k, fixed, hbm_rate; };
 constexpr Dma16Tile kFullTile{10, 256, 256, 0.0209, 15.0, 4.4e6};
 constexpr Dma16Tile kTallTile{14, 256, 128, 0.0117, 10.0, 5.8e6};
 constexpr Dma16Tile kWideTile{15, 128, 256, 0.0117, 10.0, 5.8e6};
+constexpr double kHalfTileMargin = 0.9, kUnfavouredHalfTile = 1.15;
 
 // time of the k loops of a round whose tiles are cut in `parts`, plus the second kernel (us)
 double split_round_time(const Dma16Tile& t, int64_t tail, int parts, int64_t K) {
@@ -98,7 +100,8 @@ double dma16_time(const Dma16Tile& t, const Args& a, int64_t cus, bool may_split
     if (tail) time += split_round_time(t, tail, parts, a.K) + t.fixed;
     // operands that stream from HBM: not faster than this tile pulls them
     const double bytes = (double)(a.M + a.N) * (double)a.K * 2.0 * (double)a.batch;
-    if (bytes > (double)((int64_t)256 << 20) && bytes / t.hbm_rate + t.fixed > time) time = bytes / t.hbm_rate + t.fixed;
+    // (a thousandth of the unbounded estimate on top, so that of two tiles at the same bound the one with less to do wins)
+    if (bytes > (double)((int64_t)256 << 20) && bytes / t.hbm_rate + t.fixed > time) time = bytes / t.hbm_rate + t.fixed + 1e-3 * time;
     *parts_out = parts;
     *first_split = tiles - tail;
     return time;
@@ -109,15 +112,17 @@ double dma16_time(const Dma16Tile& t, const Args& a, int64_t cus, bool may_split
 // kernel of the skinny family).  Time of the small tile with `slices` (1 = none), us.  A workgroup
 // that has its compute unit to itself walks k at a rate set by where its operands come from:
 // 0.0055 us per k for a handful of workgroups out of the L2 (512x512x4096: 23 us), 0.008 with 64
-// or more (1024x1024x4096: 31 us, 512x8192x8192: 72), 0.0122 when the operands exceed the
+// (1024x1024x4096: 31 us), 0.0093 with one on every unit (1024x4096x14336: 134 us), 0.0122 when the operands exceed the
 // last-level cache and come from HBM (128 ... 256 x 16384 x 16384: 186 to 200 us) - its ring keeps
 // 48 KiB in flight against the large tile's 128 KiB.  Two workgroups per unit: kSmallPerK per round.
 // The whole call is not faster than HBM delivers (4.7 TB/s reached by the sliced small tile).
 // Slices add the second kernel: launch + the partial results written and read once.
-constexpr double kSmallAloneFew = 0.0055, kSmallAloneMany = 0.008, kSmallAloneHbm = 0.0122;
+constexpr double kSmallAloneFew = 0.0055, kSmallAloneMany = 0.008, kSmallAloneAll = 0.0093, kSmallAloneHbm = 0.0122;
 constexpr double kSmallHbmRate = 4.7e6, kSliceMoveRate = 4.5e6;      // bytes per us
 constexpr int kSliceChoices[] = {2, 4, 8, 16};
-constexpr int64_t kMinSliceK = 256;
+constexpr int64_t kMinSliceK = 512;          // shorter k ranges spend their time filling the pipeline (256x512x4096: 8 slices 12 us, 16 slices 15)
+constexpr double kSliceMargin = 0.9;          // slices must promise 10 % (384x2048x2048: 14 us whole, 18 in 4 slices, estimated equal)
+constexpr double kSliceLaunch = 5.0;          // the second kernel of a sliced call: launch, gap, one round trip (512x2048x2048: 14 us whole, 19 in 4 slices)
 // Operands beyond the last-level cache stream from HBM on every call; there the large tile with its split
 // stays ahead of the sliced small tile (128x16384x16384: 114 against 125 us, 128x8192x28672: 104
 // against 119), so slices are considered only below this size (96...256 x 8192 x 8192, 134 to 138 MB:
@@ -131,14 +136,14 @@ double small_tile_time(const Args& a, int64_t tiles, int slices, int64_t cus) {
     const bool hbm = bytes > (double)kLastLevelCacheBytes;
     double loop;
     if (wgs <= cus) {
-        const double crowd = wgs >= 64 ? 1.0 : (double)wgs / 64.0;
-        loop = (hbm ? kSmallAloneHbm : kSmallAloneFew + (kSmallAloneMany - kSmallAloneFew) * crowd) * k;
+        const double crowd = wgs >= 64 ? 1.0 : (double)wgs / 64.0, full = wgs <= 64 ? 0.0 : (double)(wgs - 64) / (double)(cus - 64);
+        loop = (hbm ? kSmallAloneHbm : kSmallAloneFew + (kSmallAloneMany - kSmallAloneFew) * crowd + (kSmallAloneAll - kSmallAloneMany) * full) * k;
     } else {
         loop = (double)rounds * kSmallPerK * k;
     }
     if (hbm && bytes / kSmallHbmRate > loop) loop = bytes / kSmallHbmRate;
     double t = loop + (double)rounds * kSmallFixed;
-    if (slices > 1) t += kReduceLaunch + (double)slices * (double)(a.M * a.N) * 8.0 / kSliceMoveRate;
+    if (slices > 1) t += kSliceLaunch + (double)slices * (double)(a.M * a.N) * 8.0 / kSliceMoveRate;
     return t;
 }
 
@@ -169,26 +174,36 @@ TileChoice choose_tile(const Args& a, int num_cus) {
     int64_t first_split = 0;
     double t_large = dma16_time(kFullTile, a, cus, large_ok && a.batch == 1, &parts, &first_split);
     if (large_ok) {
-        // a half tile where every full tile would be at least half empty (N <= 128 or M <= 128); with more
-        // rows or columns of tiles only the last one gains, and the estimates are not sharp enough to
-        // pick that up (4096x4224x4096: 131 us on the full tile, 145 to 170 on 256x128)
-        for (const Dma16Tile* t : {&kTallTile, &kWideTile}) {
+        // A half tile (a) where every full tile would be at least half empty (N <= 128 or M <= 128), or
+        // (b) where it fills the chip better than the full tile does - 2048x4096x4096 is 128 full tiles
+        // but 256 tiles of 256x128: 56 us against 80 on 128x128 tiles; 1024x8192x8192: 103 against 122 -
+        // for operands inside the last-level cache and by a margin of 10 %: the estimates are not
+        // sharper than that (4096x4224x4096: 131 us on the full tile, 145 to 170 on 256x128, estimated
+        // 151 and 141), and from HBM the full tile with its split stays ahead (640x16384x16384: 319
+        // against 369 to 388).
+        const double t_full = t_large;
+        const bool in_cache = (a.M + a.N) * a.K * 2 * a.batch <= kLastLevelCacheBytes;
+        // On equal tile counts the half tile whose long side lies along the longer side of C is ahead
+        // (1024x512x65536: 256x128 69 us, 128x256 101; 512x512x65536: 63 and 47; 1024x1024x32768: 82 and 72).
+        const Dma16Tile* favoured = a.M > a.N ? &kTallTile : &kWideTile;
+        for (const Dma16Tile* t : {&kWideTile, &kTallTile}) {
             const int64_t halves = t == &kTallTile ? (a.N + 127) / 128 : (a.M + 127) / 128;
-            if (halves != 1) continue;
             int p = 1;
             int64_t f = 0;
-            const double tt = dma16_time(*t, a, cus, a.batch == 1, &p, &f);
-            if (tt < t_large) { t_large = tt; best_tile = t; parts = p; first_split = f; }
+            const double tt = dma16_time(*t, a, cus, a.batch == 1, &p, &f) * (t == favoured ? 1.0 : kUnfavouredHalfTile);
+            const bool allowed = halves == 1 || (in_cache && tt < kHalfTileMargin * t_full);
+            if (allowed && tt < t_large) { t_large = tt; best_tile = t; parts = p; first_split = f; }
         }
     }
     const bool small_ok = gemm::tile_variant_supports(a, kSmallTileVariant);
-    double t_small = small_tile_time(a, small, 1, cus);
+    const double t_whole = small_tile_time(a, small, 1, cus);
+    double t_small = t_whole;
     int slices = 1;
     if (small_ok && a.batch == 1 && a.N % 8 == 0 && (a.M + a.N) * a.K * 2 <= kLastLevelCacheBytes) {
         for (int sl : kSliceChoices) {
             if (a.K / sl < kMinSliceK || small * sl > 2 * cus) break;
             const double t = small_tile_time(a, small, sl, cus);
-            if (t < t_small) { t_small = t; slices = sl; }
+            if (t < t_small && t < kSliceMargin * t_whole) { t_small = t; slices = sl; }
         }
     }
     if (t_large <= t_small) {
@@ -196,7 +211,7 @@ TileChoice choose_tile(const Args& a, int num_cus) {
         return TileChoice{best_tile->variant, (int)first_split, parts, t_large};
     }
     if (!small_ok) return TileChoice{kSmallTileFallback, 0, 1, 0.0};
-    return TileChoice{a.K / slices <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, slices, t_small};
+    return TileChoice{slices == 1 && a.K <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, slices, t_small};
 }
 
 gemm_status_t ensure_workspace(gemm_handle_s* h, size_t bytes, hipStream_t stream) {
