@@ -384,10 +384,10 @@ gemm_status_t launch_plan(gemm_handle_s* h, const Args& a, gemm_plan_t& plan, in
 // tile's k loop for a few columns there, and that column of tiles can cost a round of its own
 // (8000x8200x8136: 33 tile columns for 8 columns of C, 1056 tiles = four rounds and 32 tiles).  The
 // call is then made in two: the whole tiles, and the remaining thin strip as a call of its own, which
-// the choice above sends to small tiles cut along K.  Taken when the two estimates together are 5 %
+// the choice above sends to small tiles cut along K.  Taken when the two estimates together are 3 %
 // below the estimate for the whole; a strip is at most 64 wide.  `rest` starts where `main_part` ends.
 constexpr int64_t kPeelWidest = 64;
-constexpr double kPeelGain = 0.95, kSecondLaunch = 3.0;
+constexpr double kPeelGain = 0.97, kSecondLaunch = 3.0;
 
 bool peel_remainder(const Args& a, int num_cus, double whole_time, Args* main_part, Args* rest, TileChoice* main_choice,
                     TileChoice* rest_choice) {
