@@ -121,6 +121,7 @@ constexpr double kSmallAloneFew = 0.0055, kSmallAloneMany = 0.008, kSmallAloneAl
 constexpr double kSmallHbmRate = 4.7e6, kSliceMoveRate = 4.5e6;      // bytes per us
 constexpr int kSliceChoices[] = {2, 4, 8, 16};
 constexpr int64_t kMinSliceK = 512;          // shorter k ranges spend their time filling the pipeline (256x512x4096: 8 slices 12 us, 16 slices 15)
+constexpr int64_t kMinSliceKF32 = 128;      // (an fp32 slab takes 16 times as long to multiply: 64x1024x1024 11 us in 8 slices, 18 in 2)
 constexpr double kSliceMargin = 0.9;          // slices must promise 10 % (384x2048x2048: 14 us whole, 18 in 4 slices, estimated equal)
 constexpr double kSliceLaunch = 5.0;          // the second kernel of a sliced call: launch, gap, one round trip (512x2048x2048: 14 us whole, 19 in 4 slices)
 // Operands beyond the last-level cache stream from HBM on every call; there the large tile with its split
@@ -157,14 +158,29 @@ constexpr int64_t kF32MinTiles = 1;
 TileChoice choose_tile(const Args& a, int num_cus) {
     const int64_t cus = num_cus > 0 ? num_cus : 256;
     if (a.dtype == gemm::DT_F32) {
-        // tiles per compute unit (the busiest one) times the cost of a tile, in units of a 64x64 tile: a
-        // 128x128 tile costs 3.88 of them (4096^3: 1070 against 1105 us); a compute unit that holds fewer
-        // workgroups than fit on it (2 large, 4 small) runs them 20 % / 10 % slower.  3072^3: 9 small
-        // tiles per unit against 3 large ones, 515 against 615 us.
-        const int64_t n128 = (((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch + cus - 1) / cus;
-        const int64_t n64 = (((a.M + 63) / 64) * ((a.N + 63) / 64) * a.batch + cus - 1) / cus;
-        const double t128 = (double)n128 * 3.88 * (n128 < 2 ? 1.2 : 1.0), t64 = (double)n64 * (n64 < 4 ? 1.1 : 1.0);
-        return TileChoice{t128 <= t64 ? kF32TileVariant : kF32SmallTileVariant, 0, 1, 0.0};
+        // fp32: the 128x128 tile (two workgroups per compute unit) or the 64x64 tile (four), whole or
+        // in k slices.  Estimate in us: a workgroup that has its unit to itself walks k at 0.0275
+        // (64x64: 1024^3 in 28 us) or 0.085 us per element; with more, the busiest unit takes
+        // tiles-per-unit x 0.02 (4096x1024x1024: 82 us) or x 0.068 (4096x8192x1024: 575 us); 4 us fixed;
+        // slices add the second kernel.  3072^3: 9 small tiles per unit against 3 large ones, 515 against
+        // 615 us; 4096^3: 1070 on the large tile against 1105.  Deep k on a small grid gains most from
+        // slices: 256x256x65536 1558 -> 114 us in 16, 512x512x16384 393 -> 92 in 8, 64x4096x4096 101 -> 31 in 8.
+        int best_variant = kF32SmallTileVariant, best_slices = 1;
+        double best_time = 0.0;
+        for (int big = 0; big < 2; ++big) {
+            const int64_t side = big ? 128 : 64;
+            const int64_t tiles = ((a.M + side - 1) / side) * ((a.N + side - 1) / side) * a.batch;
+            const double alone = big ? 0.085 : 0.0275, shared = big ? 0.068 : 0.02;
+            for (int sl : {1, 2, 4, 8, 16}) {
+                if (sl > 1 && (a.batch != 1 || a.N % 8 != 0 || a.K / sl < kMinSliceKF32)) break;
+                const int64_t wgs = tiles * sl, per_unit = (wgs + cus - 1) / cus;
+                const double k = (double)a.K / sl;
+                double t = (wgs <= cus ? alone : shared * (double)per_unit) * k + 4.0;
+                if (sl > 1) t = (t + kSliceLaunch + (double)sl * (double)(a.M * a.N) * 8.0 / kSliceMoveRate) / kSliceMargin;
+                if (best_time == 0.0 || t < best_time) { best_time = t; best_variant = big ? kF32TileVariant : kF32SmallTileVariant; best_slices = sl; }
+            }
+        }
+        return TileChoice{best_variant, 0, best_slices, 0.0};
     }
     // a batch multiplies the number of workgroups; its trailing round is never split along K
     const int64_t small = ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;

@@ -233,6 +233,15 @@ def test_tile_k_slices_fp32_refusals_and_automatic_choice(handle):
     g2 = DeviceProblem(gcfg, ginp)
     g2.run(handle)
     assert np.array_equal(first, g2.result_bits())
+    # fp32 operands: a few tiles with a long k loop are sliced as well; integer data -> exact
+    fcfg = base_cfg(256, 264, 8192, 1, 0, wl.F32, wl.F32, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.F32)
+    finp, _ = wl.make_integer_inputs(fcfg, 88, -2, 2)
+    fwant = oracle.decode(wl.F32, expected_bits_exact(fcfg, finp))
+    f = DeviceProblem(fcfg, finp)
+    f.run(handle)
+    kernel, variant, slices = lg.gemm_get_last_plan(handle)
+    assert kernel == lg.GEMM_KERNEL_MFMA_TILE and slices > 1 and lg.gemm_variant_name(kernel, variant).startswith("f32_")
+    assert np.array_equal(decode_c(fcfg, f.result_bits()), fwant)
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 1), (0, 0), (1, 1), (1, 0)])
