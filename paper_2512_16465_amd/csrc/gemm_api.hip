@@ -189,7 +189,7 @@ TileChoice choose_tile(const Args& a, int num_cus) {
     int parts = 1;
     int64_t first_split = 0;
     double t_large = dma16_time(kFullTile, a, cus, large_ok && a.batch == 1, &parts, &first_split);
-    if (large_ok) {
+    if (large_ok && a.batch == 1) {      // (in batched calls they were 4 to 16 % behind the 128x128 tile wherever they were chosen)
         // A half tile (a) where every full tile would be at least half empty (N <= 128 or M <= 128), or
         // (b) where it fills the chip better than the full tile does - 2048x4096x4096 is 128 full tiles
         // but 256 tiles of 256x128: 56 us against 80 on 128x128 tiles; 1024x8192x8192: 103 against 122 -
