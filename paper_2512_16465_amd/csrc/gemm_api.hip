@@ -537,12 +537,13 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
         // The paper's roofline rule (Section 4.3) in arithmetic form: few rows of C make the
         // call bandwidth-limited (stream B once, split K); otherwise it is a matrix-core problem.
         // The skinny kernels are ahead where B is a long stream: up to 32 rows, B of 128 MiB or more,
-        // K >= 4096 (32x16384x16384: 94 against 99 us on the 128x256 tile with a K split,
+        // K >= 4096, N >= 4096 (fewer than 16 column groups need more than 16 slices: 16x2048x32768 36 to 38 us
+        // against 31 to 32 on sliced tiles) (32x16384x16384: 94 against 99 us on the 128x256 tile with a K split,
         // 16x28672x8192 with B stored N x K: 79 against 92).  Smaller weights run as fast or faster as
         // sliced 128x128 tiles (32x2048x2048: 19 to 21 against 15 to 20 us, 32x256x512: 18 to 26 against
         // 10 to 13), and with 33 to 64 rows the 128x256 tile wins everywhere (64x16384x16384: 107
         // against 112 / 126 us, 64x28672x8192: 100 against 152 / 158).
-        if (gemm::skinny_supports(a) && batch_aligned && M <= kSkinnyAutoRows && N * K * 2 >= kSkinnyAutoBytes && K >= 4096) {
+        if (gemm::skinny_supports(a) && batch_aligned && M <= kSkinnyAutoRows && N * K * 2 >= kSkinnyAutoBytes && K >= 4096 && N >= 4096) {
             plan = gemm_plan_t{GEMM_KERNEL_SKINNY, gemm::skinny_variant_of(a), gemm::skinny_default_split(a, h->num_cus)};
         } else if (gemm::tile_supports(a) && batch_aligned &&
                    (a.dtype != gemm::DT_F32 || ((a.M + 63) / 64) * ((a.N + 63) / 64) * a.batch >= kF32MinTiles)) {
