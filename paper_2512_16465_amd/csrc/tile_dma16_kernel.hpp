@@ -428,10 +428,13 @@ hipError_t launch_dma16_variant(const Args& a, int group_m, const TileSplit& spl
     const int c_vec_ok = c_rows_take_vec4(a);
     // A split call streams its operands (few tiles, long k), and so does a single row or column of
     // tiles whose operands exceed the last-level cache: rotate the k walk when a k-contiguous
-    // operand has its rows a multiple of 4 KiB apart (see the kernel).
+    // operand has its rows a multiple of 4 KiB apart (see the kernel).  With more than four shares
+    // per tile the shares themselves spread the workgroups over k, and a rotation would only stop
+    // the tiles of one share from walking the smaller operand together (1024x512x65536 in 16 shares
+    // on 128x256 tiles: 104 us rotated, 69 unrotated).
     const bool a_aliases = akc && (a.lda * 2) % 4096 == 0, b_aliases = bkc && (a.ldb * 2) % 4096 == 0;
     const bool one_panel_each = (tiles_m == 1 || tiles_n == 1) && (a.M + a.N) * a.K * 2 > ((int64_t)256 << 20);
-    const int rotate = (splits || one_panel_each) && (a_aliases || b_aliases);
+    const int rotate = ((splits && split.parts <= 4) || one_panel_each) && (a_aliases || b_aliases);
 #define GEMM_TILE_LAUNCH(BF, AKC, BKC) \
     hipLaunchKernelGGL((tile_dma16_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok, \
                        split_first, split_parts, split.partials, rotate)
