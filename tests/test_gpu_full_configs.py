@@ -61,7 +61,10 @@ def test_integer_exact_with_full_coverage(handle, name):
     inp, vals = wl.make_integer_inputs(cfg, 2024, -1, 1)
     p = DeviceProblem(cfg, inp)
     p.run(handle)
-    C = p.result_bits()[:, : cfg.N]
+    check_integer_result(cfg, inp, vals, p.result_bits()[:, : cfg.N])
+
+
+def check_integer_result(cfg, inp, vals, C):
     Ci = np.rint(C).astype(np.int64)
     assert np.array_equal(Ci.astype(np.float32), C), "non-integer output on integer data"
     opA = vals["A"].T if cfg.transA else vals["A"]          # M x K
@@ -79,6 +82,24 @@ def test_integer_exact_with_full_coverage(handle, name):
     rows, cols = wl.sample_indices(cfg.M, cfg.N, 5)
     ref, _, _ = oracle.gemm_at(oracle_problem(cfg, inp), rows, cols)
     assert np.array_equal(C[rows, cols].astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("name,variant,split", [("X4", 5, 1), ("X4", 10, 1), ("X4", 15, 1), ("C5", 15, 4), ("X7", 14, 4), ("X7", 10, 8),
+                                                ("X7", 5, 4), ("C2", 14, 1), ("C2", 5, 2)])
+def test_forced_tile_plans_at_full_size(handle, name, variant, split):
+    """Plans the automatic choice does not take at these shapes, among them the rotated k walks of the
+    streaming calls (one row or column of tiles beyond the last-level cache; splits of at most four shares) on
+    the 128x128, 256x128, 128x256 and 256x256 tiles, and k slices at full size: same exact checks."""
+    cfg = wl.scaled(ALL[name], out_dtype=wl.F32, act=wl.ACT_NONE, bias_dist=None)
+    inp, vals = wl.make_integer_inputs(cfg, 2025, -1, 1)
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, variant, split)
+    try:
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_MFMA_TILE, variant, split)
+    finally:
+        lg.gemm_set_plan(handle)
+    check_integer_result(cfg, inp, vals, p.result_bits()[:, : cfg.N])
 
 
 @pytest.mark.parametrize("name", FULL)
