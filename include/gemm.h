@@ -184,6 +184,17 @@ gemm_status_t gemm_set_plan(gemm_handle_t h, const gemm_plan_t* plan);
  * Errors: GEMM_ERR_INVALID_ARG for null arguments. */
 gemm_status_t gemm_get_last_plan(gemm_handle_t h, gemm_plan_t* out);
 
+/* The plan an automatic call of this shape would take on a device with `compute_units` compute
+ * units, for operands on 16-byte boundaries, matrices of a batch packed back to back, no epilogue
+ * terms.  Host arithmetic only: no device is touched and no handle is needed, so the choice can be
+ * inspected (and is tested) without a GPU.  For a call made as two products (see
+ * gemm_get_last_plan) it is the plan of the whole tiles.
+ * Errors: GEMM_ERR_INVALID_ARG for a null `out`, sizes below 1, leading dimensions too small or an
+ * unknown enum; GEMM_ERR_UNSUPPORTED for an out_dtype that is neither dtype nor GEMM_F32. */
+gemm_status_t gemm_plan_query(int32_t compute_units, int64_t batch, int64_t M, int64_t N, int64_t K,
+                              gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype, gemm_dtype_t out_dtype,
+                              int64_t lda, int64_t ldb, int64_t ldc, gemm_plan_t* out);
+
 /* Name of a tile variant of a family (static storage), or NULL if the index is out of range.
  * Lets a harness enumerate variants: loop until NULL. */
 const char* gemm_variant_name(gemm_kernel_t kernel, int32_t variant);

@@ -21,7 +21,7 @@ GEMM_KERNEL_AUTO, GEMM_KERNEL_GENERAL, GEMM_KERNEL_MFMA_TILE, GEMM_KERNEL_SKINNY
 
 EXPORTED_SYMBOLS = (
     "gemm_create", "gemm_run", "gemm_run_batched", "gemm_destroy", "gemm_status_string",
-    "gemm_set_plan", "gemm_get_last_plan", "gemm_variant_name",
+    "gemm_set_plan", "gemm_get_last_plan", "gemm_variant_name", "gemm_plan_query",
 )
 
 
@@ -72,6 +72,9 @@ def load_library() -> ctypes.CDLL:
     lib.gemm_set_plan.argtypes = [vp, ctypes.POINTER(gemm_plan_t)]
     lib.gemm_get_last_plan.restype = ctypes.c_int
     lib.gemm_get_last_plan.argtypes = [vp, ctypes.POINTER(gemm_plan_t)]
+    lib.gemm_plan_query.restype = ctypes.c_int
+    lib.gemm_plan_query.argtypes = [ctypes.c_int32, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                    i64, i64, i64, ctypes.POINTER(gemm_plan_t)]
     lib.gemm_variant_name.restype = ctypes.c_char_p
     lib.gemm_variant_name.argtypes = [ctypes.c_int, ctypes.c_int32]
     _lib = lib
@@ -146,6 +149,19 @@ def gemm_get_last_plan(handle: int):
     st = load_library().gemm_get_last_plan(ctypes.c_void_p(handle), ctypes.byref(plan))
     if st != GEMM_OK:
         raise GemmError(st, "gemm_get_last_plan")
+    return plan.kernel, plan.variant, plan.split_k
+
+
+def gemm_plan_query(compute_units: int, batch: int, M: int, N: int, K: int, transA: int, transB: int, dtype: int,
+                    out_dtype: int, lda: int, ldb: int, ldc: int, check: bool = True):
+    """(kernel, variant, split_k) of the automatic plan for this shape; host only, needs no GPU."""
+    plan = gemm_plan_t()
+    st = load_library().gemm_plan_query(compute_units, batch, M, N, K, transA, transB, dtype, out_dtype, lda, ldb, ldc,
+                                        ctypes.byref(plan))
+    if st != GEMM_OK:
+        if check:
+            raise GemmError(st, "gemm_plan_query")
+        return st
     return plan.kernel, plan.variant, plan.split_k
 
 

@@ -434,6 +434,51 @@ bool peel_remainder(const Args& a, int num_cus, double whole_time, Args* main_pa
     return found;
 }
 
+// The paper's roofline rule (Section 4.3) in arithmetic form: few rows of C make the
+// call bandwidth-limited (stream B once, split K); otherwise it is a matrix-core problem.
+// The skinny kernels are ahead where B is a long stream: up to 32 rows, B of 128 MiB or more,
+// K >= 4096, N >= 4096 (fewer than 16 column groups need more than 16 slices: 16x2048x32768 36 to 38 us
+// against 31 to 32 on sliced tiles) (32x16384x16384: 94 against 99 us on the 128x256 tile with a K split,
+// 16x28672x8192 with B stored N x K: 79 against 92).  Smaller weights run as fast or faster as
+// sliced 128x128 tiles (32x2048x2048: 19 to 21 against 15 to 20 us, 32x256x512: 18 to 26 against
+// 10 to 13), and with 33 to 64 rows the 128x256 tile wins everywhere (64x16384x16384: 107
+// against 112 / 126 us, 64x28672x8192: 100 against 152 / 158).
+struct AutoPlan {
+    gemm_plan_t plan;          // of the call, or of its whole tiles when it is made in two
+    int split_first;
+    bool peeled;               // made in two: main_part with `plan`, then rest with rest_plan
+    Args main_part, rest;
+    gemm_plan_t rest_plan;
+    int rest_split_first;
+};
+
+AutoPlan automatic_plan(const Args& a, int num_cus, bool batch_aligned) {
+    AutoPlan ap;
+    ap.plan = gemm_plan_t{GEMM_KERNEL_GENERAL, 0, 1};
+    ap.split_first = -1;
+    ap.peeled = false;
+    ap.rest_plan = ap.plan;
+    ap.rest_split_first = -1;
+    if (gemm::skinny_supports(a) && batch_aligned && a.M <= kSkinnyAutoRows && a.N * a.K * 2 >= kSkinnyAutoBytes && a.K >= 4096 &&
+        a.N >= 4096) {
+        ap.plan = gemm_plan_t{GEMM_KERNEL_SKINNY, gemm::skinny_variant_of(a), gemm::skinny_default_split(a, num_cus)};
+    } else if (gemm::tile_supports(a) && batch_aligned &&
+               (a.dtype != gemm::DT_F32 || ((a.M + 63) / 64) * ((a.N + 63) / 64) * a.batch >= kF32MinTiles)) {
+        const TileChoice c = choose_tile(a, num_cus);
+        ap.plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, c.variant, c.parts};
+        ap.split_first = c.first_split_tile;
+        TileChoice cm, cr;
+        if (peel_remainder(a, num_cus, c.time, &ap.main_part, &ap.rest, &cm, &cr)) {
+            ap.peeled = true;
+            ap.plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, cm.variant, cm.parts};
+            ap.split_first = cm.first_split_tile;
+            ap.rest_plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, cr.variant, cr.parts};
+            ap.rest_split_first = cr.first_split_tile;
+        }
+    }
+    return ap;
+}
+
 // Largest number of matrices one launch takes (the y dimension of a grid).
 constexpr int64_t kMaxBatchPerLaunch = 65535;
 
@@ -534,36 +579,20 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
             plan = gemm_plan_t{GEMM_KERNEL_GENERAL, 0, 1};
         }
     } else {
-        // The paper's roofline rule (Section 4.3) in arithmetic form: few rows of C make the
-        // call bandwidth-limited (stream B once, split K); otherwise it is a matrix-core problem.
-        // The skinny kernels are ahead where B is a long stream: up to 32 rows, B of 128 MiB or more,
-        // K >= 4096, N >= 4096 (fewer than 16 column groups need more than 16 slices: 16x2048x32768 36 to 38 us
-        // against 31 to 32 on sliced tiles) (32x16384x16384: 94 against 99 us on the 128x256 tile with a K split,
-        // 16x28672x8192 with B stored N x K: 79 against 92).  Smaller weights run as fast or faster as
-        // sliced 128x128 tiles (32x2048x2048: 19 to 21 against 15 to 20 us, 32x256x512: 18 to 26 against
-        // 10 to 13), and with 33 to 64 rows the 128x256 tile wins everywhere (64x16384x16384: 107
-        // against 112 / 126 us, 64x28672x8192: 100 against 152 / 158).
-        if (gemm::skinny_supports(a) && batch_aligned && M <= kSkinnyAutoRows && N * K * 2 >= kSkinnyAutoBytes && K >= 4096 && N >= 4096) {
-            plan = gemm_plan_t{GEMM_KERNEL_SKINNY, gemm::skinny_variant_of(a), gemm::skinny_default_split(a, h->num_cus)};
-        } else if (gemm::tile_supports(a) && batch_aligned &&
-                   (a.dtype != gemm::DT_F32 || ((a.M + 63) / 64) * ((a.N + 63) / 64) * a.batch >= kF32MinTiles)) {
-            const TileChoice c = choose_tile(a, h->num_cus);
-            plan = gemm_plan_t{GEMM_KERNEL_MFMA_TILE, c.variant, c.parts};
-            split_first = c.first_split_tile;
-            Args main_part, rest;
-            TileChoice cm, cr;
-            if (peel_remainder(a, h->num_cus, c.time, &main_part, &rest, &cm, &cr)) {
-                gemm_plan_t pm{GEMM_KERNEL_MFMA_TILE, cm.variant, cm.parts}, pr{GEMM_KERNEL_MFMA_TILE, cr.variant, cr.parts};
-                // the workspace of both parts first: a failed allocation must leave C untouched
-                gemm_status_t st = launch_plan(h, main_part, pm, cm.first_split_tile, stream, true);
-                if (st == GEMM_OK) st = launch_plan(h, rest, pr, cr.first_split_tile, stream, true);
-                if (st != GEMM_OK) return st;
-                st = launch_plan(h, main_part, pm, cm.first_split_tile, stream);
-                if (st == GEMM_OK) st = launch_plan(h, rest, pr, cr.first_split_tile, stream);
-                if (st != GEMM_OK) return st;
-                h->last = pm;         // the plan of the whole tiles
-                return GEMM_OK;
-            }
+        const AutoPlan ap = automatic_plan(a, h->num_cus, batch_aligned);
+        plan = ap.plan;
+        split_first = ap.split_first;
+        if (ap.peeled) {
+            gemm_plan_t pm = ap.plan, pr = ap.rest_plan;
+            // the workspace of both parts first: a failed allocation must leave C untouched
+            gemm_status_t st = launch_plan(h, ap.main_part, pm, ap.split_first, stream, true);
+            if (st == GEMM_OK) st = launch_plan(h, ap.rest, pr, ap.rest_split_first, stream, true);
+            if (st != GEMM_OK) return st;
+            st = launch_plan(h, ap.main_part, pm, ap.split_first, stream);
+            if (st == GEMM_OK) st = launch_plan(h, ap.rest, pr, ap.rest_split_first, stream);
+            if (st != GEMM_OK) return st;
+            h->last = pm;         // the plan of the whole tiles
+            return GEMM_OK;
         }
     }
 
@@ -575,6 +604,35 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
 }
 
 }  // namespace
+
+GEMM_EXPORT gemm_status_t gemm_plan_query(int32_t compute_units, int64_t batch, int64_t M, int64_t N, int64_t K,
+                                          gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype, gemm_dtype_t out_dtype,
+                                          int64_t lda, int64_t ldb, int64_t ldc, gemm_plan_t* out) {
+    if (!out || compute_units < 1 || batch < 1 || M < 1 || N < 1 || K < 1) return GEMM_ERR_INVALID_ARG;
+    if ((transA != GEMM_OP_N && transA != GEMM_OP_T) || (transB != GEMM_OP_N && transB != GEMM_OP_T)) return GEMM_ERR_INVALID_ARG;
+    if (!valid_dtype(dtype) || !valid_dtype(out_dtype)) return GEMM_ERR_INVALID_ARG;
+    if (out_dtype != dtype && out_dtype != GEMM_F32) return GEMM_ERR_UNSUPPORTED;
+    const int64_t a_cols = transA == GEMM_OP_N ? K : M, b_cols = transB == GEMM_OP_N ? N : K;
+    if (lda < a_cols || ldb < b_cols || ldc < N) return GEMM_ERR_INVALID_ARG;
+    if (batch > kMaxBatchPerLaunch) batch = kMaxBatchPerLaunch;      // larger batches run in parts of this size
+    Args a;
+    a.M = M; a.N = N; a.K = K;
+    a.transA = transA == GEMM_OP_T; a.transB = transB == GEMM_OP_T;
+    a.dtype = (int)dtype; a.out_dtype = (int)out_dtype; a.bias_dtype = (int)dtype; a.act = gemm::ACT_NONE;
+    a.alpha = 1.0f; a.beta = 0.0f;
+    // stand-ins for aligned operands (never dereferenced: nothing is launched)
+    a.A = (const void*)(uintptr_t)0x100000; a.B = (const void*)(uintptr_t)0x100000; a.C = (void*)(uintptr_t)0x100000;
+    a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.bias = nullptr;
+    a.batch = (int32_t)batch;
+    a.k_total = 0;
+    const int64_t rows_a = transA == GEMM_OP_N ? M : K, rows_b = transB == GEMM_OP_N ? K : N;
+    a.strideA = batch > 1 ? rows_a * lda : 0; a.strideB = batch > 1 ? rows_b * ldb : 0; a.strideC = batch > 1 ? M * ldc : 0;
+    const int64_t in_bytes = gemm::elem_bytes(a.dtype);
+    const bool batch_aligned = batch == 1 || ((a.strideA * in_bytes) % 16 == 0 && (a.strideB * in_bytes) % 16 == 0);
+    *out = automatic_plan(a, compute_units, batch_aligned).plan;
+    return GEMM_OK;
+}
 
 GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_t K,
                                    gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,

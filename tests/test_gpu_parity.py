@@ -443,6 +443,19 @@ def test_few_rows_small_weight_automatic_choice(handle, M, N, K, tb):
     assert np.array_equal(decode_c(cfg, p.result_bits()), want)
 
 
+def test_plan_query_agrees_with_the_plan_that_ran(handle):
+    # the host-only query and the call itself go through the same choice
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    for (M, N, K, ta, tb, dtype, out) in [(512, 512, 4096, 0, 0, wl.BF16, wl.BF16), (64, 1024, 4096, 0, 1, wl.F16, wl.F32),
+                                          (300, 520, 192, 1, 1, wl.BF16, wl.BF16), (256, 264, 8192, 0, 0, wl.F32, wl.F32),
+                                          (2048, 128, 2048, 0, 0, wl.BF16, wl.BF16), (37, 29, 53, 1, 0, wl.F32, wl.F32)]:
+        cfg = base_cfg(M, N, K, ta, tb, dtype, out, a_dist=("normal", 1.0), b_dist=("normal", 0.05))
+        p = DeviceProblem(cfg, wl.make_inputs(cfg, 89))
+        p.run(handle)
+        torch.cuda.synchronize()
+        assert lg.gemm_get_last_plan(handle) == lg.gemm_plan_query(cus, 1, M, N, K, ta, tb, dtype, out, cfg.ld_a(), cfg.ld_b(), cfg.ld_c())
+
+
 # ------------------------------------------------------------------ every activation through every kernel family
 
 @pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_SILU, wl.ACT_GELU_TANH, wl.ACT_GELU_ERF])

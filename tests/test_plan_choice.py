@@ -1,0 +1,110 @@
+"""CPU-only: the host logic that picks kernel family, tile, split and slices, through
+gemm_plan_query (host arithmetic, no device).  Pins the choice for the benchmark configurations and for
+the shapes each rule was made for, on a device with 256 compute units."""
+import pytest
+
+import paper_2512_16465_amd as lg
+import workloads as wl
+
+CUS = 256
+TILE, SKINNY, GENERAL = lg.GEMM_KERNEL_MFMA_TILE, lg.GEMM_KERNEL_SKINNY, lg.GEMM_KERNEL_GENERAL
+
+
+def plan(M, N, K, ta=0, tb=0, dtype=wl.BF16, out=None, batch=1, lda=None, ldb=None, ldc=None, cus=CUS):
+    out = dtype if out is None else out
+    lda = (M if ta else K) if lda is None else lda
+    ldb = (K if tb else N) if ldb is None else ldb
+    ldc = N if ldc is None else ldc
+    kernel, variant, split = lg.gemm_plan_query(cus, batch, M, N, K, ta, tb, dtype, out, lda, ldb, ldc)
+    return kernel, lg.gemm_variant_name(kernel, variant), split
+
+
+def plan_of(name):
+    c = {**wl.CONFIGS, **wl.EXTRA_CONFIGS}[name]
+    return plan(c.M, c.N, c.K, c.transA, c.transB, c.dtype, c.out_dtype, c.batch, c.ld_a(), c.ld_b(), c.ld_c())
+
+
+def test_benchmark_configurations():
+    big = "dma16p_256x256x32_w2x2_s5"
+    assert plan_of("C1") == (TILE, "f32_64x64x32_w2x2", 1)
+    for name in ("C2", "C3", "C4", "X1", "X2"):
+        assert plan_of(name) == (TILE, big, 1), name
+    assert plan_of("C5") == (SKINNY, "skinny_nn_32x256_w4", 4)
+    assert plan_of("X5") == (SKINNY, "skinny_nn_32x256_w4", 4)
+    assert plan_of("X7") == (SKINNY, "skinny_nt_32x256_w4", 4)
+    assert plan_of("X4") == (TILE, "dma16p_256x128x32_w2x2_s5", 1)       # N = 128: every full tile would be half empty
+    assert plan_of("X6") == (TILE, "f32_128x128x32_w2x2", 1)
+    assert plan_of("X8") == (TILE, "dma_128x128x32_w2x2_s3", 1)          # batched, K = 128: ring of three, no split
+    # made in two: 8000 x 8192 on whole tiles (four full rounds), then the strip of 8 columns
+    assert plan_of("X3") == (TILE, big, 1)
+    assert plan_of("X9") == (TILE, big, 1) and plan_of("X10") == (TILE, big, 1)
+    # ... whereas one more tile column that is half full stays one call with a split trailing round
+    kernel, name, split = plan(8000, 8192 + 128, 8136, 0, 1)
+    assert (kernel, name) == (TILE, big) and split > 1
+
+
+def test_family_by_rows_and_weight_size():
+    # the streaming kernels: up to 32 rows on a B of 128 MiB or more with K and N of 4096 or more
+    assert plan(32, 8192, 8192)[0] == SKINNY and plan(1, 16384, 4096, 0, 1)[0] == SKINNY
+    assert plan(33, 16384, 16384)[:2] == (TILE, "dma16p_128x256x32_w2x2_s5")
+    assert plan(64, 16384, 16384, 0, 1) == (TILE, "dma16p_128x256x32_w2x2_s5", 4)
+    assert plan(32, 4096, 4096)[0] == TILE                      # 32 MiB of weights
+    assert plan(16, 2048, 32768)[0] == TILE                     # too few column groups
+    assert plan(16, 65536, 2048)[0] == TILE                     # short k
+    assert plan(8, 8192, 8192, ta=1)[0] == TILE                 # A stored K x M
+    # 112 column groups: two slices fill 224 of 256 units in one round
+    assert plan(32, 28672, 8192) == (SKINNY, "skinny_nn_32x256_w4", 2)
+    # anything the vector loads cannot take goes to the general kernel
+    assert plan(37, 29, 53, 1, 0, wl.F32)[0] == GENERAL
+    assert plan(128, 128, 132)[0] == GENERAL                    # K not a multiple of 8
+    assert plan(128, 128, 128, lda=132)[0] == GENERAL           # rows of A off the 16-byte grid
+
+
+def test_tile_split_and_slices():
+    small = "dma_128x128x32_w2x2_s4"
+    # 16 tiles of 128 x 128 with a long k loop: k slices
+    kernel, name, slices = plan(512, 512, 4096)
+    assert (kernel, name) == (TILE, small) and slices > 1
+    assert plan(1024, 1024, 1024) == (TILE, small, 1)           # 64 tiles, short k: whole
+    assert plan(512, 512, 4104)[2] > 1                           # a last slice shorter than the others
+    kernel, name, split = plan(512, 516, 4096, tb=1)             # slices need N to be a multiple of 8 ...
+    assert kernel == TILE and (split == 1 or name.startswith("dma16"))   # ... the split of the 16x16x32 tiles does not
+    # one partly filled round of 256 x 256 tiles: split shares; a grid the half tile fills better
+    kernel, name, shares = plan(4096, 4224, 4096)
+    assert (kernel, name) == (TILE, "dma16p_256x256x32_w2x2_s5") and shares > 1
+    assert plan(2048, 4096, 4096) == (TILE, "dma16p_128x256x32_w2x2_s5", 1)
+    assert plan(4096, 2048, 2048) == (TILE, "dma16p_256x128x32_w2x2_s5", 1)
+    # weights beyond the last-level cache stay on the full tile with its split
+    assert plan(640, 16384, 16384)[1] == "dma16p_256x256x32_w2x2_s5"
+    # batched calls: no split, no slices, no half tiles
+    for shape in ((2048, 128, 2048), (512, 512, 4096), (4096, 128, 4096)):
+        kernel, name, split = plan(*shape, batch=8)
+        assert kernel == TILE and split == 1 and not name.startswith("dma16p_256x128") and not name.startswith("dma16p_128x256")
+    # short k loops take the ring of three
+    assert plan(8192, 8192, 256)[1] == "dma_128x128x32_w2x2_s3" and plan(4096, 4096, 512)[1] == small
+
+
+def test_fp32_tiles_and_slices():
+    assert plan(1024, 1024, 1024, dtype=wl.F32) == (TILE, "f32_64x64x32_w2x2", 1)
+    assert plan(4096, 4096, 4096, dtype=wl.F32) == (TILE, "f32_128x128x32_w2x2", 1)
+    assert plan(3072, 3072, 3072, dtype=wl.F32) == (TILE, "f32_64x64x32_w2x2", 1)
+    kernel, name, slices = plan(256, 256, 65536, dtype=wl.F32)
+    assert (kernel, name, slices) == (TILE, "f32_64x64x32_w2x2", 16)
+    assert plan(64, 1024, 1024, dtype=wl.F32)[2] > 1
+
+
+def test_fewer_compute_units_change_the_choice():
+    # the same 256 tiles are two rounds on 128 units: no share of a last round to split
+    assert plan(4096, 4096, 4096, cus=128) == (TILE, "dma16p_256x256x32_w2x2_s5", 1)
+    assert plan(32, 16384, 16384, cus=128)[2] == 2              # 64 column groups x 2 slices = 128 workgroups
+
+
+def test_query_argument_errors():
+    q = lambda *args: lg.gemm_plan_query(*args, check=False)
+    ok = (CUS, 1, 64, 64, 64, 0, 0, wl.BF16, wl.BF16, 64, 64, 64)
+    assert isinstance(q(*ok), tuple)
+    assert q(0, *ok[1:]) == lg.GEMM_ERR_INVALID_ARG
+    assert q(CUS, 1, 0, 64, 64, 0, 0, wl.BF16, wl.BF16, 64, 64, 64) == lg.GEMM_ERR_INVALID_ARG
+    assert q(CUS, 1, 64, 64, 64, 0, 0, wl.BF16, wl.BF16, 63, 64, 64) == lg.GEMM_ERR_INVALID_ARG
+    assert q(CUS, 1, 64, 64, 64, 2, 0, wl.BF16, wl.BF16, 64, 64, 64) == lg.GEMM_ERR_INVALID_ARG
+    assert q(CUS, 1, 64, 64, 64, 0, 0, wl.BF16, wl.F16, 64, 64, 64) == lg.GEMM_ERR_UNSUPPORTED
