@@ -32,6 +32,8 @@ bool valid_dtype(int d) { return d == GEMM_F32 || d == GEMM_F16 || d == GEMM_BF1
 // rounds) and 83 us (32 tiles per compute unit).  So long k loops favour the large tile (2.2x
 // the flops per cycle), short ones (K below about 560) the small one, and so does a grid that
 // leaves most of the chip idle or a dimension that would waste half of every large tile.
+// The constants of all estimates below were calibrated by timing the automatic plan against every
+// forced combination of tile variant and split over a few hundred shapes.
 // Operands of 2 GiB or more take the register-staged siblings (the direct loads mask lanes with
 // a fixed 2 GiB - 16 offset).
 constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant = 5, kSmallTileFallback = 3;
@@ -45,9 +47,10 @@ constexpr double kSmallPerK = 0.0094, kSmallFixed = 1.4;     // (the large tile'
 // variant can): each of its tiles goes to several workgroups, each over a share of the k slabs of
 // at least kMinSlabsPerPart, and a second kernel adds the parts.  The number of parts minimises
 // k loop / parts + the cost of the second kernel, which moves parts x tiles partial tiles of
-// 256 KiB (0.2 us each, write and read) and adds them one after the other (0.3 us per part).
-// Measured: 512x512x65536 (4 tiles) 89 / 67 / 86 us with 16 / 32 / 64 parts, 256x256x131072
-// (1 tile) 147 / 94 / 78 us, 1024x1024x16384 (16 tiles) 67 us with 16 parts.
+// 256 KiB (0.1 us each, write and read: 1024x4096x14336 on 128 half tiles in 2 parts, 106 us) and
+// adds them one after the other (0.3 us per part).  Measured: 512x512x65536 (4 tiles) 89 / 67 /
+// 86 us with 16 / 32 / 64 parts, 256x256x131072 (1 tile) 147 / 94 / 78 us, 1024x1024x16384
+// (16 tiles) 67 / 53 us with 16 / 12 parts.
 constexpr double kSplitBelow = 0.6, kReducePerPartTile = 0.1, kReducePerPart = 0.3, kReduceLaunch = 3.0;
 constexpr int kMinSlabsPerPart = 16;
 constexpr int kPartChoices[] = {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
