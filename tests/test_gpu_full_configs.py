@@ -14,7 +14,7 @@ from gpu_harness import DeviceProblem, check_sampled, decode_c, oracle_problem
 
 pytestmark = pytest.mark.gpu
 
-FULL = ["C2", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5", "X6", "X7", "X9", "X10"]
+FULL = ["C2", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5", "X6", "X7", "X9", "X10", "X11"]
 ALL = {**wl.CONFIGS, **wl.EXTRA_CONFIGS}
 SKINNY = ("C5", "X5", "X7")
 

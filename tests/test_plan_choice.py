@@ -34,6 +34,7 @@ def test_benchmark_configurations():
     assert plan_of("X7") == (SKINNY, "skinny_nt_32x256_w4", 4)
     assert plan_of("X4") == (TILE, "dma16p_256x128x32_w2x2_s5", 1)       # N = 128: every full tile would be half empty
     assert plan_of("X6") == (TILE, "f32_128x128x32_w2x2", 1)
+    assert plan_of("X11") == (TILE, "dma16p_128x256x32_w2x2_s5", 4)   # 64 tiles in 4 shares: one workgroup per unit
     assert plan_of("X8") == (TILE, "dma_128x128x32_w2x2_s3", 1)          # batched, K = 128: ring of three, no split
     # made in two: 8000 x 8192 on whole tiles (four full rounds), then the strip of 8 columns
     assert plan_of("X3") == (TILE, big, 1)

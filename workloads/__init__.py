@@ -159,6 +159,9 @@ EXTRA_CONFIGS: Dict[str, Config] = {
     "X8": Config("X8", 2048, 2048, 128, 0, 1, BF16, BF16, batch=32,
                  a_dist=("normal", 1.0), b_dist=("normal", 128 ** -0.5),
                  note="bf16 strided batch of 32 products 2048x2048x128 NT (the per-head score products of attention), bf16 out"),
+    "X11": Config("X11", 128, 16384, 16384, 0, 1, BF16, BF16,
+                  a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                  note="bf16 128x16384x16384 NT: 128 rows on a weight kept as [out, in] (between the skinny and the square regime)"),
     "X9": Config("X9", 4096, 4104, 4096, 0, 0, BF16, BF16, alpha=1.0, beta=1.0,
                  a_dist=("normal", 1.0), b_dist=("normal", 4096 ** -0.5), c_dist=("normal", 1.0),
                  bias_dist=("normal", 0.5), bias_dtype=BF16, act=ACT_RELU,
