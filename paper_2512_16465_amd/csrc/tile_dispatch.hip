@@ -79,7 +79,7 @@ namespace {
 // number, four at a time) and of C_in and bias are issued before the first use.
 template <int P>
 __global__ __launch_bounds__(256) void tile_split_reduce_kernel(Args a, int tiles_m, int tiles_n, int group_m, int first_tile,
-                                                                int parts, const float* partials, int BM, int BN) {
+                                                                int parts, const float* partials, int BM, int BN, int c_vec_ok) {
     int tm, tn;
     tile::tile_of_workgroup(first_tile + (int)blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
     const int idx = (int)blockIdx.y * 256 + (int)threadIdx.x;          // one of BM * BN / 4 vectors
@@ -90,10 +90,20 @@ __global__ __launch_bounds__(256) void tile_split_reduce_kernel(Args a, int tile
     const float* p = partials + ((size_t)blockIdx.x * parts) * tile_floats + (size_t)r * BN + c;
     float c_in[4] = {0.0f, 0.0f, 0.0f, 0.0f}, bj[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     auto load_inputs = [&]() {
+        const bool vec = c_vec_ok && col + 3 < a.N;
+        if (vec && a.beta != 0.0f) {
+            const int64_t ci = row * a.ldc + col;
+            f32x4 v;
+            if (a.out_dtype == DT_F32) v = tile::OutVec<DT_F32>::load4((const float*)a.C + ci);
+            else if (a.out_dtype == DT_BF16) v = tile::OutVec<DT_BF16>::load4((const uint16_t*)a.C + ci);
+            else v = tile::OutVec<DT_F16>::load4((const uint16_t*)a.C + ci);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) c_in[e] = v[e];
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if (col + e >= a.N) break;
-            if (a.beta != 0.0f) c_in[e] = load_elem(a.C, a.out_dtype, row * a.ldc + col + e);
+            if (!vec && a.beta != 0.0f) c_in[e] = load_elem(a.C, a.out_dtype, row * a.ldc + col + e);
             if (a.bias) bj[e] = load_elem(a.bias, a.bias_dtype, col + e);
         }
     };
@@ -119,10 +129,20 @@ __global__ __launch_bounds__(256) void tile_split_reduce_kernel(Args a, int tile
         }
         for (; q < parts; ++q) s += *(const f32x4*)(p + (size_t)q * tile_floats);
     }
+    f32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = epilogue_value(s[e], a.alpha, a.beta, c_in[e], bj[e], a.act);
+    if (c_vec_ok && col + 3 < a.N) {          // four outputs in one store
+        const int64_t ci = row * a.ldc + col;
+        if (a.out_dtype == DT_F32) tile::OutVec<DT_F32>::store4((float*)a.C + ci, o);
+        else if (a.out_dtype == DT_BF16) tile::OutVec<DT_BF16>::store4((uint16_t*)a.C + ci, o);
+        else tile::OutVec<DT_F16>::store4((uint16_t*)a.C + ci, o);
+        return;
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         if (col + e >= a.N) break;
-        store_elem(a.C, a.out_dtype, row * a.ldc + col + e, epilogue_value(s[e], a.alpha, a.beta, c_in[e], bj[e], a.act));
+        store_elem(a.C, a.out_dtype, row * a.ldc + col + e, o[e]);
     }
 }
 
@@ -136,9 +156,10 @@ hipError_t launch_tile_split_reduce(const Args& a, int variant, int group_m, con
     if (tail <= 0) return hipSuccess;
     const dim3 grid((unsigned)tail, (unsigned)(BM * BN / 4 / 256)), block(256);
     const int gm = group_m < 1 ? 1 : group_m;
+    const int c_vec_ok = c_rows_take_vec4(a);
 #define GEMM_REDUCE_LAUNCH(P)                                                                                       \
     hipLaunchKernelGGL(tile_split_reduce_kernel<P>, grid, block, 0, stream, a, tiles_m, tiles_n, gm, split.first_tile, \
-                       split.parts, (const float*)split.partials, BM, BN)
+                       split.parts, (const float*)split.partials, BM, BN, c_vec_ok)
     switch (split.parts) {
         case 2: GEMM_REDUCE_LAUNCH(2); break;
         case 3: GEMM_REDUCE_LAUNCH(3); break;
