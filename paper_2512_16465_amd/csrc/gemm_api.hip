@@ -65,30 +65,34 @@ constexpr int64_t kSkinnyAutoRows = 32, kSkinnyAutoBytes = (int64_t)128 << 20;
 // (4096^3: 116 us on either against 94 on the full tile = 0.0117 us per k and tile, 10 us fixed).
 // It pays where the full tile would be half empty: 65536x128x4096 100 us against 120 on the
 // 128x128 tile and 146 on the full tile, 32768x256x4096 75 against 87.
-struct Dma16Tile { int variant; int bm, bn; double per_k, fixed, hbm_rate; };
-constexpr Dma16Tile kFullTile{10, 256, 256, 0.0209, 15.0, 4.4e6};
-constexpr Dma16Tile kTallTile{14, 256, 128, 0.0117, 10.0, 5.8e6};
-constexpr Dma16Tile kWideTile{15, 128, 256, 0.0117, 10.0, 5.8e6};
+struct Dma16Tile { int variant; int bm, bn; double per_k, fixed, hbm_rate; int min_slabs; };   // min_slabs: shortest share of a split, in slabs of 32
+constexpr Dma16Tile kFullTile{10, 256, 256, 0.0209, 15.0, 4.4e6, kMinSlabsPerPart};
+constexpr Dma16Tile kTallTile{14, 256, 128, 0.0117, 10.0, 5.8e6, kMinSlabsPerPart};
+constexpr Dma16Tile kWideTile{15, 128, 256, 0.0117, 10.0, 5.8e6, kMinSlabsPerPart};
+// ... and quartered (128x128, 16 MFMAs per step): 1024x4096x4096 in 38.5 us on 256 tiles; with its split it is
+// the tile for small grids with long k loops (48x4096x4096: 15 us in 8 shares against 19 on sliced 32x32x16 tiles).
+constexpr Dma16Tile kQuarterTile{16, 128, 128, 0.0082, 4.0, 5.0e6, 4};       // (its steps are short: 64x4096x512 11 us in 4 shares of 4 slabs, 14 whole)
 constexpr double kHalfTileMargin = 0.9, kUnfavouredHalfTile = 1.15;
+constexpr int64_t kQuarterTileRows = 64;
 
 // time of the k loops of a round whose tiles are cut in `parts`, plus the second kernel (us)
-double split_round_time(const Dma16Tile& t, int64_t tail, int parts, int64_t K) {
+double split_round_time(const Dma16Tile& t, int64_t tail, int parts, int64_t K, double live = 1.0) {
     const double loop = t.per_k * (double)K / parts;
     if (parts <= 1) return loop;
-    const double area = (double)(t.bm * t.bn) / 65536.0;
+    const double area = live * (double)(t.bm * t.bn) / 65536.0;      // (rows of a tile below the last row of C are not moved)
     const double move = kReducePerPartTile * area * parts * (double)tail, add = kReducePerPart * parts;
     return loop + (move > add ? move : add) + kReduceLaunch;
 }
 
 // parts per tile of the trailing `tail` tiles (1 = no split)
-int tail_parts(const Dma16Tile& t, int64_t tail, int64_t cus, int64_t K) {
+int tail_parts(const Dma16Tile& t, int64_t tail, int64_t cus, int64_t K, double live = 1.0) {
     if (tail <= 0 || (double)tail >= kSplitBelow * (double)cus) return 1;
     const int64_t slabs = (K + 31) / 32;
     int best = 1;
-    double best_t = split_round_time(t, tail, 1, K);
+    double best_t = split_round_time(t, tail, 1, K, live);
     for (int parts : kPartChoices) {
-        if (parts * tail > cus || slabs / parts < kMinSlabsPerPart) break;
-        const double tt = split_round_time(t, tail, parts, K);
+        if (parts * tail > cus || slabs / parts < t.min_slabs) break;
+        const double tt = split_round_time(t, tail, parts, K, live);
         if (tt < best_t) { best_t = tt; best = parts; }
     }
     return best;
@@ -98,9 +102,11 @@ int tail_parts(const Dma16Tile& t, int64_t tail, int64_t cus, int64_t K) {
 double dma16_time(const Dma16Tile& t, const Args& a, int64_t cus, bool may_split, int* parts_out, int64_t* first_split) {
     const int64_t tiles = ((a.M + t.bm - 1) / t.bm) * ((a.N + t.bn - 1) / t.bn) * a.batch;
     const int64_t tail = tiles % cus;
-    const int parts = may_split ? tail_parts(t, tail, cus, a.K) : 1;
+    const int64_t rows = ((a.M + t.bm - 1) / t.bm) * t.bm;
+    const double live = (double)a.M / (double)rows;
+    const int parts = may_split ? tail_parts(t, tail, cus, a.K, live) : 1;
     double time = (double)(tiles / cus) * (t.per_k * (double)a.K + t.fixed);
-    if (tail) time += split_round_time(t, tail, parts, a.K) + t.fixed;
+    if (tail) time += split_round_time(t, tail, parts, a.K, live) + t.fixed;
     // operands that stream from HBM: not faster than this tile pulls them
     const double bytes = (double)(a.M + a.N) * (double)a.K * 2.0 * (double)a.batch;
     // (a thousandth of the unbounded estimate on top, so that of two tiles at the same bound the one with less to do wins)
@@ -205,12 +211,15 @@ TileChoice choose_tile(const Args& a, int num_cus) {
         // On equal tile counts the half tile whose long side lies along the longer side of C is ahead
         // (1024x512x65536: 256x128 69 us, 128x256 101; 512x512x65536: 63 and 47; 1024x1024x32768: 82 and 72).
         const Dma16Tile* favoured = a.M > a.N ? &kTallTile : &kWideTile;
-        for (const Dma16Tile* t : {&kWideTile, &kTallTile}) {
-            const int64_t halves = t == &kTallTile ? (a.N + 127) / 128 : (a.M + 127) / 128;
+        for (const Dma16Tile* t : {&kWideTile, &kTallTile, &kQuarterTile}) {
+            const int64_t halves = t == &kTallTile ? (a.N + 127) / 128 : (t == &kWideTile ? (a.M + 127) / 128 : 0);
             int p = 1;
             int64_t f = 0;
-            const double tt = dma16_time(*t, a, cus, a.batch == 1, &p, &f) * (t == favoured ? 1.0 : kUnfavouredHalfTile);
-            const bool allowed = halves == 1 || (in_cache && tt < kHalfTileMargin * t_full);
+            const double tt = dma16_time(*t, a, cus, a.batch == 1, &p, &f) * (t == favoured || t == &kQuarterTile ? 1.0 : kUnfavouredHalfTile);
+            // the quartered tile: for at most 64 rows of C, where it was ahead of every other plan on all 32 shapes
+            // tried (48 x N x K; by 10 to 38 % over the sliced 32x32x16 tile); elsewhere the estimates at 10 to 20 us are
+            // not sharp enough to place it (128x2048x2048: 14 us against 12), and it is left to forced plans
+            const bool allowed = t == &kQuarterTile ? (a.M <= kQuarterTileRows && in_cache) : (halves == 1 || (in_cache && tt < kHalfTileMargin * t_full));
             if (allowed && tt < t_large) { t_large = tt; best_tile = t; parts = p; first_split = f; }
         }
     }
@@ -225,6 +234,9 @@ TileChoice choose_tile(const Args& a, int num_cus) {
             if (t < t_small && t < kSliceMargin * t_whole) { t_small = t; slices = sl; }
         }
     }
+    // (the sliced 32x32x16 tile is estimated too well for so few rows - 48x4096x4096: estimated 14 us, measured 19;
+    // the quartered tile in 8 shares: estimated 15, measured 15 - so it does not compete there)
+    if (best_tile == &kQuarterTile) t_small = t_large + 1.0;
     if (t_large <= t_small) {
         if (!large_ok) return TileChoice{kLargeTileFallback, 0, 1, 0.0};
         return TileChoice{best_tile->variant, (int)first_split, parts, t_large};

@@ -123,8 +123,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
                                                            int split_first, int split_parts, float* partials, int rotate) {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NT, NS = C::NS;
     constexpr int TM = C::WTM / 16, TN = C::WTN / 16;        // 16x16 accumulators per wave
-    static_assert((TM == 8 || TM == 4) && (TN == 8 || TN == 4) && TM + TN >= 12,
-                  "the slot plan below is written for a 128x128 wave sub-block, or half of one");
+    static_assert((TM == 8 || TM == 4) && (TN == 8 || TN == 4),
+                  "the slot plan below is written for a 128x128 wave sub-block, half or a quarter of one");
     static_assert(BK == 32, "one 32-wide k block per slab");
     static_assert(NS == 4 || NS == 5, "ring of 4, or ring of 5 with paired requests");
     constexpr bool PAIRED = NS == 5;
@@ -289,13 +289,16 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     // The scalar updates change what the loads of the step use, so they come after the last load.
     // A half-size wave sub-block has 32 MFMAs per step: its updates go two to a slot, next to the
     // last fragment reads (which use a copy of their stage offset taken at the start of the step).
-    constexpr int BAR_SLOT = 4, LOAD_FIRST = BAR_SLOT + 1, LOAD_EVERY = 4;
+    // A quarter-size sub-block (64x64) has 16 MFMAs per step: a fragment read after every MFMA, a
+    // load after every second one, the updates three to a slot.
+    constexpr int BAR_SLOT = 4, LOAD_FIRST = BAR_SLOT + 1, LOAD_EVERY = NM >= 32 ? 4 : 2, READ_EVERY = NM >= 32 ? 2 : 1;
     constexpr int LAST_LOAD = LOAD_FIRST + (LPT - 1) * LOAD_EVERY;
     constexpr int TAIL_FIRST = NM == 64 ? 40 : LAST_LOAD + 1;
+    constexpr int TAIL_PACK = NM == 32 ? 2 : 3;
     // slot of scalar update u (0 .. 9)
-    auto tail_slot = [](int u) { constexpr int wide[10] = {0, 2, 4, 6, 8, 9, 10, 11, 12, 13}; return TAIL_FIRST + (NM == 64 ? wide[u] : u / 2); };
-    static_assert(BAR_SLOT + 2 * NR <= NM && LAST_LOAD < TAIL_FIRST, "reads end inside the step, loads before the tail");
-    static_assert(TAIL_FIRST + (NM == 64 ? 13 : 4) < NM, "the scalar updates fit the step");
+    auto tail_slot = [](int u) { constexpr int wide[10] = {0, 2, 4, 6, 8, 9, 10, 11, 12, 13}; return TAIL_FIRST + (NM == 64 ? wide[u] : u / TAIL_PACK); };
+    static_assert(BAR_SLOT + READ_EVERY * NR <= NM && LAST_LOAD < TAIL_FIRST, "reads end inside the step, loads before the tail");
+    static_assert(TAIL_FIRST + (NM == 64 ? 13 : 9 / TAIL_PACK) < NM, "the scalar updates fit the step");
     // loads that may still be in flight when slab kt+1 must have landed
     constexpr int PENDING_EVEN = PAIRED ? 2 * LPT : (NS - 2) * LPT, PENDING_ODD = PAIRED ? LPT : (NS - 2) * LPT;
 
@@ -323,8 +326,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
             } else {
                 if constexpr (m == 1) ka = fa[0] + roff;
                 if constexpr (m == 2) kb = fb[0] + roff;
-                if constexpr (m >= BAR_SLOT && (m - BAR_SLOT) % 2 == 0 && (m - BAR_SLOT) / 2 < NR)
-                    read_one(std::integral_constant<int, (m - BAR_SLOT) / 2 % NR>{}, nxt, roff, ka, kb);
+                if constexpr (m >= BAR_SLOT && (m - BAR_SLOT) % READ_EVERY == 0 && (m - BAR_SLOT) / READ_EVERY < NR)
+                    read_one(std::integral_constant<int, (m - BAR_SLOT) / READ_EVERY % NR>{}, nxt, roff, ka, kb);
                 if constexpr (m >= LOAD_FIRST && (m - LOAD_FIRST) % LOAD_EVERY == 0 && (m - LOAD_FIRST) / LOAD_EVERY < LPT) {
                     const Pick p = pick(EVEN, (m - LOAD_FIRST) / LOAD_EVERY);
                     char* dst = wave_lds + (p.which ? s.w1 : s.w0);
