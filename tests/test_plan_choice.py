@@ -40,7 +40,7 @@ def test_benchmark_configurations():
     assert plan_of("X3") == (TILE, big, 1)
     assert plan_of("X9") == (TILE, big, 1) and plan_of("X10") == (TILE, big, 1)
     # ... whereas one more tile column that is half full stays one call with a split trailing round
-    kernel, name, split = plan(8000, 8192 + 128, 8136, 0, 1)
+    kernel, name, split = plan(8192, 8192 + 128, 8192, 0, 1)
     assert (kernel, name) == (TILE, big) and split > 1
 
 
