@@ -50,6 +50,10 @@ def test_family_by_rows_and_weight_size():
     assert plan(33, 16384, 16384)[:2] == (TILE, "dma16p_128x256x32_w2x2_s5")
     assert plan(64, 16384, 16384, 0, 1) == (TILE, "dma16p_128x256x32_w2x2_s5", 4)
     assert plan(32, 4096, 4096)[0] == TILE                      # 32 MiB of weights
+    # up to 64 rows on cache-resident weights: the quartered 16x16x32 tile with its split
+    kernel, name, shares = plan(48, 4096, 4096, 0, 1)
+    assert (kernel, name) == (TILE, "dma16p_128x128x32_w2x2_s5") and shares > 1
+    assert plan(64, 1024, 1024)[1] == "dma16p_128x128x32_w2x2_s5" and plan(65, 1024, 1024)[1] != "dma16p_128x128x32_w2x2_s5"
     assert plan(16, 2048, 32768)[0] == TILE                     # too few column groups
     assert plan(16, 65536, 2048)[0] == TILE                     # short k
     assert plan(8, 8192, 8192, ta=1)[0] == TILE                 # A stored K x M
