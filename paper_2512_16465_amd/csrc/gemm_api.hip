@@ -73,7 +73,7 @@ constexpr Dma16Tile kWideTile{15, 128, 256, 0.0117, 10.0, 5.8e6, kMinSlabsPerPar
 // the tile for small grids with long k loops (48x4096x4096: 15 us in 8 shares against 19 on sliced 32x32x16 tiles).
 constexpr Dma16Tile kQuarterTile{16, 128, 128, 0.0082, 4.0, 5.0e6, 4};       // (its steps are short: 64x4096x512 11 us in 4 shares of 4 slabs, 14 whole)
 constexpr double kHalfTileMargin = 0.9, kUnfavouredHalfTile = 1.15;
-constexpr int64_t kQuarterTileRows = 64;
+constexpr int64_t kQuarterTileRows = 64, kQuarterTileLongK = 16384;
 
 // time of the k loops of a round whose tiles are cut in `parts`, plus the second kernel (us)
 double split_round_time(const Dma16Tile& t, int64_t tail, int parts, int64_t K, double live = 1.0) {
@@ -242,6 +242,15 @@ TileChoice choose_tile(const Args& a, int num_cus) {
         return TileChoice{best_tile->variant, (int)first_split, parts, t_large};
     }
     if (!small_ok) return TileChoice{kSmallTileFallback, 0, 1, 0.0};
+    // Where the 128x128 grid would be sliced along a long k, the quartered 16x16x32 tile with its own split does
+    // the same job 3 to 23 % faster (256x1024x32768: 31 against 38 us, 512x1024x16384: 29 against 33); with shorter
+    // k loops the sliced 32x32x16 tile stays ahead (128x1024x8192: 15 against 18).
+    if (slices > 1 && a.K >= kQuarterTileLongK && large_ok && (a.M + a.N) * a.K * 2 <= kLastLevelCacheBytes) {
+        int p = 1;
+        int64_t f = 0;
+        const double tq = dma16_time(kQuarterTile, a, cus, true, &p, &f);
+        if (p > 1) return TileChoice{kQuarterTile.variant, (int)f, p, tq};
+    }
     return TileChoice{slices == 1 && a.K <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, slices, t_small};
 }
 
