@@ -443,6 +443,22 @@ def test_few_rows_small_weight_automatic_choice(handle, M, N, K, tb):
     assert np.array_equal(decode_c(cfg, p.result_bits()), want)
 
 
+@pytest.mark.parametrize("M,N,K,tb", [(128, 264, 40960, 0), (200, 520, 16392, 1)])
+def test_long_k_on_few_tiles_takes_the_quarter_tile_with_its_split(handle, M, N, K, tb):
+    # a handful of 128 x 128 tiles with k of 16384 or more: the 16x16x32 tile of that size, its one round cut
+    # into shares along k (32 and 24 of them here, added up by the generic reduction), with partly filled tiles and
+    # a k that ends inside a slab.  Integers -> exact.
+    cfg = base_cfg(M, N, K, 0, tb, wl.BF16, wl.F32, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.F32)
+    inp, _ = wl.make_integer_inputs(cfg, 87, -2, 2)
+    print(f"long k {M}x{N}x{K}: oracle", flush=True)
+    want = oracle.decode(wl.F32, expected_bits_exact(cfg, inp))
+    p = DeviceProblem(cfg, inp)
+    p.run(handle)
+    kernel, variant, shares = lg.gemm_get_last_plan(handle)
+    assert kernel == lg.GEMM_KERNEL_MFMA_TILE and lg.gemm_variant_name(kernel, variant) == "dma16p_128x128x32_w2x2_s5" and shares > 1
+    assert np.array_equal(decode_c(cfg, p.result_bits()), want)
+
+
 def test_plan_query_agrees_with_the_plan_that_ran(handle):
     # the host-only query and the call itself go through the same choice
     cus = torch.cuda.get_device_properties(0).multi_processor_count

@@ -79,6 +79,11 @@ def test_tile_split_and_slices():
     assert (kernel, name) == (TILE, "dma16p_256x256x32_w2x2_s5") and shares > 1
     assert plan(2048, 4096, 4096) == (TILE, "dma16p_128x256x32_w2x2_s5", 1)
     assert plan(4096, 2048, 2048) == (TILE, "dma16p_256x128x32_w2x2_s5", 1)
+    # a few 128 x 128 tiles with k of 16384 or more: the 16x16x32 tile of that size with its split, not slices
+    for shape in ((256, 1024, 32768), (512, 1024, 16384), (128, 512, 65536)):
+        kernel, name, shares = plan(*shape)
+        assert (kernel, name) == (TILE, "dma16p_128x128x32_w2x2_s5") and shares > 1, shape
+    assert plan(128, 1024, 8192)[1] == small and plan(256, 1024, 8192)[1] == small
     # weights beyond the last-level cache stay on the full tile with its split
     assert plan(640, 16384, 16384)[1] == "dma16p_256x256x32_w2x2_s5"
     # batched calls: no split, no slices, no half tiles
