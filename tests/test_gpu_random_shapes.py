@@ -1,0 +1,70 @@
+"""GPU parity on seeded random calls in the automatic plan: shapes drawn around the tile edges (one
+below, on, one vector above), both layouts of each operand, all element types, padded leading
+dimensions, alpha / beta / bias / ReLU drawn per case.  Operands are small integers, so every
+partial sum is exact in fp32 and the result is unique: the library must match the oracle's value,
+rounded once to the output type, bit for bit, and must leave the padding columns of C alone."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2512_16465_amd as lg
+import workloads as wl
+from gpu_harness import DeviceProblem, c_bits_as_uint, expected_bits_exact
+
+pytestmark = pytest.mark.gpu
+
+ROWS = [1, 8, 31, 32, 33, 48, 64, 72, 128, 136, 200, 256, 264, 384, 520]
+COLS = [8, 24, 120, 128, 136, 256, 264, 512, 520, 1024, 1032]
+DEPTH = [8, 32, 40, 200, 256, 512, 1024, 2048, 4104, 8192, 16392]
+MAX_MACS = 3 << 28          # bounds the oracle's time per case (about a second)
+
+
+def draw_case(rng):
+    while True:
+        M, N, K = (int(rng.choice(ROWS)), int(rng.choice(COLS)), int(rng.choice(DEPTH)))
+        if M * N * K <= MAX_MACS:
+            break
+    ta, tb = int(rng.integers(2)), int(rng.integers(2))
+    dtype = int(rng.choice([wl.BF16, wl.BF16, wl.F16, wl.F32]))
+    out = dtype if rng.random() < 0.5 else wl.F32
+    pad = lambda: int(rng.choice([0, 0, 8, 24]))
+    a_cols, b_cols = (M if ta else K), (K if tb else N)
+    return wl.Config("random", M, N, K, ta, tb, dtype, out,
+                     alpha=float(rng.choice([1.0, 1.0, 2.0, -0.5])), beta=float(rng.choice([0.0, 0.0, 1.0, -2.0])),
+                     bias_dist=("normal", 1.0) if rng.random() < 0.4 else None, bias_dtype=wl.F32,
+                     act=int(rng.choice([wl.ACT_NONE, wl.ACT_NONE, wl.ACT_RELU])),
+                     lda=a_cols + pad(), ldb=b_cols + pad(), ldc=N + int(rng.choice([0, 0, 8, 5])))
+
+
+@pytest.fixture(scope="module")
+def handle():
+    h = lg.gemm_create()
+    yield h
+    lg.gemm_destroy(h)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_calls_match_the_oracle_exactly(handle, seed):
+    rng = np.random.default_rng([2718, seed])
+    seen = set()
+    for i in range(10):
+        cfg = draw_case(rng)
+        # K <= 16384 and |a|, |b| <= 2: |sum| <= 2^16, times |alpha| <= 2, plus |beta| * 4 + 8: far below 2^24
+        inp, _ = wl.make_integer_inputs(cfg, 100 * seed + i, -2, 2)
+        what = (f"seed {seed} case {i}: {cfg.M}x{cfg.N}x{cfg.K} ta={cfg.transA} tb={cfg.transB} dtype={cfg.dtype} out={cfg.out_dtype} "
+                f"ld=({cfg.ld_a()},{cfg.ld_b()},{cfg.ld_c()}) alpha={cfg.alpha} beta={cfg.beta} bias={cfg.bias_dist is not None} act={cfg.act}")
+        print(what, flush=True)
+        want = expected_bits_exact(cfg, inp)
+        p = DeviceProblem(cfg, inp)
+        before = p.result_bits().copy()
+        p.run(handle)
+        after = p.result_bits()
+        kernel, variant, split = lg.gemm_get_last_plan(handle)
+        seen.add((lg.gemm_variant_name(kernel, variant), split > 1))
+        got, ref = c_bits_as_uint(cfg, after), c_bits_as_uint(cfg, want.reshape(cfg.M, cfg.N))
+        # +0 and -0 are the same value (ReLU of a negative, a sum that cancels): compare values, then NaN-freeness
+        g, r = oracle.decode(cfg.out_dtype, got), oracle.decode(cfg.out_dtype, ref)
+        assert np.array_equal(g, r), f"{what}: {np.sum(g != r)} elements differ ({lg.gemm_variant_name(kernel, variant)}, split {split})"
+        if cfg.ld_c() > cfg.N and cfg.M > 1:
+            assert np.array_equal(before[:-1, cfg.N:].view(np.uint8), after[:-1, cfg.N:].view(np.uint8)), f"{what}: padding of C written"
+    assert len(seen) >= 3, seen       # the draw reaches several kernels
