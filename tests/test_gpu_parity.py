@@ -711,3 +711,48 @@ def test_batched_argument_errors_and_empty_batch(handle):
     assert lg.gemm_run_batched(**{**args, **ok, "batch": 0}) == lg.GEMM_OK
     torch.cuda.synchronize()
     assert np.array_equal(wl.torch_to_bits(p.C).view(np.uint8), before.view(np.uint8))
+
+
+# ------------------------------------------------------------------ handles, streams, workspace
+
+def test_two_handles_on_two_streams_and_a_growing_workspace(handle):
+    # Distinct handles own distinct workspaces and may run side by side on two streams; within one handle a call
+    # that needs more workspace than the calls before it waits for its stream, then replaces the buffer, while
+    # the other handle's work goes on.  Integer data -> every result exact.
+    other = lg.gemm_create()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    sliced = base_cfg(392, 328, 1096, 0, 1, wl.BF16, wl.F32)                   # 3 slices: 1.5 MiB of partial results
+    grown = base_cfg(1024, 1024, 1024, 0, 0, wl.BF16, wl.F32)                  # 16 slices: 64 MiB, beyond the first buffer
+    streamed = base_cfg(32, 2048, 4096, 0, 0, wl.BF16, wl.BF16)                # split-K of the streaming kernels
+    inputs = {id(c): wl.make_integer_inputs(c, 90 + i, -2, 2)[0] for i, c in enumerate((sliced, grown, streamed))}
+    wants = {id(c): oracle.decode(c.out_dtype, expected_bits_exact(c, inputs[id(c)])) for c in (sliced, grown, streamed)}
+    first = [DeviceProblem(sliced, inputs[id(sliced)]) for _ in range(6)]
+    beside = [DeviceProblem(streamed, inputs[id(streamed)]) for _ in range(6)]
+    big, last = DeviceProblem(grown, inputs[id(grown)]), DeviceProblem(sliced, inputs[id(sliced)])
+    torch.cuda.synchronize()
+    try:
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, 5, 3)
+        lg.gemm_set_plan(other, lg.GEMM_KERNEL_SKINNY, -1, 4)
+        for p, q in zip(first, beside):
+            with torch.cuda.stream(s1):
+                p.run(handle)
+            with torch.cuda.stream(s2):
+                q.run(other)
+        assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_MFMA_TILE, 5, 3) and lg.gemm_get_last_plan(other)[0] == lg.GEMM_KERNEL_SKINNY
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, 5, 16)
+        with torch.cuda.stream(s1):
+            big.run(handle)                      # the workspace grows with six launches queued ahead of it
+        assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_MFMA_TILE, 5, 16)
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, 5, 3)
+        with torch.cuda.stream(s1):
+            last.run(handle)
+        torch.cuda.synchronize()
+    finally:
+        lg.gemm_set_plan(handle)
+        torch.cuda.synchronize()
+        lg.gemm_destroy(other)
+    for p in first + [last]:
+        assert np.array_equal(decode_c(sliced, p.result_bits()), wants[id(sliced)])
+    for q in beside:
+        assert np.array_equal(decode_c(streamed, q.result_bits()), wants[id(streamed)])
+    assert np.array_equal(decode_c(grown, big.result_bits()), wants[id(grown)])
