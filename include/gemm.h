@@ -162,9 +162,10 @@ typedef struct {
     int32_t variant;        /* tile variant index within the family; -1 = automatic */
     int32_t split_k;        /* number of K slices; 0 = automatic, 1 = none.  Skinny family: every
                              * column group is cut into that many slices.  Macro-tile family, the
-                             * 256x256 tiles on the 16x16x32 MFMA: only the tiles of the last, partly
-                             * filled round of workgroups (all tiles when there are fewer tiles than
-                             * compute units) are cut, each into that many shares of the k range.
+                             * tiles on the 16x16x32 MFMA (256x256, 256x128, 128x256, 128x128): only
+                             * the tiles of the last, partly filled round of workgroups (all tiles when
+                             * there are fewer tiles than compute units) are cut, each into that many
+                             * shares of the k range (at most one share per 32-element slab).
                              * Every other tile variant: the whole product is cut into that many
                              * ranges of K (whole 32-element slabs; fewer if K has not enough of
                              * them), computed side by side into fp32 partial results and added by a
