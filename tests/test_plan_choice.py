@@ -118,3 +118,31 @@ def test_query_argument_errors():
     assert q(CUS, 1, 64, 64, 64, 0, 0, wl.BF16, wl.BF16, 63, 64, 64) == lg.GEMM_ERR_INVALID_ARG
     assert q(CUS, 1, 64, 64, 64, 2, 0, wl.BF16, wl.BF16, 64, 64, 64) == lg.GEMM_ERR_INVALID_ARG
     assert q(CUS, 1, 64, 64, 64, 0, 0, wl.BF16, wl.F16, 64, 64, 64) == lg.GEMM_ERR_UNSUPPORTED
+
+
+def test_invariants_over_random_shapes():
+    """Whatever the shape: a valid plan; the general kernel exactly when an operand cannot be read in 16-byte
+    vectors; the streaming kernels only for few rows of a row-major A; no split inside a batch."""
+    import random
+    rng = random.Random(5)
+    dims = [1, 7, 8, 24, 32, 33, 64, 100, 128, 136, 256, 520, 1024, 2056, 4096, 8192, 16384, 28672, 65536]
+    for _ in range(3000):
+        M, N, K = rng.choice(dims), rng.choice(dims), rng.choice(dims)
+        ta, tb = rng.randint(0, 1), rng.randint(0, 1)
+        dtype = rng.choice([wl.BF16, wl.F16, wl.F32])
+        out = rng.choice([dtype, wl.F32])
+        batch = rng.choice([1, 1, 1, 4])
+        pad = lambda: rng.choice([0, 0, 0, 8, 3])
+        lda, ldb, ldc = (M if ta else K) + pad(), (K if tb else N) + pad(), N + pad()
+        kernel, variant, split = lg.gemm_plan_query(CUS, batch, M, N, K, ta, tb, dtype, out, lda, ldb, ldc)
+        what = (batch, M, N, K, ta, tb, dtype, out, lda, ldb, ldc)
+        assert kernel in (TILE, SKINNY, GENERAL) and split >= 1, what
+        assert lg.gemm_variant_name(kernel, variant) is not None, what
+        vec = 4 if dtype == wl.F32 else 8
+        # rows of both operands start on 16-byte boundaries and hold whole vectors
+        loadable = lda % vec == 0 and ldb % vec == 0 and (M if ta else K) % vec == 0 and (K if tb else N) % vec == 0
+        assert (kernel == GENERAL) == (not loadable), what
+        if kernel == SKINNY:
+            assert M <= 32 and not ta and dtype != wl.F32, what
+        if batch > 1:
+            assert split == 1 or kernel == SKINNY, what
