@@ -241,7 +241,7 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
             ([&] {
                 slot(std::integral_constant<int, M>{}, std::false_type{});
                 constexpr int i = M / TN, j = (i & 1) ? TN - 1 - M % TN : M % TN;     // boustrophedon: consecutive MFMAs share an operand
-                mfma16<IS_BF16>(acc[i][j], ua[i], ub[j]);
+                mfma16<IS_BF16>(acc[i][j], ub[j], ua[i]);      // the block of C transposed: see the epilogue
                 slot(std::integral_constant<int, M>{}, std::true_type{});
             }(), ...);
         }
@@ -403,7 +403,9 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
         e.out_dtype = DT_F32; e.alpha = 1.0f; e.beta = 0.0f; e.bias = nullptr; e.act = ACT_NONE;
         em0 = 0; en0 = 0; c_vec_ok = 1;
     }
-    // accumulator register v of lane l: row 4*(l/16) + v, column l%16 of its 16x16 tile
+    // The MFMAs took B's fragment as their first operand, so each 16x16 accumulator holds its block
+    // of C transposed: register v of lane l is row l%16, column 4*(l/16) + v, and a lane's four
+    // registers are four consecutive columns, parked with one 16-byte LDS write.
     const int c16 = lane & 15, g4 = lane >> 4;
     tile_epilogue_bands<C>(
         [&](auto band, char* region) {
@@ -412,9 +414,7 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
             for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        *(float*)(region + ((16 * i2 + 4 * g4 + v) * EL::RS + j * 16 + c16) * 4) = acc[2 * b + i2][j][v];
+                    *(f32x4*)(region + ((16 * i2 + c16) * EL::RS + j * 16 + 4 * g4) * 4) = acc[2 * b + i2][j];
         },
         lds, e, em0, en0, c_vec_ok, live_rows);
 }
