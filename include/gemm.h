@@ -19,11 +19,14 @@
  *
  * All matrix and bias pointers are DEVICE pointers owned by the caller; the library never
  * allocates, frees or retains them.  gemm_run is asynchronous: it enqueues work on the given
- * HIP stream and returns without synchronising.  Nothing here throws, aborts or prints.
+ * HIP stream and returns without synchronising, in every case.  The one thing it may do besides
+ * launching kernels is grow the handle's split-K workspace with hipMalloc (see gemm_create and
+ * gemm_reserve_workspace); it never frees device memory.  Nothing here throws, aborts or prints.
  */
 #ifndef LIBGEMM_GEMM_H
 #define LIBGEMM_GEMM_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -71,9 +74,33 @@ typedef struct {
  * Creates a handle on the current HIP device.  The handle owns only a split-K workspace
  * (allocated on first need, grown on demand, freed by gemm_destroy).  Calls that use the handle
  * must be made with the same device current; otherwise they return GEMM_ERR_INVALID_ARG.
+ *
+ * Workspace rule.  A call whose plan splits K needs fp32 scratch for the partial results.  When
+ * the handle's buffer is too small, gemm_run allocates a larger one (hipMalloc, at least twice the
+ * old size, at least 32 MiB) and goes on; the old buffer is neither freed nor waited for, because
+ * work enqueued earlier may still be using it: it is kept by the handle until
+ * gemm_reserve_workspace or gemm_destroy.  A caller that cannot have hipMalloc inside gemm_run (a
+ * stream capture, a latency-critical loop) sizes the workspace once with gemm_reserve_workspace;
+ * calls that fit it allocate nothing.
  * Errors: GEMM_ERR_INVALID_ARG if out is NULL; GEMM_ERR_HIP if no device is usable.
  */
 gemm_status_t gemm_create(gemm_handle_t* out);
+
+/*
+ * Makes the handle's workspace at least `bytes` large and frees every buffer that an earlier growth
+ * set aside.  This is the one call besides gemm_destroy that frees device memory, and it may block:
+ * the caller must have synchronised every stream that used the handle.  The skinny family needs
+ * split_k * M * N * 4 bytes; the macro-tile family needs, for a split last round, (tiles in that
+ * round) * split_k * (tile rows * tile columns) * 4, and for k slices split_k * M * N * 4;
+ * 256 MiB covers every shape of the bench.  bytes == 0 only frees the set-aside buffers.
+ * Errors: GEMM_ERR_INVALID_ARG for a null handle or another current device; GEMM_ERR_ALLOC if the
+ * allocation failed (the old workspace stays); GEMM_ERR_HIP if freeing failed.
+ */
+gemm_status_t gemm_reserve_workspace(gemm_handle_t h, size_t bytes);
+
+/* Size in bytes of the handle's current workspace (0 before the first split-K call or reservation).
+ * Errors: GEMM_ERR_INVALID_ARG for null arguments. */
+gemm_status_t gemm_workspace_size(gemm_handle_t h, size_t* bytes);
 
 /*
  * Enqueues C = act(alpha*op(A)*op(B) + beta*C + bias) on `stream` (a hipStream_t passed as
@@ -99,7 +126,8 @@ gemm_status_t gemm_create(gemm_handle_t* out);
  *                         matrix pointer for a non-empty operand; an enum value out of range; a
  *                         current device other than the handle's.
  *   GEMM_ERR_UNSUPPORTED  out_dtype neither the input type nor GEMM_F32.
- *   GEMM_ERR_ALLOC        the split-K workspace could not be allocated.
+ *   GEMM_ERR_ALLOC        the split-K workspace could not be grown (hipMalloc failed, or it has
+ *                         been grown 48 times without a gemm_reserve_workspace in between).
  *   GEMM_ERR_HIP          a launch failed (the HIP error is consumed).
  *
  * A handle must not be used from two streams at once (they would share the workspace);
@@ -138,7 +166,7 @@ gemm_status_t gemm_run_batched(gemm_handle_t h, int64_t batch, int64_t M, int64_
                                float beta, void* C, int64_t ldc, int64_t strideC,
                                const gemm_epilogue_t* epilogue, void* stream);
 
-/* Frees the workspace and the handle.  The caller must have synchronised the streams that used
+/* Frees the workspace, the buffers set aside by earlier growth, and the handle.  The caller must have synchronised the streams that used
  * it.  NULL is accepted.  Errors: GEMM_ERR_HIP if freeing device memory failed. */
 gemm_status_t gemm_destroy(gemm_handle_t h);
 

@@ -22,6 +22,7 @@ GEMM_KERNEL_AUTO, GEMM_KERNEL_GENERAL, GEMM_KERNEL_MFMA_TILE, GEMM_KERNEL_SKINNY
 EXPORTED_SYMBOLS = (
     "gemm_create", "gemm_run", "gemm_run_batched", "gemm_destroy", "gemm_status_string",
     "gemm_set_plan", "gemm_get_last_plan", "gemm_variant_name", "gemm_plan_query",
+    "gemm_reserve_workspace", "gemm_workspace_size",
 )
 
 
@@ -75,6 +76,10 @@ def load_library() -> ctypes.CDLL:
     lib.gemm_plan_query.restype = ctypes.c_int
     lib.gemm_plan_query.argtypes = [ctypes.c_int32, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                     i64, i64, i64, ctypes.POINTER(gemm_plan_t)]
+    lib.gemm_reserve_workspace.restype = ctypes.c_int
+    lib.gemm_reserve_workspace.argtypes = [vp, ctypes.c_size_t]
+    lib.gemm_workspace_size.restype = ctypes.c_int
+    lib.gemm_workspace_size.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
     lib.gemm_variant_name.restype = ctypes.c_char_p
     lib.gemm_variant_name.argtypes = [ctypes.c_int, ctypes.c_int32]
     _lib = lib
@@ -98,6 +103,22 @@ def gemm_destroy(handle: int) -> None:
     st = load_library().gemm_destroy(ctypes.c_void_p(handle))
     if st != GEMM_OK:
         raise GemmError(st, "gemm_destroy")
+
+
+def gemm_reserve_workspace(handle: int, nbytes: int, check: bool = True) -> int:
+    """The caller must have synchronised the streams that used the handle."""
+    st = load_library().gemm_reserve_workspace(ctypes.c_void_p(handle), ctypes.c_size_t(nbytes))
+    if check and st != GEMM_OK:
+        raise GemmError(st, "gemm_reserve_workspace")
+    return st
+
+
+def gemm_workspace_size(handle: int) -> int:
+    n = ctypes.c_size_t()
+    st = load_library().gemm_workspace_size(ctypes.c_void_p(handle), ctypes.byref(n))
+    if st != GEMM_OK:
+        raise GemmError(st, "gemm_workspace_size")
+    return n.value
 
 
 def gemm_run(handle: int, M: int, N: int, K: int, transA: int, transB: int, dtype: int,

@@ -6,11 +6,18 @@
 
 #define GEMM_EXPORT extern "C" __attribute__((visibility("default")))
 
+// A workspace grows by at least doubling, so 48 replaced buffers cover any sequence of sizes.
+constexpr int kMaxRetired = 48;
+
 struct gemm_handle_s {
     int device;
     int num_cus;
     float* workspace;
     size_t workspace_bytes;
+    // Buffers that a larger one has replaced.  Work enqueued earlier may still use them, so they are
+    // kept until the caller vouches for the streams (gemm_reserve_workspace, gemm_destroy).
+    void* retired[kMaxRetired];
+    int num_retired;
     bool forced;
     gemm_plan_t plan;        // forced plan (valid when forced)
     gemm_plan_t last;        // plan of the last successful run
@@ -254,24 +261,32 @@ TileChoice choose_tile(const Args& a, int num_cus) {
     return TileChoice{slices == 1 && a.K <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, slices, t_small};
 }
 
-gemm_status_t ensure_workspace(gemm_handle_s* h, size_t bytes, hipStream_t stream) {
+// Makes the workspace at least `bytes` large without waiting for anything: a buffer that is too
+// small is set aside (launches already enqueued, on this or another stream, may still be using it)
+// and a new one of at least twice its size is allocated.
+gemm_status_t ensure_workspace(gemm_handle_s* h, size_t bytes) {
     if (bytes <= h->workspace_bytes) return GEMM_OK;
-    if (h->workspace) {
-        // earlier launches on the caller's stream may still read the old buffer
-        if (hipStreamSynchronize(stream) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_HIP; }
-        if (hipFree(h->workspace) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_HIP; }
-        h->workspace = nullptr;
-        h->workspace_bytes = 0;
-    }
+    if (h->workspace && h->num_retired >= kMaxRetired) return GEMM_ERR_ALLOC;
     size_t want = bytes < ((size_t)32 << 20) ? ((size_t)32 << 20) : bytes;
+    if (want < 2 * h->workspace_bytes) want = 2 * h->workspace_bytes;
     void* p = nullptr;
     if (hipMalloc(&p, want) != hipSuccess) {
         (void)hipGetLastError();
-        return GEMM_ERR_ALLOC;
+        if (want == bytes || hipMalloc(&p, bytes) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_ALLOC; }
+        want = bytes;
     }
+    if (h->workspace) h->retired[h->num_retired++] = h->workspace;
     h->workspace = (float*)p;
     h->workspace_bytes = want;
     return GEMM_OK;
+}
+
+gemm_status_t free_retired(gemm_handle_s* h) {
+    gemm_status_t st = GEMM_OK;
+    for (int i = 0; i < h->num_retired; ++i)
+        if (hipFree(h->retired[i]) != hipSuccess) { (void)hipGetLastError(); st = GEMM_ERR_HIP; }
+    h->num_retired = 0;
+    return st;
 }
 
 }  // namespace
@@ -292,6 +307,7 @@ GEMM_EXPORT gemm_status_t gemm_create(gemm_handle_t* out) {
     h->num_cus = cus > 0 ? cus : 256;
     h->workspace = nullptr;
     h->workspace_bytes = 0;
+    h->num_retired = 0;
     h->forced = false;
     h->plan = gemm_plan_t{GEMM_KERNEL_AUTO, -1, 0};
     h->last = gemm_plan_t{GEMM_KERNEL_AUTO, -1, 0};
@@ -301,13 +317,32 @@ GEMM_EXPORT gemm_status_t gemm_create(gemm_handle_t* out) {
 
 GEMM_EXPORT gemm_status_t gemm_destroy(gemm_handle_t h) {
     if (!h) return GEMM_OK;
-    gemm_status_t st = GEMM_OK;
+    gemm_status_t st = free_retired(h);
     if (h->workspace && hipFree(h->workspace) != hipSuccess) {
         (void)hipGetLastError();
         st = GEMM_ERR_HIP;
     }
     delete h;
     return st;
+}
+
+GEMM_EXPORT gemm_status_t gemm_reserve_workspace(gemm_handle_t h, size_t bytes) {
+    if (!h) return GEMM_ERR_INVALID_ARG;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return GEMM_ERR_HIP; }
+    if (dev != h->device) return GEMM_ERR_INVALID_ARG;
+    // the caller has synchronised: nothing uses the replaced buffers any more
+    gemm_status_t st = free_retired(h);
+    if (st != GEMM_OK) return st;
+    st = ensure_workspace(h, bytes);
+    if (st != GEMM_OK) return st;
+    return free_retired(h);
+}
+
+GEMM_EXPORT gemm_status_t gemm_workspace_size(gemm_handle_t h, size_t* bytes) {
+    if (!h || !bytes) return GEMM_ERR_INVALID_ARG;
+    *bytes = h->workspace_bytes;
+    return GEMM_OK;
 }
 
 GEMM_EXPORT const char* gemm_status_string(gemm_status_t s) {
@@ -364,7 +399,7 @@ gemm_status_t launch_plan(gemm_handle_s* h, const Args& a, gemm_plan_t& plan, in
         if (plan.split_k > max_split) plan.split_k = max_split;
         const size_t need = gemm::skinny_workspace_bytes(a, plan.split_k);
         if (need) {
-            const gemm_status_t st = ensure_workspace(h, need, stream);
+            const gemm_status_t st = ensure_workspace(h, need);
             if (st != GEMM_OK) return st;
         }
         // one matrix per launch (the slices of a split share the workspace, in stream order)
@@ -391,7 +426,7 @@ gemm_status_t launch_plan(gemm_handle_s* h, const Args& a, gemm_plan_t& plan, in
         }
         if (plan.split_k > 1 && slice_len > 0) {
             const int64_t len = slice_len;
-            const gemm_status_t st = ensure_workspace(h, (size_t)plan.split_k * (size_t)M * (size_t)N * sizeof(float), stream);
+            const gemm_status_t st = ensure_workspace(h, (size_t)plan.split_k * (size_t)M * (size_t)N * sizeof(float));
             if (st != GEMM_OK) return st;
             Args p = a;
             p.K = len; p.k_total = K;
@@ -406,7 +441,7 @@ gemm_status_t launch_plan(gemm_handle_s* h, const Args& a, gemm_plan_t& plan, in
             const gemm::TileVariantInfo* info = gemm::tile_variant_info(plan.variant);
             const int64_t tiles = ((a.M + info->BM - 1) / info->BM) * ((a.N + info->BN - 1) / info->BN);
             const size_t need = (size_t)(tiles - split_first) * plan.split_k * info->BM * info->BN * sizeof(float);
-            const gemm_status_t st = ensure_workspace(h, need, stream);
+            const gemm_status_t st = ensure_workspace(h, need);
             if (st != GEMM_OK) return st;
             split = gemm::TileSplit{split_first, plan.split_k, h->workspace};
             if (!allocate_only) e = gemm::launch_tile(a, plan.variant, kTileBandRows, split, stream);

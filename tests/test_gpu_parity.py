@@ -717,8 +717,8 @@ def test_batched_argument_errors_and_empty_batch(handle):
 
 def test_two_handles_on_two_streams_and_a_growing_workspace(handle):
     # Distinct handles own distinct workspaces and may run side by side on two streams; within one handle a call
-    # that needs more workspace than the calls before it waits for its stream, then replaces the buffer, while
-    # the other handle's work goes on.  Integer data -> every result exact.
+    # that needs more workspace than the calls before it takes a new buffer and leaves the old one to the
+    # launches queued ahead of it, while the other handle's work goes on.  Integer data -> every result exact.
     other = lg.gemm_create()
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
     sliced = base_cfg(392, 328, 1096, 0, 1, wl.BF16, wl.F32)                   # 3 slices: 1.5 MiB of partial results
@@ -756,3 +756,51 @@ def test_two_handles_on_two_streams_and_a_growing_workspace(handle):
     for q in beside:
         assert np.array_equal(decode_c(streamed, q.result_bits()), wants[id(streamed)])
     assert np.array_equal(decode_c(grown, big.result_bits()), wants[id(grown)])
+
+
+def test_a_growing_workspace_does_not_wait_for_the_stream(handle):
+    # gemm_run never synchronises: a call that needs a larger workspace than the handle holds returns while the
+    # work queued ahead of it (which uses the old buffer) is still running, and both results are exact.
+    h = lg.gemm_create()
+    queued = base_cfg(392, 328, 1096, 0, 1, wl.BF16, wl.F32)                   # 3 slices: uses the first (32 MiB) buffer
+    grown = base_cfg(1024, 1024, 1024, 0, 0, wl.BF16, wl.F32)                  # 16 slices: 64 MiB
+    filler = base_cfg(4096, 4096, 4096, 0, 1, wl.BF16, wl.BF16)                # ~0.1 ms each, no workspace
+    iq, ig = wl.make_integer_inputs(queued, 31, -2, 2)[0], wl.make_integer_inputs(grown, 32, -2, 2)[0]
+    want_q = oracle.decode(queued.out_dtype, expected_bits_exact(queued, iq))
+    want_g = oracle.decode(grown.out_dtype, expected_bits_exact(grown, ig))
+    pq, pg = DeviceProblem(queued, iq), DeviceProblem(grown, ig)
+    pf = DeviceProblem(filler, wl.make_integer_inputs(filler, 33, -1, 1)[0])
+    stream = torch.cuda.Stream()
+    done = torch.cuda.Event()
+    torch.cuda.synchronize()
+    try:
+        with torch.cuda.stream(stream):
+            lg.gemm_set_plan(h, lg.GEMM_KERNEL_MFMA_TILE, 5, 3)
+            pq.run(h)
+            assert lg.gemm_workspace_size(h) == 32 << 20
+            lg.gemm_set_plan(h)
+            for _ in range(300):                                               # some 30 ms of work on the stream
+                pf.run(h)
+            lg.gemm_set_plan(h, lg.GEMM_KERNEL_MFMA_TILE, 5, 3)
+            pq.run(h)                                                          # still on the first buffer
+            done.record(stream)
+            lg.gemm_set_plan(h, lg.GEMM_KERNEL_MFMA_TILE, 5, 16)
+            pg.run(h)
+            returned_early = not done.query()
+            assert lg.gemm_workspace_size(h) >= 64 << 20
+        torch.cuda.synchronize()
+        assert returned_early, "the growing call waited for the work queued ahead of it"
+        assert np.array_equal(decode_c(queued, pq.result_bits()), want_q)
+        assert np.array_equal(decode_c(grown, pg.result_bits()), want_g)
+        # with every stream idle, a reservation frees what the growth set aside and keeps the size
+        lg.gemm_reserve_workspace(h, 0)
+        assert lg.gemm_workspace_size(h) >= 64 << 20
+        lg.gemm_reserve_workspace(h, 200 << 20)
+        assert lg.gemm_workspace_size(h) >= 200 << 20
+        with torch.cuda.stream(stream):
+            pg.run(h)
+        torch.cuda.synchronize()
+        assert np.array_equal(decode_c(grown, pg.result_bits()), want_g)
+    finally:
+        torch.cuda.synchronize()
+        lg.gemm_destroy(h)
