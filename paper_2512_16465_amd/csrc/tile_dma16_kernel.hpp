@@ -162,8 +162,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     static_assert(LA::L % 2 == 0 && LB::L % 2 == 0, "a slab is requested in two halves");
     LA la;
     LB lb;
-    la.init(tid, a.lda);
-    lb.init(tid, a.ldb);
+    la.init(tid, a.lda, (int)(a.M - m0 < BM ? a.M - m0 : BM));
+    lb.init(tid, a.ldb, (int)(a.N - n0 < BN ? a.N - n0 : BN));
     const int64_t a_step = LA::k_step_bytes(a.lda), b_step = LB::k_step_bytes(a.ldb);
     const char* pa = LA::tile_base(a.A, m0, a.lda) + slab0 * a_step;
     const char* pb = LB::tile_base(a.B, n0, a.ldb) + slab0 * b_step;
@@ -291,13 +291,28 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     // last fragment reads (which use a copy of their stage offset taken at the start of the step).
     // A quarter-size sub-block (64x64) has 16 MFMAs per step: a fragment read after every MFMA, a
     // load after every second one, the updates three to a slot.
-    constexpr int BAR_SLOT = 4, LOAD_FIRST = BAR_SLOT + 1, LOAD_EVERY = NM >= 32 ? 4 : 2, READ_EVERY = NM >= 32 ? 2 : 1;
+#ifndef GEMM_DMA16_PIPELINED_TAIL
+#define GEMM_DMA16_PIPELINED_TAIL 1
+#endif
+#ifndef GEMM_DMA16_SPREAD
+#define GEMM_DMA16_SPREAD 1
+#endif
+    // Full sub-block (64 MFMAs per step): the 16 fragment reads are spread over the step, one after every
+    // third MFMA, and the loads go one after every sixth: four waves reading a kilobyte after every second
+    // MFMA would ask the LDS for all of its 128 bytes per clock for the first half of the step, on top of
+    // the slabs arriving from memory, and a wave whose read finds the LDS queue full stops issuing MFMAs.
+    constexpr bool SPREAD = GEMM_DMA16_SPREAD && NM == 64;
+    constexpr int BAR_SLOT = 4, LOAD_FIRST = BAR_SLOT + 1, LOAD_EVERY = SPREAD ? 6 : (NM >= 32 ? 4 : 2),
+                  READ_EVERY = SPREAD ? 3 : (NM >= 32 ? 2 : 1);
     constexpr int LAST_LOAD = LOAD_FIRST + (LPT - 1) * LOAD_EVERY;
-    constexpr int TAIL_FIRST = NM == 64 ? 40 : LAST_LOAD + 1;
+    constexpr int TAIL_FIRST = NM == 64 ? (SPREAD ? 50 : 40) : LAST_LOAD + 1;
     constexpr int TAIL_PACK = NM == 32 ? 2 : 3;
     // slot of scalar update u (0 .. 9)
-    auto tail_slot = [](int u) { constexpr int wide[10] = {0, 2, 4, 6, 8, 9, 10, 11, 12, 13}; return TAIL_FIRST + (NM == 64 ? wide[u] : u / TAIL_PACK); };
-    static_assert(BAR_SLOT + READ_EVERY * NR <= NM && LAST_LOAD < TAIL_FIRST, "reads end inside the step, loads before the tail");
+    auto tail_slot = [](int u) {
+        constexpr int wide[10] = {0, 2, 4, 6, 8, 9, 10, 11, 12, 13};
+        return TAIL_FIRST + (NM == 64 ? (SPREAD ? u : wide[u]) : u / TAIL_PACK);
+    };
+    static_assert(BAR_SLOT + READ_EVERY * (NR - 1) < NM && LAST_LOAD < TAIL_FIRST, "reads end inside the step, loads before the tail");
     static_assert(TAIL_FIRST + (NM == 64 ? 13 : 9 / TAIL_PACK) < NM, "the scalar updates fit the step");
     // loads that may still be in flight when slab kt+1 must have landed
     constexpr int PENDING_EVEN = PAIRED ? 2 * LPT : (NS - 2) * LPT, PENDING_ODD = PAIRED ? LPT : (NS - 2) * LPT;
@@ -314,7 +329,10 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
 
     // Steady state: every slab requested exists and lies wholly inside K; the k advance is the
     // loads' scalar offset, which the range check ignores (see load_to_lds_b128).
-    auto step_hot = [&](Sched& s, auto parity) {
+    // `da0`, `da1`, `db0`, `db1`: descriptors of A and B for the loads of the first and the second slab of
+    // the pair (the operands' own in the steady state).
+    auto step_hot = [&](Sched& s, auto parity, __amdgpu_buffer_rsrc_t da0, __amdgpu_buffer_rsrc_t da1, __amdgpu_buffer_rsrc_t db0,
+                        __amdgpu_buffer_rsrc_t db1) {
         constexpr bool EVEN = decltype(parity)::value == 0;
         constexpr int cur = EVEN ? 0 : 1, nxt = cur ^ 1;
         const uint32_t roff = EVEN ? s.r1 : s.r2;
@@ -331,8 +349,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
                 if constexpr (m >= LOAD_FIRST && (m - LOAD_FIRST) % LOAD_EVERY == 0 && (m - LOAD_FIRST) / LOAD_EVERY < LPT) {
                     const Pick p = pick(EVEN, (m - LOAD_FIRST) / LOAD_EVERY);
                     char* dst = wave_lds + (p.which ? s.w1 : s.w0);
-                    if (p.is_a) la.issue_at(p.i, ra0, dst, p.which ? s.sa1 : s.sa0);
-                    else lb.issue_at(p.i, rb0, dst + C::A_BYTES, p.which ? s.sb1 : s.sb0);
+                    if (p.is_a) la.issue_at(p.i, p.which ? da1 : da0, dst, p.which ? s.sa1 : s.sa0);
+                    else lb.issue_at(p.i, p.which ? db1 : db0, dst + C::A_BYTES, p.which ? s.sb1 : s.sb0);
                 }
                 if constexpr (!EVEN) {      // next pair of steps: everything moves on by two slabs
                     if constexpr (m == tail_slot(0)) s.r1 = advance2(s.r1);
@@ -381,10 +399,26 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
         Sched s{stage_off(1), stage_off(2), stage_off(4), stage_off(5), (uint32_t)(physical(4) * a_step), (uint32_t)(physical(5) * a_step),
                 (uint32_t)(physical(4) * b_step), (uint32_t)(physical(5) * b_step)};
         for (; kt + 1 + NS < full_tiles; kt += 2) {      // the two steps request slabs up to kt + 5
-            step_hot(s, Even{});
-            step_hot(s, Odd{});
+            step_hot(s, Even{}, ra0, ra0, rb0, rb0);
+            step_hot(s, Odd{}, ra0, ra0, rb0, rb0);
         }
-        for (; kt < k_tiles; kt += 2) {
+        if (GEMM_DMA16_PIPELINED_TAIL && k_tiles == full_tiles) {
+            // Whole slabs only: the last steps are steady-state steps too.  A slab past the end is
+            // requested through a descriptor of length zero: the load fetches nothing, but it is issued
+            // and completes in order like any other, so the wait counts of the steps (loads that may
+            // stay in flight behind the slab needed next) remain exact, and what it writes, if
+            // anything, goes to a stage that no later step reads.  The very last step also reads
+            // fragments of a slab that does not exist; nothing multiplies them.
+            const __amdgpu_buffer_rsrc_t ra_none = make_rsrc(pa, 0), rb_none = make_rsrc(pb, 0);
+            for (; kt < k_tiles; kt += 2) {
+                const bool has0 = kt + 4 < k_tiles, has1 = kt + 5 < k_tiles;
+                const __amdgpu_buffer_rsrc_t da0 = has0 ? ra0 : ra_none, da1 = has1 ? ra0 : ra_none;
+                const __amdgpu_buffer_rsrc_t db0 = has0 ? rb0 : rb_none, db1 = has1 ? rb0 : rb_none;
+                step_hot(s, Even{}, da0, da1, db0, db1);
+                if (kt + 1 < k_tiles) step_hot(s, Odd{}, da0, da1, db0, db1);
+            }
+        }
+        for (; kt < k_tiles; kt += 2) {                 // a partial last slab: per-slab descriptors, masks, full waits
             step_edge(kt, Even{});
             if (kt + 1 < k_tiles) step_edge(kt + 1, Odd{});
         }

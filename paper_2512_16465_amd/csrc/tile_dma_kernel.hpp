@@ -19,9 +19,11 @@
 //     row per lane) is read with two transposing loads ds_read_b64_tr_b16, in which lane j of a
 //     16-lane group supplies the address of row k0 + j/4, columns 4*(j%4).., and lane i receives
 //     column i of rows k0 .. k0+3.
-// Loads past the end of an operand return zero through the buffer descriptor's range check, so
-// edge tiles need no clamping; a partial last k slab masks the lanes whose chunk lies beyond K
-// (k-contiguous operands) by giving them an out-of-range offset.
+// Rows of a k-contiguous operand past its end return zero through the buffer descriptor's range
+// check; the chunks of an m/n-contiguous operand past the tile's last valid column are clamped to
+// the last valid chunk (the range check does not see the scalar k advance of the steady state); a
+// partial last k slab masks the lanes whose chunk lies beyond K (k-contiguous operands) by giving
+// them an out-of-range offset.
 #pragma once
 #include "tile_kernel.hpp"
 
@@ -71,7 +73,7 @@ struct DmaKC {
     static_assert(SLOTS % NT == 0, "slots must divide evenly over the threads");
     uint32_t voff[L];      // byte offset of this lane's chunk from the slab's first byte
 
-    __device__ __forceinline__ void init(int tid, int64_t ld) {
+    __device__ __forceinline__ void init(int tid, int64_t ld, int /*valid_rows*/) {
 #pragma unroll
         for (int i = 0; i < L; ++i) {
             const uint32_t S = i * NT + tid;                      // LDS slot this lane fills with load i
@@ -132,13 +134,18 @@ struct DmaMC {
     static_assert(SLOTS % NT == 0 && CPK % 16 == 0, "a k-row must be whole 256-byte windows");
     uint32_t voff[L];
 
-    __device__ __forceinline__ void init(int tid, int64_t ld) {
+    // `valid_rows`: rows (columns of the stored matrix) of this tile inside the operand, a multiple
+    // of 8.  Chunks beyond them would lie in the next stored row or, in the operand's last k-row,
+    // past its end, and the steady state's scalar k advance escapes the range check: such lanes fetch
+    // the tile's last valid chunk instead (their rows of the tile are never stored).
+    __device__ __forceinline__ void init(int tid, int64_t ld, int valid_rows) {
 #pragma unroll
         for (int i = 0; i < L; ++i) {
             const uint32_t S = i * NT + tid;
             const uint32_t k = S / CPK, cs = S % CPK;
             const uint32_t c = cs ^ mc_swizzle(k);
-            voff[i] = (uint32_t)((k * ld + c * 8) * 2);
+            const uint32_t c8 = (int)(c * 8 + 8) <= valid_rows ? c * 8 : (uint32_t)(valid_rows - 8);
+            voff[i] = (uint32_t)((k * ld + c8) * 2);
         }
     }
     __device__ __forceinline__ void issue(bool /*masked*/, int i, __amdgpu_buffer_rsrc_t rsrc, char* stage, int wave, int /*tid*/,
@@ -230,8 +237,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
     using LB = typename std::conditional<B_KC, DmaKC<BN, BK, NT>, DmaMC<BN, BK, NT>>::type;
     LA la;
     LB lb;
-    la.init(tid, a.lda);
-    lb.init(tid, a.ldb);
+    la.init(tid, a.lda, (int)(a.M - m0 < BM ? a.M - m0 : BM));
+    lb.init(tid, a.ldb, (int)(a.N - n0 < BN ? a.N - n0 : BN));
     const char* pa = LA::tile_base(a.A, m0, a.lda);
     const char* pb = LB::tile_base(a.B, n0, a.ldb);
     const int64_t a_step = LA::k_step_bytes(a.lda), b_step = LB::k_step_bytes(a.ldb);

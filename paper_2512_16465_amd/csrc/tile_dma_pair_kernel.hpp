@@ -48,8 +48,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma_pair_kernel(Args a, int tiles_
     static_assert(LA::L % 2 == 0 && LB::L % 2 == 0, "a slab is requested in two halves");
     LA la;
     LB lb;
-    la.init(tid, a.lda);
-    lb.init(tid, a.ldb);
+    la.init(tid, a.lda, (int)(a.M - m0 < BM ? a.M - m0 : BM));
+    lb.init(tid, a.ldb, (int)(a.N - n0 < BN ? a.N - n0 : BN));
     const char* pa = LA::tile_base(a.A, m0, a.lda);
     const char* pb = LB::tile_base(a.B, n0, a.ldb);
     const int64_t a_step = LA::k_step_bytes(a.lda), b_step = LB::k_step_bytes(a.ldb);
