@@ -40,7 +40,8 @@ typedef enum {
     GEMM_ERR_INVALID_ARG = 1,   /* null handle/pointer, negative size, small ld, unknown enum value */
     GEMM_ERR_UNSUPPORTED = 2,   /* a valid request outside what is built (see gemm_run) */
     GEMM_ERR_ALLOC = 3,         /* workspace allocation failed */
-    GEMM_ERR_HIP = 4            /* a HIP call or kernel launch failed */
+    GEMM_ERR_HIP = 4,           /* a HIP call or kernel launch failed */
+    GEMM_ERR_SCRATCH_LIMIT = 5  /* gemm_run_noalloc only: the plan needs more than GEMM_NOALLOC_SCRATCH_BYTES */
 } gemm_status_t;
 
 typedef enum { GEMM_OP_N = 0, GEMM_OP_T = 1 } gemm_op_t;
@@ -140,6 +141,31 @@ gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_t K,
                        const void* B, int64_t ldb,
                        float beta, void* C, int64_t ldc,
                        const gemm_epilogue_t* epilogue, void* stream);
+
+/*
+ * gemm_run for callers that cannot allocate device memory at all: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * bits in C as gemm_run; the one difference is where split-K partial results go: into a buffer of
+ * GEMM_NOALLOC_SCRATCH_BYTES that is part of the library's device image (each GPU the library runs
+ * on holds its copy from load until the process ends) instead of the handle's workspace.  The
+ * call never invokes hipMalloc, hipFree or any allocating routine.
+ *
+ * A call whose plan needs more scratch than that returns GEMM_ERR_SCRATCH_LIMIT before anything
+ * is launched, C untouched (the need per plan is stated at gemm_reserve_workspace: 32 rows on a
+ * 16384 x 16384 weight in four k slices take 8 MiB; a plan that does not split K takes none).
+ * Every call on one GPU shares that GPU's buffer, whatever the handle or stream: calls that may
+ * overlap in time on one GPU race on it and must be ordered by the caller (one stream, or events).
+ * The buffer keeps the last call's contents; the kernels write every partial result before the
+ * reduction reads it, so nothing needs clearing between calls.
+ * Errors otherwise as gemm_run (GEMM_ERR_ALLOC cannot occur).
+ */
+#define GEMM_NOALLOC_SCRATCH_BYTES (32u << 20)
+gemm_status_t gemm_run_noalloc(gemm_handle_t h, int64_t M, int64_t N, int64_t K,
+                               gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,
+                               float alpha, const void* A, int64_t lda,
+                               const void* B, int64_t ldb,
+                               float beta, void* C, int64_t ldc,
+                               const gemm_epilogue_t* epilogue, void* stream);
 
 /*
  * The same product for `batch` independent problems of one shape, whose matrices lie at constant

@@ -13,7 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgemm.so")
 
 # enums of include/gemm.h
-GEMM_OK, GEMM_ERR_INVALID_ARG, GEMM_ERR_UNSUPPORTED, GEMM_ERR_ALLOC, GEMM_ERR_HIP = 0, 1, 2, 3, 4
+GEMM_OK, GEMM_ERR_INVALID_ARG, GEMM_ERR_UNSUPPORTED, GEMM_ERR_ALLOC, GEMM_ERR_HIP, GEMM_ERR_SCRATCH_LIMIT = 0, 1, 2, 3, 4, 5
+GEMM_NOALLOC_SCRATCH_BYTES = 32 << 20
 GEMM_OP_N, GEMM_OP_T = 0, 1
 GEMM_F32, GEMM_F16, GEMM_BF16 = 0, 1, 2
 GEMM_ACT_NONE, GEMM_ACT_GELU_ERF, GEMM_ACT_RELU, GEMM_ACT_SILU, GEMM_ACT_GELU_TANH = 0, 1, 2, 3, 4
@@ -22,7 +23,7 @@ GEMM_KERNEL_AUTO, GEMM_KERNEL_GENERAL, GEMM_KERNEL_MFMA_TILE, GEMM_KERNEL_SKINNY
 EXPORTED_SYMBOLS = (
     "gemm_create", "gemm_run", "gemm_run_batched", "gemm_destroy", "gemm_status_string",
     "gemm_set_plan", "gemm_get_last_plan", "gemm_variant_name", "gemm_plan_query",
-    "gemm_reserve_workspace", "gemm_workspace_size",
+    "gemm_reserve_workspace", "gemm_workspace_size", "gemm_run_noalloc",
 )
 
 
@@ -65,6 +66,8 @@ def load_library() -> ctypes.CDLL:
     lib.gemm_run.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                              ctypes.c_float, vp, i64, vp, i64, ctypes.c_float, vp, i64,
                              ctypes.POINTER(gemm_epilogue_t), vp]
+    lib.gemm_run_noalloc.restype = ctypes.c_int
+    lib.gemm_run_noalloc.argtypes = lib.gemm_run.argtypes
     lib.gemm_run_batched.restype = ctypes.c_int
     lib.gemm_run_batched.argtypes = [vp, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_float, vp, i64, i64, vp, i64, i64, ctypes.c_float, vp, i64, i64,
@@ -133,6 +136,20 @@ def gemm_run(handle: int, M: int, N: int, K: int, transA: int, transB: int, dtyp
         ctypes.c_void_p(stream))
     if check and st != GEMM_OK:
         raise GemmError(st, "gemm_run")
+    return st
+
+
+def gemm_run_noalloc(handle: int, M: int, N: int, K: int, transA: int, transB: int, dtype: int,
+                     alpha: float, A: int, lda: int, B: int, ldb: int, beta: float, C: int, ldc: int,
+                     epilogue: Optional[gemm_epilogue_t] = None, stream: int = 0, check: bool = True) -> int:
+    """gemm_run with the split-K scratch in the library's static device buffer: allocates nothing."""
+    st = load_library().gemm_run_noalloc(
+        ctypes.c_void_p(handle), M, N, K, transA, transB, dtype, ctypes.c_float(alpha),
+        ctypes.c_void_p(A), lda, ctypes.c_void_p(B), ldb, ctypes.c_float(beta),
+        ctypes.c_void_p(C), ldc, ctypes.byref(epilogue) if epilogue is not None else None,
+        ctypes.c_void_p(stream))
+    if check and st != GEMM_OK:
+        raise GemmError(st, "gemm_run_noalloc")
     return st
 
 

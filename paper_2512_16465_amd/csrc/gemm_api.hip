@@ -9,6 +9,14 @@
 // A workspace grows by at least doubling, so 48 replaced buffers cover any sequence of sizes.
 constexpr int kMaxRetired = 48;
 
+// Split-K scratch of gemm_run_noalloc: device memory that exists from the moment the library is
+// loaded, so that entry point never allocates.  Every GPU holds its own copy at its own address;
+// the name below is only the host-side handle of the symbol, never an address to hand to a kernel:
+// gemm_create looks the address up once per device (scratch_of_device) and everything else uses that.
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+
 struct gemm_handle_s {
     int device;
     int num_cus;
@@ -18,6 +26,7 @@ struct gemm_handle_s {
     // kept until the caller vouches for the streams (gemm_reserve_workspace, gemm_destroy).
     void* retired[kMaxRetired];
     int num_retired;
+    float* scratch;          // this device's copy of the static split-K scratch
     bool forced;
     gemm_plan_t plan;        // forced plan (valid when forced)
     gemm_plan_t last;        // plan of the last successful run
@@ -281,6 +290,31 @@ gemm_status_t ensure_workspace(gemm_handle_s* h, size_t bytes) {
     return GEMM_OK;
 }
 
+// Address of the static scratch on `device`, which must be current; looked up on first use.
+gemm_status_t scratch_of_device(int device, float** out) {
+    static void* table[kMaxDevices];          // (written once per device; a race writes the same value twice)
+    if (device < 0 || device >= kMaxDevices) return GEMM_ERR_HIP;
+    if (!table[device]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return GEMM_ERR_HIP; }
+        table[device] = p;
+    }
+    *out = (float*)table[device];
+    return GEMM_OK;
+}
+
+// Where a call's partial results go: the handle's own buffer, which may grow, or the static scratch,
+// which may not.
+struct Workspace {
+    gemm_handle_s* h;
+    bool fixed;
+    float* ptr() const { return fixed ? h->scratch : h->workspace; }
+    gemm_status_t ensure(size_t bytes) const {
+        if (fixed) return bytes <= kScratchBytes ? GEMM_OK : GEMM_ERR_SCRATCH_LIMIT;
+        return ensure_workspace(h, bytes);
+    }
+};
+
 gemm_status_t free_retired(gemm_handle_s* h) {
     gemm_status_t st = GEMM_OK;
     for (int i = 0; i < h->num_retired; ++i)
@@ -308,6 +342,11 @@ GEMM_EXPORT gemm_status_t gemm_create(gemm_handle_t* out) {
     h->workspace = nullptr;
     h->workspace_bytes = 0;
     h->num_retired = 0;
+    h->scratch = nullptr;
+    {
+        const gemm_status_t st = scratch_of_device(dev, &h->scratch);
+        if (st != GEMM_OK) { delete h; return st; }
+    }
     h->forced = false;
     h->plan = gemm_plan_t{GEMM_KERNEL_AUTO, -1, 0};
     h->last = gemm_plan_t{GEMM_KERNEL_AUTO, -1, 0};
@@ -352,6 +391,7 @@ GEMM_EXPORT const char* gemm_status_string(gemm_status_t s) {
         case GEMM_ERR_UNSUPPORTED: return "unsupported combination";
         case GEMM_ERR_ALLOC: return "workspace allocation failed";
         case GEMM_ERR_HIP: return "HIP call or kernel launch failed";
+        case GEMM_ERR_SCRATCH_LIMIT: return "the call needs more split-K scratch than the static buffer of gemm_run_noalloc holds";
     }
     return "unknown status";
 }
@@ -389,7 +429,7 @@ namespace {
 // Launches the kernels of a plan for the (validated) call `a`; may lower plan.split_k to what the
 // call can take.  split_first: first tile of a split trailing round (macro-tile family).
 // allocate_only: stop after making the workspace large enough for the plan.
-gemm_status_t launch_plan(gemm_handle_s* h, const Args& a, gemm_plan_t& plan, int split_first, hipStream_t stream,
+gemm_status_t launch_plan(const Workspace& ws, const Args& a, gemm_plan_t& plan, int split_first, hipStream_t stream,
                           bool allocate_only = false) {
     const int64_t M = a.M, N = a.N, K = a.K, batch = a.batch;
     const int64_t in_bytes = gemm::elem_bytes(a.dtype);
@@ -399,7 +439,7 @@ gemm_status_t launch_plan(gemm_handle_s* h, const Args& a, gemm_plan_t& plan, in
         if (plan.split_k > max_split) plan.split_k = max_split;
         const size_t need = gemm::skinny_workspace_bytes(a, plan.split_k);
         if (need) {
-            const gemm_status_t st = ensure_workspace(h, need);
+            const gemm_status_t st = ws.ensure(need);
             if (st != GEMM_OK) return st;
         }
         // one matrix per launch (the slices of a split share the workspace, in stream order)
@@ -409,7 +449,7 @@ gemm_status_t launch_plan(gemm_handle_s* h, const Args& a, gemm_plan_t& plan, in
             one.A = (const char*)a.A + b * a.strideA * in_bytes;
             one.B = (const char*)a.B + b * a.strideB * in_bytes;
             one.C = (char*)a.C + b * a.strideC * gemm::elem_bytes(a.out_dtype);
-            e = gemm::launch_skinny(one, plan.split_k, h->workspace, stream);
+            e = gemm::launch_skinny(one, plan.split_k, ws.ptr(), stream);
         }
     } else if (plan.kernel == GEMM_KERNEL_MFMA_TILE) {
         gemm::TileSplit split{0, 1, nullptr};
@@ -426,24 +466,24 @@ gemm_status_t launch_plan(gemm_handle_s* h, const Args& a, gemm_plan_t& plan, in
         }
         if (plan.split_k > 1 && slice_len > 0) {
             const int64_t len = slice_len;
-            const gemm_status_t st = ensure_workspace(h, (size_t)plan.split_k * (size_t)M * (size_t)N * sizeof(float));
+            const gemm_status_t st = ws.ensure((size_t)plan.split_k * (size_t)M * (size_t)N * sizeof(float));
             if (st != GEMM_OK) return st;
             Args p = a;
             p.K = len; p.k_total = K;
             p.batch = plan.split_k;
             p.strideA = a.transA ? len * a.lda : len;
             p.strideB = a.transB ? len : len * a.ldb;
-            p.C = h->workspace; p.ldc = N; p.strideC = M * N;
+            p.C = ws.ptr(); p.ldc = N; p.strideC = M * N;
             p.out_dtype = gemm::DT_F32; p.alpha = 1.0f; p.beta = 0.0f; p.bias = nullptr; p.act = gemm::ACT_NONE;
             if (!allocate_only) e = gemm::launch_tile(p, plan.variant, kTileBandRows, split, stream);
-            if (!allocate_only && e == hipSuccess) e = gemm::launch_splitk_reduce(a, plan.split_k, h->workspace, stream);
+            if (!allocate_only && e == hipSuccess) e = gemm::launch_splitk_reduce(a, plan.split_k, ws.ptr(), stream);
         } else if (plan.split_k > 1) {
             const gemm::TileVariantInfo* info = gemm::tile_variant_info(plan.variant);
             const int64_t tiles = ((a.M + info->BM - 1) / info->BM) * ((a.N + info->BN - 1) / info->BN);
             const size_t need = (size_t)(tiles - split_first) * plan.split_k * info->BM * info->BN * sizeof(float);
-            const gemm_status_t st = ensure_workspace(h, need);
+            const gemm_status_t st = ws.ensure(need);
             if (st != GEMM_OK) return st;
-            split = gemm::TileSplit{split_first, plan.split_k, h->workspace};
+            split = gemm::TileSplit{split_first, plan.split_k, ws.ptr()};
             if (!allocate_only) e = gemm::launch_tile(a, plan.variant, kTileBandRows, split, stream);
             if (!allocate_only && e == hipSuccess) e = gemm::launch_tile_split_reduce(a, plan.variant, kTileBandRows, split, stream);
         } else if (!allocate_only) {
@@ -541,7 +581,7 @@ AutoPlan automatic_plan(const Args& a, int num_cus, bool batch_aligned) {
 // Largest number of matrices one launch takes (the y dimension of a grid).
 constexpr int64_t kMaxBatchPerLaunch = 65535;
 
-gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, int64_t K,
+gemm_status_t run_batch(gemm_handle_t h, bool fixed_scratch, int64_t batch, int64_t M, int64_t N, int64_t K,
                         gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,
                         float alpha, const void* A, int64_t lda, int64_t strideA,
                         const void* B, int64_t ldb, int64_t strideB,
@@ -578,7 +618,7 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
         const int64_t ea = gemm::elem_bytes((int)dtype), ec = gemm::elem_bytes((int)epi.out_dtype);
         for (int64_t b0 = 0; b0 < batch; b0 += kMaxBatchPerLaunch) {
             const int64_t nb = batch - b0 < kMaxBatchPerLaunch ? batch - b0 : kMaxBatchPerLaunch;
-            const gemm_status_t st = run_batch(h, nb, M, N, K, transA, transB, dtype, alpha,
+            const gemm_status_t st = run_batch(h, fixed_scratch, nb, M, N, K, transA, transB, dtype, alpha,
                                                A ? (const char*)A + b0 * strideA * ea : nullptr, lda, strideA,
                                                B ? (const char*)B + b0 * strideB * ea : nullptr, ldb, strideB, beta,
                                                (char*)C + b0 * strideC * ec, ldc, strideC, epilogue, stream_);
@@ -588,6 +628,7 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
     }
 
     hipStream_t stream = (hipStream_t)stream_;
+    const Workspace ws{h, fixed_scratch};
     Args a;
     a.M = M; a.N = N; a.K = K;
     a.transA = transA == GEMM_OP_T; a.transB = transB == GEMM_OP_T;
@@ -644,11 +685,11 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
         if (ap.peeled) {
             gemm_plan_t pm = ap.plan, pr = ap.rest_plan;
             // the workspace of both parts first: a failed allocation must leave C untouched
-            gemm_status_t st = launch_plan(h, ap.main_part, pm, ap.split_first, stream, true);
-            if (st == GEMM_OK) st = launch_plan(h, ap.rest, pr, ap.rest_split_first, stream, true);
+            gemm_status_t st = launch_plan(ws, ap.main_part, pm, ap.split_first, stream, true);
+            if (st == GEMM_OK) st = launch_plan(ws, ap.rest, pr, ap.rest_split_first, stream, true);
             if (st != GEMM_OK) return st;
-            st = launch_plan(h, ap.main_part, pm, ap.split_first, stream);
-            if (st == GEMM_OK) st = launch_plan(h, ap.rest, pr, ap.rest_split_first, stream);
+            st = launch_plan(ws, ap.main_part, pm, ap.split_first, stream);
+            if (st == GEMM_OK) st = launch_plan(ws, ap.rest, pr, ap.rest_split_first, stream);
             if (st != GEMM_OK) return st;
             h->last = pm;         // the plan of the whole tiles
             return GEMM_OK;
@@ -656,7 +697,7 @@ gemm_status_t run_batch(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, in
     }
 
     // ---- launch ----
-    const gemm_status_t st = launch_plan(h, a, plan, split_first, stream);
+    const gemm_status_t st = launch_plan(ws, a, plan, split_first, stream);
     if (st != GEMM_OK) return st;
     h->last = plan;
     return GEMM_OK;
@@ -699,7 +740,16 @@ GEMM_EXPORT gemm_status_t gemm_run(gemm_handle_t h, int64_t M, int64_t N, int64_
                                    const void* B, int64_t ldb,
                                    float beta, void* C, int64_t ldc,
                                    const gemm_epilogue_t* epilogue, void* stream) {
-    return run_batch(h, 1, M, N, K, transA, transB, dtype, alpha, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, epilogue, stream);
+    return run_batch(h, false, 1, M, N, K, transA, transB, dtype, alpha, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, epilogue, stream);
+}
+
+GEMM_EXPORT gemm_status_t gemm_run_noalloc(gemm_handle_t h, int64_t M, int64_t N, int64_t K,
+                                           gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype,
+                                           float alpha, const void* A, int64_t lda,
+                                           const void* B, int64_t ldb,
+                                           float beta, void* C, int64_t ldc,
+                                           const gemm_epilogue_t* epilogue, void* stream) {
+    return run_batch(h, true, 1, M, N, K, transA, transB, dtype, alpha, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, epilogue, stream);
 }
 
 GEMM_EXPORT gemm_status_t gemm_run_batched(gemm_handle_t h, int64_t batch, int64_t M, int64_t N, int64_t K,
@@ -708,6 +758,6 @@ GEMM_EXPORT gemm_status_t gemm_run_batched(gemm_handle_t h, int64_t batch, int64
                                            const void* B, int64_t ldb, int64_t strideB,
                                            float beta, void* C, int64_t ldc, int64_t strideC,
                                            const gemm_epilogue_t* epilogue, void* stream) {
-    return run_batch(h, batch, M, N, K, transA, transB, dtype, alpha, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC,
+    return run_batch(h, false, batch, M, N, K, transA, transB, dtype, alpha, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC,
                      epilogue, stream);
 }
