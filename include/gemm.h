@@ -16,6 +16,9 @@
  *   C is M x N, C(i,j) = C[i*ldc + j], ldc >= N.
  * Products are accumulated in fp32 (bf16 x bf16 and fp16 x fp16 products are exact), the
  * epilogue runs in fp32, and the result is rounded once, to nearest-even, into the type of C.
+ * IEEE special values behave as in that arithmetic: subnormal inputs are multiplied (not flushed
+ * to zero), fp32 results below the normal range stay subnormal, a result beyond the largest
+ * finite value of the type of C becomes an infinity, Inf times zero is a NaN.
  *
  * All matrix and bias pointers are DEVICE pointers owned by the caller; the library never
  * allocates, frees or retains them.  gemm_run is asynchronous: it enqueues work on the given

@@ -150,3 +150,47 @@ def test_operand_beyond_two_gib(handle):
     assert np.array_equal(got, ref), f"{np.sum(got != ref)} elements differ in the sampled rows"
     # every element is a finite integer (no row or tile was skipped)
     assert bool(torch.all(C == torch.round(C)))
+
+
+def test_batched_full_config_x8(handle):
+    """The strided batch of the bench (32 per-head products 2048 x 2048 x 128) at full size, in the automatic plan:
+    a stratified sample of every matrix against the oracle, the same call twice gives the same bits, and on
+    integer data every matrix satisfies the sign-vector identities exactly."""
+    cfg = ALL["X8"]
+
+    def run(c, inp):
+        dev = torch.device("cuda:0")
+        A, B = wl.bits_to_torch(inp["A"], c.dtype, dev), wl.bits_to_torch(inp["B"], c.dtype, dev)
+        tdt = {wl.F32: torch.float32, wl.F16: torch.float16, wl.BF16: torch.bfloat16}[c.out_dtype]
+        C = torch.full((c.batch * c.M * c.ld_c(),), float("nan"), dtype=tdt, device=dev)
+        lg.gemm_run_batched(handle, c.batch, c.M, c.N, c.K, c.transA, c.transB, c.dtype, c.alpha, A.data_ptr(), c.ld_a(),
+                            c.stride_a(), B.data_ptr(), c.ld_b(), c.stride_b(), c.beta, C.data_ptr(), c.ld_c(), c.stride_c(),
+                            lg.make_epilogue(c.out_dtype), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        return wl.torch_to_bits(C).reshape(c.batch, c.M, c.ld_c())
+
+    print("X8: gaussian batch", flush=True)
+    inp = wl.make_inputs(cfg)
+    bits = run(cfg, inp)
+    assert lg.gemm_get_last_plan(handle)[0] == lg.GEMM_KERNEL_MFMA_TILE
+    one = wl.scaled(cfg, batch=1)
+    for b in range(cfg.batch):
+        sub = {"A": inp["A"][b * cfg.stride_a():(b + 1) * cfg.stride_a()], "B": inp["B"][b * cfg.stride_b():(b + 1) * cfg.stride_b()],
+               "C": None, "bias": None}
+        rows, cols = wl.sample_indices(cfg.M, cfg.N, wl.DEFAULT_SEED + b, grid=16)
+        ref, _, mag = oracle.gemm_at(oracle_problem(one, sub), rows, cols)
+        got = oracle.decode(cfg.out_dtype, np.ascontiguousarray(bits[b][rows, cols]))
+        from gpu_harness import assert_close
+        assert_close(one, got, ref, mag, f"X8 matrix {b}")
+    again = run(cfg, inp)
+    assert np.array_equal(bits.view(np.uint8), again.view(np.uint8)), "X8: two runs differ"
+    print("X8: integer batch", flush=True)
+    icfg = wl.scaled(cfg, out_dtype=wl.F32)
+    iinp, vals = wl.make_integer_inputs(icfg, 2026, -1, 1)
+    C = run(icfg, iinp)
+    ione = wl.scaled(icfg, batch=1)
+    for b in range(cfg.batch):
+        v = {"A": vals["A"][b * cfg.M:(b + 1) * cfg.M], "B": vals["B"][b * cfg.N:(b + 1) * cfg.N], "C": None}
+        sub = {"A": iinp["A"][b * cfg.stride_a():(b + 1) * cfg.stride_a()], "B": iinp["B"][b * cfg.stride_b():(b + 1) * cfg.stride_b()],
+               "C": None, "bias": None}
+        check_integer_result(ione, sub, v, C[b][:, : cfg.N])
