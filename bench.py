@@ -54,11 +54,12 @@ def measured_traffic(name: str):
 
 def classify(cfg) -> str:
     """The paper's roofline rule (Section 4.3): left of the ridge of the slowest unit (fp32
-    vector ALUs) is memory-bound, right of the ridge of the fastest unit (matrix cores) is
-    compute-bound, in between is the middle zone."""
+    vector ALUs) is memory-bound, right of the ridge of the fastest unit that can do the work (the
+    matrix cores for the operand type) is compute-bound, in between is the middle zone."""
+    import workloads as wl
     ai = cfg.flops() / cfg.algorithmic_bytes()
     low = FP32_VECTOR_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
-    high = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
+    high = (FP32_MFMA_PEAK_TFLOPS if cfg.dtype == wl.F32 else MFMA_BF16_PEAK_TFLOPS) * 1e12 / (HBM_PEAK_GBPS * 1e9)
     return "memory-bound" if ai < low else ("compute-bound" if ai > high else "middle-zone")
 
 
@@ -176,7 +177,8 @@ def quick_verify(res: Resident, lg, handle):
 
 
 def cpu_baseline(res: Resident, target_seconds: float = 12.0):
-    """The oracle as it stands, on the host cores, over whole rows of C of the same workload."""
+    """The oracle as it stands, on the host cores, over whole rows of C of the same workload (of the
+    first matrix of a batch); the time for the whole workload is a projection from that sample."""
     import oracle
     cfg = res.cfg
     inp = res.host_inputs
@@ -194,7 +196,8 @@ def cpu_baseline(res: Resident, target_seconds: float = 12.0):
     flops = 2.0 * nrows * cfg.N * cfg.K
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "sample": f"rows 0..{nrows - 1} of C ({nrows} x {cfg.N} outputs, K={cfg.K}) in {dt:.1f} s; "
-                      f"projected full matrix {dt * cfg.M / nrows:.0f} s"}
+                      f"projected whole workload {dt * cfg.M * cfg.batch / nrows:.1f} s",
+            "projected_seconds": dt * cfg.M * cfg.batch / nrows}
 
 
 def main():
@@ -202,16 +205,20 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5,X6,X7,X8,X11",
+    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5,X6,X7,X8,X11,G1,G2,G3,G4,G5,G6",
                     help="first one is the headline workload; X* are the further shapes of workloads.EXTRA_CONFIGS")
     ap.add_argument("--settle-ms", type=float, default=80.0,
                     help="the warm-up keeps launching until this much time has passed (clock ramp after idle); 0 = exactly --warmup launches")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time spent on the headline workload")
+    ap.add_argument("--cpu-seconds-other", type=float, default=1.0,
+                    help="oracle time spent on each further configuration (a projection from a few rows of C); 0 = none")
     ap.add_argument("--no-verify", action="store_true")
     ap.add_argument("--kernel", type=int, default=0, help="force a kernel family (gemm_kernel_t); 0 = automatic")
     ap.add_argument("--variant", type=int, default=-1, help="tile variant when --kernel is forced")
     ap.add_argument("--split-k", type=int, default=0, help="split-K factor when --kernel is forced; 0 = automatic")
+    ap.add_argument("--library", default="", help="path of another build of libgemm.so to measure (see paper_2512_16465_amd/build.py --output)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device-to-device copy (3 times) so that a counter run can scale "
                          "FETCH_SIZE / WRITE_SIZE by what they read for a transfer of known size")
@@ -229,6 +236,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.library:
+        import paper_2512_16465_amd.binding as binding
+        binding.LIB_PATH = os.path.abspath(args.library)
     lg.load_library()          # fails loudly when the HIP library is not built
     seed = wl.DEFAULT_SEED if args.seed is None else args.seed
     if args.copy_calibration:
@@ -270,6 +280,8 @@ def main():
             "ms_per_step": wall_ms, "launch_ms_mean": ev_mean, "launch_ms_min": ev_min, "launch_ms_std": ev_std,
             "tflops": tflops, "algorithmic_gbps": gbps, "verified_sample": ok, "warmup_launches": warm_done, "roofline": roof,
         }
+        if idx > 0 and not args.no_cpu_baseline and args.cpu_seconds_other > 0:
+            results[name]["cpu_baseline"] = cpu_baseline(res, args.cpu_seconds_other)
         if idx == 0:
             headline = (name, cfg, res, wall_ms, tflops, roof)
         else:
@@ -279,13 +291,17 @@ def main():
     name, cfg, res, wall_ms, tflops, roof = headline
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(res)
+        cpu = cpu_baseline(res, args.cpu_seconds)
     torch.cuda.synchronize()
     lg.gemm_destroy(handle)
     line = {
         "metric": "gemm_tflops_bf16_8192cubed" if name == "C3" else f"gemm_tflops_{name}",
-        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        # launches before the timed region: at least --warmup, then as many as fill --settle-ms (clock ramp)
+        "warmup": results[name]["warmup_launches"], "warmup_requested": args.warmup, "settle_ms": args.settle_ms,
         "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "clocks": {"value, ms_per_step, tflops, algorithmic_gbps": "host wall clock around the timed launches, between two device synchronisations",
+                   "roofline.achieved, launch_ms_*": "HIP events on the launch stream around the same number of launches"},
         "dtype": "bf16" if cfg.dtype == wl.BF16 else ("f16" if cfg.dtype == wl.F16 else "f32"),
         "data": "synthetic",
         "config": {"workload": f"{name}: {cfg.note}", "M": cfg.M, "N": cfg.N, "K": cfg.K,

@@ -209,9 +209,11 @@ typedef enum {
     GEMM_KERNEL_AUTO = 0,      /* let the library choose (default) */
     GEMM_KERNEL_GENERAL = 1,   /* one thread per output element, any shape/alignment */
     GEMM_KERNEL_MFMA_TILE = 2, /* LDS-staged macro-tile kernel on MFMA */
-    GEMM_KERNEL_SKINNY = 3     /* small-M (M <= 64) streaming kernels with split-K: variant 0 for a row-major
-                                  B (K x N), variant 1 for B stored N x K; the layout of the call
-                                  decides, a variant forced against it is GEMM_ERR_UNSUPPORTED */
+    GEMM_KERNEL_SKINNY = 3     /* streaming kernels with split-K for few rows of C.  bf16 / fp16, M <= 64: variant 0
+                                  for a row-major B (K x N), variant 1 for B stored N x K (an A stored K x M is first
+                                  gathered into a row-major copy in the workspace).  fp32, M <= 8, A row-major:
+                                  variants 2 and 3, the same two layouts on the vector ALUs.  The layout and type
+                                  of the call decide; a variant forced against them is GEMM_ERR_UNSUPPORTED */
 } gemm_kernel_t;
 
 typedef struct {
@@ -252,6 +254,23 @@ gemm_status_t gemm_get_last_plan(gemm_handle_t h, gemm_plan_t* out);
 gemm_status_t gemm_plan_query(int32_t compute_units, int64_t batch, int64_t M, int64_t N, int64_t K,
                               gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype, gemm_dtype_t out_dtype,
                               int64_t lda, int64_t ldb, int64_t ldc, gemm_plan_t* out);
+
+/*
+ * The roofline rule of the paper (Section 4.3) that the automatic choice starts from.  A call is
+ * placed by its arithmetic intensity, 2*M*N*K*batch flop over the bytes of one pass over every
+ * operand (A, B, C written, C read if `reads_c`, the bias if `has_bias`), against two ridge points of
+ * the MI355X roofline at 8 TB/s: 19.7 flop/byte, where the fp32 vector ALUs (157.3 TFLOP/s) meet the
+ * memory roof, and the ridge of the matrix cores for the operand type (bf16, fp16: 2.5 PFLOP/s ->
+ * 312.5; fp32: 157.3 TFLOP/s -> 19.7).  Left of the first: memory-bound, the streaming kernels are
+ * candidates and bytes per second is the objective; right of the second: compute-bound, matrix-core
+ * tiles only; in between: middle zone, both families compete and measured thresholds decide.
+ * Host arithmetic only.  `intensity` may be NULL.
+ * Errors: GEMM_ERR_INVALID_ARG for a null `cls`, sizes below 1 or an unknown enum.
+ */
+typedef enum { GEMM_MEMORY_BOUND = 0, GEMM_MIDDLE_ZONE = 1, GEMM_COMPUTE_BOUND = 2 } gemm_roofline_t;
+gemm_status_t gemm_roofline_class(int64_t batch, int64_t M, int64_t N, int64_t K, gemm_dtype_t dtype, gemm_dtype_t out_dtype,
+                                  int32_t reads_c, int32_t has_bias, gemm_dtype_t bias_dtype, gemm_roofline_t* cls,
+                                  double* intensity);
 
 /* Name of a tile variant of a family (static storage), or NULL if the index is out of range.
  * Lets a harness enumerate variants: loop until NULL. */

@@ -19,11 +19,12 @@ GEMM_OP_N, GEMM_OP_T = 0, 1
 GEMM_F32, GEMM_F16, GEMM_BF16 = 0, 1, 2
 GEMM_ACT_NONE, GEMM_ACT_GELU_ERF, GEMM_ACT_RELU, GEMM_ACT_SILU, GEMM_ACT_GELU_TANH = 0, 1, 2, 3, 4
 GEMM_KERNEL_AUTO, GEMM_KERNEL_GENERAL, GEMM_KERNEL_MFMA_TILE, GEMM_KERNEL_SKINNY = 0, 1, 2, 3
+GEMM_MEMORY_BOUND, GEMM_MIDDLE_ZONE, GEMM_COMPUTE_BOUND = 0, 1, 2
 
 EXPORTED_SYMBOLS = (
     "gemm_create", "gemm_run", "gemm_run_batched", "gemm_destroy", "gemm_status_string",
     "gemm_set_plan", "gemm_get_last_plan", "gemm_variant_name", "gemm_plan_query",
-    "gemm_reserve_workspace", "gemm_workspace_size", "gemm_run_noalloc",
+    "gemm_reserve_workspace", "gemm_workspace_size", "gemm_run_noalloc", "gemm_roofline_class",
 )
 
 
@@ -83,6 +84,9 @@ def load_library() -> ctypes.CDLL:
     lib.gemm_reserve_workspace.argtypes = [vp, ctypes.c_size_t]
     lib.gemm_workspace_size.restype = ctypes.c_int
     lib.gemm_workspace_size.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.gemm_roofline_class.restype = ctypes.c_int
+    lib.gemm_roofline_class.argtypes = [i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
+                                        ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)]
     lib.gemm_variant_name.restype = ctypes.c_char_p
     lib.gemm_variant_name.argtypes = [ctypes.c_int, ctypes.c_int32]
     _lib = lib
@@ -201,6 +205,17 @@ def gemm_plan_query(compute_units: int, batch: int, M: int, N: int, K: int, tran
             raise GemmError(st, "gemm_plan_query")
         return st
     return plan.kernel, plan.variant, plan.split_k
+
+
+def gemm_roofline_class(batch: int, M: int, N: int, K: int, dtype: int, out_dtype: int, reads_c: bool = False,
+                        bias_dtype: Optional[int] = None):
+    """(class, arithmetic intensity in flop/byte) by the roofline rule of Section 4.3; host only."""
+    cls, ai = ctypes.c_int(), ctypes.c_double()
+    st = load_library().gemm_roofline_class(batch, M, N, K, dtype, out_dtype, int(bool(reads_c)), int(bias_dtype is not None),
+                                            bias_dtype if bias_dtype is not None else 0, ctypes.byref(cls), ctypes.byref(ai))
+    if st != GEMM_OK:
+        raise GemmError(st, "gemm_roofline_class")
+    return cls.value, ai.value
 
 
 def gemm_variant_name(kernel: int, variant: int) -> Optional[str]:

@@ -2,6 +2,9 @@
 
     python -m paper_2512_16465_amd.build            # compile what changed, link
     python -m paper_2512_16465_amd.build --force    # recompile everything
+    python -m paper_2512_16465_amd.build --define NAME=VALUE [--define ...] --output /some/where/libgemm_x.so
+        # a second build with compile-time switches of the kernels set differently (for A/B measurements:
+        # bench.py --library loads it); its objects go to a directory next to the output
 
 Objects go to paper_2512_16465_amd/_build/ (not tracked); the shared library lands next to
 this file so that it travels with the source tree.
@@ -40,7 +43,7 @@ def _tile_variant_indices():
 def _units():
     """(source, object, extra flags) for every translation unit."""
     units = []
-    for name in ("gemm_api.hip", "general_kernel.hip", "skinny_kernel.hip", "tile_dispatch.hip"):
+    for name in ("gemm_api.hip", "general_kernel.hip", "skinny_kernel.hip", "gemv_f32_kernel.hip", "tile_dispatch.hip"):
         units.append((os.path.join(CSRC, name), os.path.join(OBJ, name.replace(".hip", ".o")), []))
     for i in _tile_variant_indices():      # one small source file per variant of tile_variants.def
         units.append((os.path.join(CSRC, f"tile_variant_{i}.hip"), os.path.join(OBJ, f"tile_variant_{i}.o"), []))
@@ -59,15 +62,19 @@ def _newest_header():
 def _compile(unit):
     src, obj, extra = unit
     cmd = [HIPCC, *FLAGS, *extra, "-c", src, "-o", obj]
-    if os.environ.get("GEMM_KEEP_ASM"):      # keep the device assembly next to the object, for inspection
-        cmd.insert(1, "-save-temps=obj")
     p = subprocess.run(cmd, capture_output=True, text=True)
     noise = ("is not a recognized feature", "unknown feature")
     err = "\n".join(l for l in p.stderr.splitlines() if not any(n in l for n in noise))
     return p.returncode, " ".join(cmd), err
 
 
-def build_library(force: bool = False, jobs: int = 8, verbose: bool = True) -> str:
+def build_library(force: bool = False, jobs: int = 8, verbose: bool = True, defines=(), output: str = "") -> str:
+    global OBJ, LIB, FLAGS
+    if output:
+        LIB = os.path.abspath(output)
+        OBJ = LIB + ".objs"
+    if defines:
+        FLAGS = FLAGS + ["-D" + d for d in defines]
     os.makedirs(OBJ, exist_ok=True)
     hdr = _newest_header()
     todo = []
@@ -92,4 +99,7 @@ def build_library(force: bool = False, jobs: int = 8, verbose: bool = True) -> s
 
 
 if __name__ == "__main__":
-    print(build_library(force="--force" in sys.argv))
+    argv = sys.argv[1:]
+    defs = [argv[i + 1] for i, x in enumerate(argv) if x == "--define" and i + 1 < len(argv)]
+    outp = next((argv[i + 1] for i, x in enumerate(argv) if x == "--output" and i + 1 < len(argv)), "")
+    print(build_library(force="--force" in argv or bool(defs), defines=defs, output=outp))

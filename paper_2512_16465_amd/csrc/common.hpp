@@ -180,6 +180,7 @@ const TileVariantInfo* tile_variant_info(int variant);
 bool tile_supports(const Args& a);
 // further preconditions of one variant (beyond tile_supports)
 bool tile_variant_supports(const Args& a, int variant);
+bool shortk_call_fits(const Args& a);
 // Split of the trailing tiles along K.  Tiles are numbered in launch order; those with number >=
 // first_tile are computed by `parts` workgroups each, every one over a contiguous share of the k
 // slabs, which write raw fp32 partial tiles to `partials` ([tile - first_tile][part][BM][BN]);
@@ -207,6 +208,12 @@ hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream
 // Adds `split_k` fp32 partial results `partials[s][M][N]` (rows N apart) in the order of s and applies
 // the epilogue of `a` into C.  N must be a multiple of 8.
 hipError_t launch_splitk_reduce(const Args& a, int split_k, const float* partials, hipStream_t stream);
+
+// fp32 operands, at most 8 rows: the streaming kernels on the vector ALUs (part of the skinny family)
+bool gemv_f32_supports(const Args& a);
+int gemv_f32_max_split(const Args& a);
+int gemv_f32_default_split(const Args& a, int num_cus);
+hipError_t launch_gemv_f32(const Args& a, int split_k, float* workspace, hipStream_t stream);
 
 hipError_t launch_general(const Args& a, hipStream_t stream);
 

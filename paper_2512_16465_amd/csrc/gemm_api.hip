@@ -58,6 +58,9 @@ constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant 
 // K = 512 on: 4096x4096x512 27 against 25, 256x4096x512 7.4 against 6.7; slices take the ring of four)
 constexpr int kSmallTileShortK = 12;
 constexpr int64_t kShortK = 256;
+// ... and for K <= 128 with at least two tiles per compute unit the persistent kernel, which overlaps the
+// loads, the arithmetic and the stores of successive tiles (32 x 2048x2048x128: see the bench row X8)
+constexpr int kPersistentShortK = 17;
 constexpr double kSmallPerK = 0.0094, kSmallFixed = 1.4;     // (the large tile's 0.0209 us per k and 15 us fixed: kFullTile below)
 // A last round that fills less than this fraction of the compute units is split along K (when the
 // variant can): each of its tiles goes to several workgroups, each over a share of the k slabs of
@@ -74,7 +77,7 @@ constexpr int kPartChoices[] = {2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
 // tiles (8 x 4 with bands of 8 measured 0.5 % slower on 8192^3 and 8192x28672x8192, bands of 16 3 % slower).
 constexpr int kTileBandRows = 4;
 // most rows of C for which the automatic choice takes the skinny family
-constexpr int64_t kSkinnyAutoRows = 32, kSkinnyAutoBytes = (int64_t)128 << 20;
+constexpr int64_t kSkinnyAutoRows = 32, kSkinnyAutoBytes = (int64_t)128 << 20, kSkinnyAutoBytesF32 = (int64_t)16 << 20;
 
 // The 16x16x32 kernel with its tile halved along one side (256x128, 128x256): half the MFMAs per
 // slab and 12 instead of 16 fragment reads, so LDS rather than the matrix pipe bounds it
@@ -267,6 +270,7 @@ TileChoice choose_tile(const Args& a, int num_cus) {
         const double tq = dma16_time(kQuarterTile, a, cus, true, &p, &f);
         if (p > 1) return TileChoice{kQuarterTile.variant, (int)f, p, tq};
     }
+    if (slices == 1 && small >= 2 * cus && gemm::tile_variant_supports(a, kPersistentShortK)) return TileChoice{kPersistentShortK, 0, 1, t_small};
     return TileChoice{slices == 1 && a.K <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, slices, t_small};
 }
 
@@ -533,15 +537,46 @@ bool peel_remainder(const Args& a, int num_cus, double whole_time, Args* main_pa
     return found;
 }
 
-// The paper's roofline rule (Section 4.3) in arithmetic form: few rows of C make the
-// call bandwidth-limited (stream B once, split K); otherwise it is a matrix-core problem.
-// The skinny kernels are ahead where B is a long stream: up to 32 rows, B of 128 MiB or more,
-// K >= 4096, N >= 4096 (fewer than 16 column groups need more than 16 slices: 16x2048x32768 36 to 38 us
-// against 31 to 32 on sliced tiles) (32x16384x16384: 94 against 99 us on the 128x256 tile with a K split,
-// 16x28672x8192 with B stored N x K: 79 against 92).  Smaller weights run as fast or faster as
-// sliced 128x128 tiles (32x2048x2048: 19 to 21 against 15 to 20 us, 32x256x512: 18 to 26 against
-// 10 to 13), and with 33 to 64 rows the 128x256 tile wins everywhere (64x16384x16384: 107
-// against 112 / 126 us, 64x28672x8192: 100 against 152 / 158).
+// The roofline rule of the paper (Section 4.3) as arithmetic.  A kernel is placed by its arithmetic
+// intensity, flop per byte of compulsory traffic: left of the point where the roof of the
+// lowest-throughput unit (the fp32 vector ALUs) meets the memory roof it is memory-bound, right of the
+// point where the roof of the highest-throughput unit that can do the work (the matrix cores for the
+// operand type) meets it, compute-bound, in between in the middle zone.  The class names the resource
+// to optimise for: memory-bound and middle-zone calls are candidates for the streaming (skinny)
+// family, whose objective is bytes per second on one pass over B; compute-bound calls go to the
+// macro-tile family, whose objective is matrix-core occupancy, and never to the streaming family.
+constexpr double kPeakVectorFlops = 157.3e12, kPeakMatrixFlops16 = 2.5e15, kPeakMatrixFlops32 = 157.3e12, kPeakMemoryBytes = 8.0e12;
+
+struct Roofline { double intensity; gemm_roofline_t cls; };
+
+Roofline roofline_of(int64_t batch, int64_t M, int64_t N, int64_t K, int dtype, int out_dtype, bool reads_c, int bias_dtype) {
+    const double in_b = (double)gemm::elem_bytes(dtype), out_b = (double)gemm::elem_bytes(out_dtype);
+    double bytes = ((double)M * (double)K + (double)K * (double)N) * in_b + (double)M * (double)N * out_b * (reads_c ? 2.0 : 1.0);
+    bytes *= (double)batch;
+    if (bias_dtype >= 0) bytes += (double)N * (double)gemm::elem_bytes(bias_dtype);
+    const double flops = 2.0 * (double)M * (double)N * (double)K * (double)batch;
+    Roofline r;
+    r.intensity = bytes > 0.0 ? flops / bytes : 0.0;
+    const double ridge_low = kPeakVectorFlops / kPeakMemoryBytes;
+    const double ridge_high = (dtype == gemm::DT_F32 ? kPeakMatrixFlops32 : kPeakMatrixFlops16) / kPeakMemoryBytes;
+    r.cls = r.intensity < ridge_low ? GEMM_MEMORY_BOUND : (r.intensity > ridge_high ? GEMM_COMPUTE_BOUND : GEMM_MIDDLE_ZONE);
+    return r;
+}
+
+Roofline roofline_of(const Args& a) {
+    return roofline_of(a.batch, a.M, a.N, a.K, a.dtype, a.out_dtype, a.beta != 0.0f, a.bias ? a.bias_dtype : -1);
+}
+
+// Inside the two classes that may stream, measurements break the tie between the families.  16-bit
+// operands: the skinny kernels are ahead where B is a long stream - up to 32 rows, B of 128 MiB or
+// more, K >= 4096, N >= 4096 (fewer than 16 column groups need more than 16 slices: 16x2048x32768 36
+// to 38 us against 31 to 32 on sliced tiles; 32x16384x16384: 94 against 99 us on the 128x256 tile
+// with a K split, 16x28672x8192 with B stored N x K: 79 against 92).  Smaller weights run as fast or
+// faster as sliced 128x128 tiles or split quarter tiles (1...8 x 4096 x 4096: 11.5 to 12 us against
+// 11.5 to 15; 32x2048x2048: 15 to 20 against 19 to 21), and with 33 to 64 rows the 128x256 tile wins
+// everywhere (64x16384x16384: 107 against 112 / 126 us).  fp32 operands: up to 8 rows on a B of 16 MiB
+// or more take the fp32 streaming kernels (vector ALUs: at half a flop per byte and row the matrix
+// cores have nothing to add), everything else the fp32 tiles.
 struct AutoPlan {
     gemm_plan_t plan;          // of the call, or of its whole tiles when it is made in two
     int split_first;
@@ -558,8 +593,18 @@ AutoPlan automatic_plan(const Args& a, int num_cus, bool batch_aligned) {
     ap.peeled = false;
     ap.rest_plan = ap.plan;
     ap.rest_split_first = -1;
-    if (gemm::skinny_supports(a) && batch_aligned && a.M <= kSkinnyAutoRows && a.N * a.K * 2 >= kSkinnyAutoBytes && a.K >= 4096 &&
-        a.N >= 4096) {
+    const Roofline roof = roofline_of(a);
+    const bool may_stream = roof.cls != GEMM_COMPUTE_BOUND && gemm::skinny_supports(a) && batch_aligned;
+    // fp32: B stored N x K from 16 MiB on; a row-major B from 16 MiB per row of C on (its kernel spends vector
+    // instructions per row: 8 x 4096 x 4096 43 us against 29 on the fp32 tiles, 8 x 8192 x 8192 73 against 85)
+    const bool long_stream = a.dtype == gemm::DT_F32
+                                 ? (a.N * a.K * 4 >= kSkinnyAutoBytesF32 * (a.transB ? 1 : a.M) && a.K >= 1024 && a.N >= 1024)
+                                 : (a.M <= kSkinnyAutoRows && a.N * a.K * 2 >= kSkinnyAutoBytes && a.K >= 4096 && a.N >= 4096 && !a.transA);
+    // An A stored K x M costs the streaming kernels a copy (3 to 4 us: 8 x 8192 x 8192 33 us against 30 on split
+    // quarter tiles, 32 x 16384 x 16384 98 against 93), so they take it only where the macro tiles cannot: a row
+    // count that is no multiple of 8, which would otherwise fall to the general kernel.
+    const bool only_stream = a.transA && !gemm::tile_supports(a);
+    if (may_stream && (long_stream || only_stream)) {
         ap.plan = gemm_plan_t{GEMM_KERNEL_SKINNY, gemm::skinny_variant_of(a), gemm::skinny_default_split(a, num_cus)};
     } else if (gemm::tile_supports(a) && batch_aligned &&
                (a.dtype != gemm::DT_F32 || ((a.M + 63) / 64) * ((a.N + 63) / 64) * a.batch >= kF32MinTiles)) {
@@ -704,6 +749,17 @@ gemm_status_t run_batch(gemm_handle_t h, bool fixed_scratch, int64_t batch, int6
 }
 
 }  // namespace
+
+GEMM_EXPORT gemm_status_t gemm_roofline_class(int64_t batch, int64_t M, int64_t N, int64_t K, gemm_dtype_t dtype, gemm_dtype_t out_dtype,
+                                              int32_t reads_c, int32_t has_bias, gemm_dtype_t bias_dtype, gemm_roofline_t* cls,
+                                              double* intensity) {
+    if (!cls || batch < 1 || M < 1 || N < 1 || K < 1) return GEMM_ERR_INVALID_ARG;
+    if (!valid_dtype(dtype) || !valid_dtype(out_dtype) || (has_bias && !valid_dtype(bias_dtype))) return GEMM_ERR_INVALID_ARG;
+    const Roofline r = roofline_of(batch, M, N, K, (int)dtype, (int)out_dtype, reads_c != 0, has_bias ? (int)bias_dtype : -1);
+    *cls = r.cls;
+    if (intensity) *intensity = r.intensity;
+    return GEMM_OK;
+}
 
 GEMM_EXPORT gemm_status_t gemm_plan_query(int32_t compute_units, int64_t batch, int64_t M, int64_t N, int64_t K,
                                           gemm_op_t transA, gemm_op_t transB, gemm_dtype_t dtype, gemm_dtype_t out_dtype,

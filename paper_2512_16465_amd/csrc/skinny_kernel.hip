@@ -500,39 +500,68 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(Args a, int split_k,
     sk_store_row(a, row, col, x, in, c_vec_ok != 0);
 }
 
+// A stored K x M (transA): the few rows of op(A) are gathered once into a row-major M x K copy in the
+// workspace (2 MiB at most), and the streaming kernels then run on the copy.  One thread moves eight
+// consecutive k of one row: neighbouring lanes read neighbouring elements of a stored row and each
+// writes 16 bytes of the copy.
+__global__ __launch_bounds__(256) void skinny_transpose_a_kernel(const uint16_t* A, int64_t lda, int M, int K, uint16_t* At) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t blocks = K / 8;
+    if (idx >= blocks * M) return;
+    const int m = (int)(idx % M);
+    const int64_t k0 = (idx / M) * 8;
+    u32x4 o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        o[j] = (uint32_t)A[(k0 + 2 * j) * lda + m] | ((uint32_t)A[(k0 + 2 * j + 1) * lda + m] << 16);
+    *(u32x4*)(At + (int64_t)m * K + k0) = o;
+}
+
 }  // namespace
 
 bool skinny_supports(const Args& a) {
+    if (a.dtype == DT_F32) return gemv_f32_supports(a);
     if (a.dtype != DT_BF16 && a.dtype != DT_F16) return false;
-    if (a.transA) return false;
     if (a.M < 1 || a.M > SK_MAX_ROWS || a.N < 8 || a.K < 8) return false;
-    if ((a.N & 7) || (a.K & 7) || (a.lda & 7) || (a.ldb & 7)) return false;
-    if (((uintptr_t)a.A & 15) || ((uintptr_t)a.B & 15)) return false;
+    if ((a.N & 7) || (a.K & 7) || (a.ldb & 7)) return false;
+    if ((uintptr_t)a.B & 15) return false;
+    // a row-major A is read in 16-byte pieces; an A stored K x M element by element, into an aligned copy
+    if (!a.transA && ((a.lda & 7) || ((uintptr_t)a.A & 15))) return false;
+    if (a.transA && a.K * a.lda * 2 >= (int64_t)1 << 40) return false;
     // 32-bit byte offsets into A and B (row-major B: with room for the rows past K that read as
     // zero; B stored N x K: below the offset that masks a lane)
     const int64_t b_bytes = a.transB ? a.N * a.ldb * 2 : (a.K + 16) * a.ldb * 2;
     if (b_bytes >= (int64_t)ST_MASKED) return false;
-    if ((a.M * a.lda) * 2 >= (int64_t)ST_MASKED) return false;
+    if ((a.M * (a.transA ? a.K : a.lda)) * 2 >= (int64_t)ST_MASKED) return false;
     if ((a.N + SK_COLS - 1) / SK_COLS > 65535 * 16) return false;
     return true;
 }
 
 // variant 0: row-major B (K x N); variant 1: B stored N x K.  The layout of the call decides.
+// Variants 2 and 3: the same two layouts for fp32 operands and at most 8 rows (gemv_f32_kernel.hip).
 const char* skinny_variant_name(int variant) {
-    return variant == 0 ? "skinny_nn_32x256_w4" : (variant == 1 ? "skinny_nt_32x256_w4" : nullptr);
+    switch (variant) {
+        case 0: return "skinny_nn_32x256_w4";
+        case 1: return "skinny_nt_32x256_w4";
+        case 2: return "gemv_f32_nn_8x256_w4";
+        case 3: return "gemv_f32_nt_8x32_w4";
+        default: return nullptr;
+    }
 }
 
-int skinny_variant_of(const Args& a) { return a.transB ? 1 : 0; }
+int skinny_variant_of(const Args& a) { return (a.dtype == DT_F32 ? 2 : 0) + (a.transB ? 1 : 0); }
 
 // units the k range is cut in: steps of 16 (row-major B) or chunks of ST_CHUNK (B stored N x K)
 static int64_t skinny_k_units(const Args& a) { return a.transB ? (a.K + ST_CHUNK - 1) / ST_CHUNK : (a.K + 15) / 16; }
 
 int skinny_max_split(const Args& a) {
+    if (a.dtype == DT_F32) return gemv_f32_max_split(a);
     const int64_t units = skinny_k_units(a);
     return (int)(units < 1 ? 1 : (units > 64 ? 64 : units));
 }
 
 int skinny_default_split(const Args& a, int num_cus) {
+    if (a.dtype == DT_F32) return gemv_f32_default_split(a, num_cus);
     const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS, cus = num_cus > 0 ? num_cus : 256;
     // keep the pipeline of every wave filled a few times over (row-major B: the waves of a
     // workgroup share its k range; B stored N x K: every wave walks all of it, four visits per chunk)
@@ -557,8 +586,13 @@ int skinny_default_split(const Args& a, int num_cus) {
     return (int)best;
 }
 
+// fp32 partial results [split][M][N] (none without a split), then the row-major copy of an A stored K x M
+static size_t skinny_partial_bytes(const Args& a, int split_k) {
+    const size_t n = split_k > 1 ? (size_t)split_k * (size_t)a.M * (size_t)a.N * sizeof(float) : 0;
+    return (n + 255) & ~(size_t)255;
+}
 size_t skinny_workspace_bytes(const Args& a, int split_k) {
-    return split_k > 1 ? (size_t)split_k * (size_t)a.M * (size_t)a.N * sizeof(float) : 0;
+    return skinny_partial_bytes(a, split_k) + (a.transA && a.dtype != DT_F32 ? (size_t)a.M * (size_t)a.K * 2 : 0);
 }
 
 namespace {
@@ -573,7 +607,21 @@ void launch_nt(const Args& a, dim3 grid, int split_k, float* ws, hipStream_t str
 }
 }  // namespace
 
-hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream_t stream) {
+hipError_t launch_skinny(const Args& call, int split_k, float* workspace, hipStream_t stream) {
+    if (call.dtype == DT_F32) return launch_gemv_f32(call, split_k, workspace, stream);
+    Args a = call;
+    if (call.transA) {
+        if (workspace == nullptr) return hipErrorInvalidValue;
+        const int64_t units = skinny_k_units(call);
+        const int s = split_k < 1 ? 1 : (split_k > units ? (int)units : split_k);
+        uint16_t* copy = (uint16_t*)((char*)workspace + skinny_partial_bytes(call, s));
+        const int64_t threads = call.M * (call.K / 8);
+        hipLaunchKernelGGL(skinny_transpose_a_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
+                           (const uint16_t*)call.A, call.lda, (int)call.M, (int)call.K, copy);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        a.A = copy; a.lda = call.K; a.transA = 0;
+    }
     const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS;
     const int64_t units = skinny_k_units(a);
     if (split_k < 1) split_k = 1;

@@ -35,7 +35,7 @@ def test_benchmark_configurations():
     assert plan_of("X4") == (TILE, "dma16p_256x128x32_w2x2_s5", 1)       # N = 128: every full tile would be half empty
     assert plan_of("X6") == (TILE, "f32_128x128x32_w2x2", 1)
     assert plan_of("X11") == (TILE, "dma16p_128x256x32_w2x2_s5", 4)   # 64 tiles in 4 shares: one workgroup per unit
-    assert plan_of("X8") == (TILE, "dma_128x128x32_w2x2_s3", 1)          # batched, K = 128: ring of three, no split
+    assert plan_of("X8") == (TILE, "shortk_128x128_w2x2_persistent", 1)  # batched, K = 128, 32 tiles per unit: persistent workgroups
     # made in two: 8000 x 8192 on whole tiles (four full rounds), then the strip of 8 columns
     assert plan_of("X3") == (TILE, big, 1)
     assert plan_of("X9") == (TILE, big, 1) and plan_of("X10") == (TILE, big, 1)
@@ -56,13 +56,47 @@ def test_family_by_rows_and_weight_size():
     assert plan(64, 1024, 1024)[1] == "dma16p_128x128x32_w2x2_s5" and plan(65, 1024, 1024)[1] != "dma16p_128x128x32_w2x2_s5"
     assert plan(16, 2048, 32768)[0] == TILE                     # too few column groups
     assert plan(16, 65536, 2048)[0] == TILE                     # short k
-    assert plan(8, 8192, 8192, ta=1)[0] == TILE                 # A stored K x M
+    assert plan(8, 8192, 8192, ta=1)[0] == TILE                 # A stored K x M: the tiles take 8 rows ...
+    assert plan(5, 8192, 8192, ta=1)[0] == SKINNY and plan(1, 512, 1024, ta=1, tb=1)[0] == SKINNY    # ... but no other count below it
     # 112 column groups: two slices fill 224 of 256 units in one round
     assert plan(32, 28672, 8192) == (SKINNY, "skinny_nn_32x256_w4", 2)
     # anything the vector loads cannot take goes to the general kernel
     assert plan(37, 29, 53, 1, 0, wl.F32)[0] == GENERAL
     assert plan(128, 128, 132)[0] == GENERAL                    # K not a multiple of 8
     assert plan(128, 128, 128, lda=132)[0] == GENERAL           # rows of A off the 16-byte grid
+
+
+def test_roofline_rule_of_section_4_3():
+    """The class every bench row gets from the library equals the one the bench computes for it from the
+    workload's own flop and byte counts; the ridge points are where the rule puts them; and the class
+    gates the family: compute-bound calls never stream, whatever their shape."""
+    import bench
+    names = {lg.GEMM_MEMORY_BOUND: "memory-bound", lg.GEMM_MIDDLE_ZONE: "middle-zone", lg.GEMM_COMPUTE_BOUND: "compute-bound"}
+    for name, c in {**wl.CONFIGS, **wl.EXTRA_CONFIGS}.items():
+        cls, ai = lg.gemm_roofline_class(c.batch, c.M, c.N, c.K, c.dtype, c.out_dtype, c.beta != 0.0,
+                                         c.bias_dtype if c.bias_dist is not None else None)
+        assert names[cls] == bench.classify(c), name
+        assert abs(ai - c.flops() / c.algorithmic_bytes()) <= 1e-9 * ai, name
+    expect = {"C1": "compute-bound", "C2": "compute-bound", "C3": "compute-bound", "C4": "compute-bound", "C5": "middle-zone",
+              "X5": "memory-bound", "X7": "middle-zone", "X8": "middle-zone", "X4": "middle-zone", "X11": "middle-zone",
+              "G1": "memory-bound", "G2": "memory-bound", "G5": "memory-bound", "G6": "memory-bound", "X6": "compute-bound"}
+    for name, want in expect.items():
+        assert bench.classify({**wl.CONFIGS, **wl.EXTRA_CONFIGS}[name]) == want, name
+    # ridge points: 157.3e12 / 8e12 = 19.66 flop/byte and 2.5e15 / 8e12 = 312.5 (bf16, fp16); fp32 has one ridge
+    # bf16 M x N x N with N large: intensity -> M flop/byte
+    big = 1 << 15
+    assert lg.gemm_roofline_class(1, 19, big, big, wl.BF16, wl.BF16)[0] == lg.GEMM_MEMORY_BOUND
+    assert lg.gemm_roofline_class(1, 20, big, big, wl.BF16, wl.BF16)[0] == lg.GEMM_MIDDLE_ZONE
+    assert lg.gemm_roofline_class(1, 316, big, big, wl.BF16, wl.BF16)[0] == lg.GEMM_MIDDLE_ZONE
+    assert lg.gemm_roofline_class(1, 324, big, big, wl.BF16, wl.BF16)[0] == lg.GEMM_COMPUTE_BOUND
+    assert lg.gemm_roofline_class(1, 39, big, big, wl.F32, wl.F32)[0] == lg.GEMM_MEMORY_BOUND       # M / 2 flop per byte
+    assert lg.gemm_roofline_class(1, 40, big, big, wl.F32, wl.F32)[0] == lg.GEMM_COMPUTE_BOUND
+    # the streaming family is a candidate only left of the matrix-core ridge; it is chosen for long streams of B
+    assert plan(1, 8192, 8192)[0] == SKINNY and plan(8, 8192, 8192, 0, 1)[0] == SKINNY
+    assert plan(1, 8192, 8192, dtype=wl.F32) == (SKINNY, "gemv_f32_nn_8x256_w4", 8)
+    assert plan(8, 8192, 8192, 0, 1, dtype=wl.F32) == (SKINNY, "gemv_f32_nt_8x32_w4", 1)
+    assert plan(8, 4096, 4096, dtype=wl.F32)[0] == TILE and plan(8, 4096, 4096, 0, 1, dtype=wl.F32)[0] == SKINNY
+    assert plan(9, 8192, 8192, dtype=wl.F32)[0] == TILE and plan(1, 512, 512, dtype=wl.F32)[0] == TILE
 
 
 def test_tile_split_and_slices():
@@ -122,7 +156,8 @@ def test_query_argument_errors():
 
 def test_invariants_over_random_shapes():
     """Whatever the shape: a valid plan; the general kernel exactly when an operand cannot be read in 16-byte
-    vectors; the streaming kernels only for few rows of a row-major A; no split inside a batch."""
+    vectors (but for an A stored K x M with at most 64 rows, which the streaming kernels copy element by element);
+    the streaming kernels only for few rows; no split inside a batch."""
     import random
     rng = random.Random(5)
     dims = [1, 7, 8, 24, 32, 33, 64, 100, 128, 136, 256, 520, 1024, 2056, 4096, 8192, 16384, 28672, 65536]
@@ -141,8 +176,18 @@ def test_invariants_over_random_shapes():
         vec = 4 if dtype == wl.F32 else 8
         # rows of both operands start on 16-byte boundaries and hold whole vectors
         loadable = lda % vec == 0 and ldb % vec == 0 and (M if ta else K) % vec == 0 and (K if tb else N) % vec == 0
-        assert (kernel == GENERAL) == (not loadable), what
-        if kernel == SKINNY:
-            assert M <= 32 and not ta and dtype != wl.F32, what
+        copied_a = (ta and dtype != wl.F32 and M <= 64 and not loadable
+                    and ldb % 8 == 0 and (K if tb else N) % 8 == 0 and K % 8 == 0 and N % 8 == 0
+                    and (N if tb else K + 16) * ldb * 2 < 0x7ffffff0 and M * K * 2 < 0x7ffffff0)      # 32-bit offsets into B and the copy
+        if copied_a and batch > 1:
+            assert kernel in (SKINNY, GENERAL), what          # (the strides of the batch may break the alignment of B)
+        elif copied_a:
+            assert kernel == SKINNY, what
+        else:
+            assert (kernel == GENERAL) == (not loadable), what
+        if kernel == SKINNY and dtype == wl.F32:
+            assert M <= 8 and not ta, what
+        elif kernel == SKINNY:
+            assert (M <= 32 and not ta) or copied_a, what
         if batch > 1:
             assert split == 1 or kernel == SKINNY, what

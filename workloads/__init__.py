@@ -169,6 +169,20 @@ EXTRA_CONFIGS: Dict[str, Config] = {
     "X10": Config("X10", 4120, 4096, 4096, 1, 1, F16, F32,
                   a_dist=("normal", 1.0), b_dist=("normal", 4096 ** -0.5),
                   note="fp16 4120x4096x4096 TT, fp32 out: 16 whole tile rows and a strip of 24 rows"),
+    # matrix-vector and few-row products (the paper's memory-bound kernel, Section 5.3) on weights of 32 to 256 MiB,
+    # in both layouts of the weight and in bf16 and fp32
+    "G1": Config("G1", 1, 8192, 8192, 0, 1, BF16, BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                 note="bf16 1x8192x8192 NT: a matrix-vector product on a 128 MiB weight kept as [out, in]"),
+    "G2": Config("G2", 8, 8192, 8192, 0, 0, BF16, BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                 note="bf16 8x8192x8192 NN: 8 rows on a 128 MiB row-major weight"),
+    "G3": Config("G3", 1, 4096, 4096, 0, 0, BF16, BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                 note="bf16 1x4096x4096 NN: a matrix-vector product on a 32 MiB weight (cache resident, launch bound)"),
+    "G4": Config("G4", 8, 4096, 4096, 0, 1, BF16, BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                 note="bf16 8x4096x4096 NT: 8 rows on a 32 MiB weight kept as [out, in] (cache resident, launch bound)"),
+    "G5": Config("G5", 1, 8192, 8192, 0, 0, F32, F32, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                 note="fp32 1x8192x8192 NN: a matrix-vector product on a 256 MiB weight, vector ALUs"),
+    "G6": Config("G6", 8, 8192, 8192, 0, 1, F32, F32, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                 note="fp32 8x8192x8192 NT: 8 rows on a 256 MiB weight kept as [out, in], vector ALUs"),
 }
 
 
