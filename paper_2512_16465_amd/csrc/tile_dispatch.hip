@@ -58,12 +58,25 @@ bool tile_variant_supports(const Args& a, int variant) {
     if (variant < 0 || variant >= kNum) return false;
     if ((kInfo[variant].kind == 4) != (a.dtype == DT_F32)) return false;
     if (kInfo[variant].kind == 0 || kInfo[variant].kind == 4) return true;
+    if (kInfo[variant].kind == 5 && !shortk_call_fits(a)) return false;
     const int64_t a_bytes = ((a.transA ? a.K : a.M) * a.lda) * 2, b_bytes = ((a.transB ? a.N : a.K) * a.ldb) * 2;
     return a_bytes < 0x7ffffff0ll && b_bytes < 0x7ffffff0ll;
 }
 
+// The persistent short-k kernel (kind 5): whole slabs, K <= 128, C write-only, no bias, stored in 16-byte pieces,
+// the operands of a tile or its staged results inside 64 KiB of LDS.  (Restated here from
+// tile_shortk_kernel.hpp, which only the variant's own translation unit includes.)
+bool shortk_call_fits(const Args& a) {
+    if (a.K % 32 != 0 || a.K > 128 || a.beta != 0.0f || a.bias != nullptr || a.k_total != 0) return false;
+    const int64_t ob = elem_bytes(a.out_dtype);
+    if (128 * 128 * ob > 64 * 1024) return false;
+    if (a.N % 8 != 0 || a.ldc % (16 / ob) != 0 || ((uintptr_t)a.C & 15)) return false;
+    if (a.batch > 1 && (a.strideC * ob) % 16 != 0) return false;
+    return true;
+}
+
 bool tile_variant_splits(int variant) { return variant >= 0 && variant < kNum && kInfo[variant].kind == 3; }
-bool tile_variant_slices(int variant) { return variant >= 0 && variant < kNum && kInfo[variant].kind != 3; }
+bool tile_variant_slices(int variant) { return variant >= 0 && variant < kNum && kInfo[variant].kind != 3 && kInfo[variant].kind != 5; }
 
 hipError_t launch_tile(const Args& a, int variant, int group_m, const TileSplit& split, hipStream_t stream) {
     if (variant < 0 || variant >= kNum) return hipErrorInvalidValue;
