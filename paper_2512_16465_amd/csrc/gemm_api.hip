@@ -40,7 +40,7 @@ bool valid_dtype(int d) { return d == GEMM_F32 || d == GEMM_F16 || d == GEMM_BF1
 
 // Picks a tile variant for the macro-tile family by comparing two estimates of the run time in
 // microseconds.  A workgroup of the 256x256 tile (16x16x32 MFMA, direct-to-LDS, one workgroup per
-// compute unit) takes 0.0209 us * K for its k loop plus 15 us for filling the pipeline
+// compute unit) takes 0.0203 us * K for its k loop plus 12 us for filling the pipeline
 // and for the epilogue, which nothing overlaps; the 128x128 tile (two workgroups per compute
 // unit, each other's epilogue hidden behind the other's k loop) takes kSmallPerK * K + kSmallFixed
 // per tile and compute unit.  Measured: 8192^3 in 744 us with the large tile (4 rounds) and
@@ -61,7 +61,7 @@ constexpr int64_t kShortK = 256;
 // ... and for K <= 128 with at least two tiles per compute unit the persistent kernel, which overlaps the
 // loads, the arithmetic and the stores of successive tiles (32 x 2048x2048x128: see the bench row X8)
 constexpr int kPersistentShortK = 17;
-constexpr double kSmallPerK = 0.0094, kSmallFixed = 1.4;     // (the large tile's 0.0209 us per k and 15 us fixed: kFullTile below)
+constexpr double kSmallPerK = 0.0094, kSmallFixed = 1.4;     // (the large tile's 0.0203 us per k and 12 us fixed: kFullTile below)
 // A last round that fills less than this fraction of the compute units is split along K (when the
 // variant can): each of its tiles goes to several workgroups, each over a share of the k slabs of
 // at least kMinSlabsPerPart, and a second kernel adds the parts.  The number of parts minimises
@@ -85,14 +85,15 @@ constexpr int64_t kSkinnyAutoRows = 32, kSkinnyAutoBytes = (int64_t)128 << 20, k
 // It pays where the full tile would be half empty: 65536x128x4096 100 us against 120 on the
 // 128x128 tile and 146 on the full tile, 32768x256x4096 75 against 87.
 struct Dma16Tile { int variant; int bm, bn; double per_k, fixed, hbm_rate; int min_slabs; };   // min_slabs: shortest share of a split, in slabs of 32
-constexpr Dma16Tile kFullTile{10, 256, 256, 0.0209, 15.0, 4.4e6, kMinSlabsPerPart};
-constexpr Dma16Tile kTallTile{14, 256, 128, 0.0117, 10.0, 5.8e6, kMinSlabsPerPart};
-constexpr Dma16Tile kWideTile{15, 128, 256, 0.0117, 10.0, 5.8e6, kMinSlabsPerPart};
+constexpr Dma16Tile kFullTile{10, 256, 256, 0.0203, 12.0, 4.4e6, kMinSlabsPerPart};      // (8192^3: 709 us in four rounds; 4096^3: 92; 4096x4096x512: 21)
+constexpr Dma16Tile kTallTile{14, 256, 128, 0.0117, 9.0, 5.8e6, kMinSlabsPerPart};
+constexpr Dma16Tile kWideTile{15, 128, 256, 0.0117, 9.0, 5.8e6, kMinSlabsPerPart};
 // ... and quartered (128x128, 16 MFMAs per step): 1024x4096x4096 in 38.5 us on 256 tiles; with its split it is
 // the tile for small grids with long k loops (48x4096x4096: 15 us in 8 shares against 19 on sliced 32x32x16 tiles).
-constexpr Dma16Tile kQuarterTile{16, 128, 128, 0.0082, 4.0, 5.0e6, 4};       // (its steps are short: 64x4096x512 11 us in 4 shares of 4 slabs, 14 whole)
+constexpr Dma16Tile kQuarterTile{16, 128, 128, 0.0082, 3.0, 5.0e6, 4};       // (its steps are short: 64x4096x512 11 us in 4 shares of 4 slabs, 14 whole)
 constexpr double kHalfTileMargin = 0.9, kUnfavouredHalfTile = 1.15;
 constexpr int64_t kQuarterTileRows = 64, kQuarterTileLongK = 16384;
+constexpr double kQuarterTileMargin = 0.92;
 
 // time of the k loops of a round whose tiles are cut in `parts`, plus the second kernel (us)
 double split_round_time(const Dma16Tile& t, int64_t tail, int parts, int64_t K, double live = 1.0) {
@@ -256,6 +257,16 @@ TileChoice choose_tile(const Args& a, int num_cus) {
     // (the sliced 32x32x16 tile is estimated too well for so few rows - 48x4096x4096: estimated 14 us, measured 19;
     // the quartered tile in 8 shares: estimated 15, measured 15 - so it does not compete there)
     if (best_tile == &kQuarterTile) t_small = t_large + 1.0;
+    // The quartered tile against whatever won so far, for operands inside the last-level cache: with the last
+    // steps of its k loop pipelined it is ahead of the sliced 32x32x16 tile on grids of one to two hundred small
+    // tiles (128x4096x4096: 17 us in 6 shares against 20 in 8 slices; 512x4096x4096: 28 in 2 shares against 33
+    // whole), where its estimate says so by 8 %.
+    if (large_ok && a.batch == 1 && best_tile != &kQuarterTile && (a.M + a.N) * a.K * 2 <= kLastLevelCacheBytes) {
+        int p = 1;
+        int64_t f = 0;
+        const double tq = dma16_time(kQuarterTile, a, cus, true, &p, &f);
+        if (tq < kQuarterTileMargin * t_small && tq < kQuarterTileMargin * t_large) return TileChoice{kQuarterTile.variant, (int)f, p, tq};
+    }
     if (t_large <= t_small) {
         if (!large_ok) return TileChoice{kLargeTileFallback, 0, 1, 0.0};
         return TileChoice{best_tile->variant, (int)first_split, parts, t_large};

@@ -117,15 +117,17 @@ def test_tile_split_and_slices():
     for shape in ((256, 1024, 32768), (512, 1024, 16384), (128, 512, 65536)):
         kernel, name, shares = plan(*shape)
         assert (kernel, name) == (TILE, "dma16p_128x128x32_w2x2_s5") and shares > 1, shape
-    assert plan(128, 1024, 8192)[1] == small and plan(256, 1024, 8192)[1] == small
+    assert plan(128, 1024, 8192)[1] == small
+    # ... and on grids of 30 to 200 small tiles inside the cache when its estimate is 8 % ahead of the sliced 32x32x16 tile
+    assert plan(128, 4096, 4096) == (TILE, "dma16p_128x128x32_w2x2_s5", 6) and plan(512, 4096, 4096) == (TILE, "dma16p_128x128x32_w2x2_s5", 2)
     # weights beyond the last-level cache stay on the full tile with its split
     assert plan(640, 16384, 16384)[1] == "dma16p_256x256x32_w2x2_s5"
     # batched calls: no split, no slices, no half tiles
     for shape in ((2048, 128, 2048), (512, 512, 4096), (4096, 128, 4096)):
         kernel, name, split = plan(*shape, batch=8)
         assert kernel == TILE and split == 1 and not name.startswith("dma16p_256x128") and not name.startswith("dma16p_128x256")
-    # short k loops take the ring of three
-    assert plan(8192, 8192, 256)[1] == "dma_128x128x32_w2x2_s3" and plan(4096, 4096, 512)[1] == small
+    # short k loops over several rounds take the ring of three; one round of large tiles with K = 512 beats four of small ones (21 against 25 us)
+    assert plan(8192, 8192, 256)[1] == "dma_128x128x32_w2x2_s3" and plan(4096, 4096, 512)[1] == "dma16p_256x256x32_w2x2_s5"
 
 
 def test_fp32_tiles_and_slices():
