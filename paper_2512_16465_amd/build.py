@@ -50,6 +50,17 @@ def _units():
     return units
 
 
+def device_assembly(source_name: str, out_path: str) -> str:
+    """Compiles the device side of one translation unit of csrc/ to gfx950 assembly text, with the
+    flags the library is built with.  For checks that read the generated code."""
+    src = os.path.join(CSRC, source_name)
+    cmd = [HIPCC, *[f for f in FLAGS if f != "-fPIC"], "--cuda-device-only", "-S", src, "-o", out_path]
+    p = subprocess.run(cmd, capture_output=True, text=True)
+    if p.returncode != 0:
+        raise RuntimeError(f"hipcc failed: {' '.join(cmd)}\n{p.stderr}")
+    return out_path
+
+
 def _newest_header():
     t = 0.0
     for root in (CSRC, os.path.join(os.path.dirname(HERE), "include")):

@@ -402,7 +402,9 @@ __global__ __launch_bounds__(C::NT) void tile_dma_kernel(Args a, int tiles_m, in
         __builtin_amdgcn_sched_barrier(0);
         int kt = 0;
         for (; kt + D < full_tiles; ++kt) step_hot(kt);
-        for (; kt < k_tiles; ++kt) step_edge(kt);
+        // at least one step is left (kt + D >= full_tiles or kt == 0, and D >= 1): a loop that is entered
+        // without a test, so that no path leads from the fragment reads above past every wait for them
+        do { step_edge(kt); } while (++kt < k_tiles);
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS is reused by the epilogue
 #undef GEMM_WAIT_VM_BARRIER

@@ -9,14 +9,14 @@
 //
 //   a workgroup stays on its compute unit and walks a list of tiles; per tile it
 //     requests all operands of the tile at once into its 64 KiB of LDS (direct-to-LDS loads),
-//     waits for them, multiplies (16x16x32 MFMA, four waves of 64x64),
+//     multiplies slab by slab as they land (16x16x32 MFMA, four waves of 64x64),
 //     applies alpha, the activation and the one rounding in the accumulator layout and parks the
 //     results, in the type of C, where the operands were (a region per wave, swizzled in 16-byte units),
 //     reads them back row by row and writes C with full 16-byte stores (128-byte row segments for
 //     16-bit results).
 //   While one workgroup of a compute unit waits for its operands or moves its results, the other
-//   multiplies.  The wait for the operands is a wait for everything the wave has in flight; the stores
-//   of the tile before are older than the loads and have had the loads' whole latency to retire.
+//   multiplies.  The waits for the operands count this wave's operations in flight; the stores of the
+//   tile before are older than the loads and have had the loads' whole latency to retire.
 //
 // All LDS traffic is assembly: the compiler would make every LDS access wait for the direct-to-LDS
 // loads in flight.  C is write-only here (beta == 0, no bias); calls with beta != 0, a bias, longer or
@@ -37,9 +37,31 @@ struct ShortK {
     static constexpr int lds_need(int slabs, int out_bytes) { return slabs * SLAB > BM * BN * out_bytes ? slabs * SLAB : BM * BN * out_bytes; }
 };
 
-template <int BYTES> struct ShortkVec;
-template <> struct ShortkVec<8> { typedef u32x2 type; };
-template <> struct ShortkVec<16> { typedef u32x4 type; };
+// Registers of a fragment between its LDS read and the wait for it.  The value of a k-contiguous
+// operand is the one 16-byte register group that the read defines, and it stays whole until the wait
+// has named it: a value taken apart before the wait (two halves, say) may be put together again by
+// register copies that the compiler is free to place ahead of the wait, where they would copy what
+// the registers held before.
+struct ShortkRawKC { u32x4 q; };
+struct ShortkRawMC { u32x2 lo, hi; };
+template <int TILE, class F>
+__device__ __forceinline__ void shortk_read(uint32_t addr, ShortkRawKC& r) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r.q) : "v"(addr), "n"(TILE * 1024));
+}
+template <int TILE, class F>
+__device__ __forceinline__ void shortk_read(uint32_t addr, ShortkRawMC& r) {
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r.lo) : "v"(addr));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(F::HALF_BYTES));
+}
+__device__ __forceinline__ void shortk_wait(ShortkRawKC (&r)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0].q), "+v"(r[1].q), "+v"(r[2].q), "+v"(r[3].q));
+}
+__device__ __forceinline__ void shortk_wait(ShortkRawMC (&r)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(r[0].lo), "+v"(r[0].hi), "+v"(r[1].lo), "+v"(r[1].hi), "+v"(r[2].lo), "+v"(r[2].hi), "+v"(r[3].lo), "+v"(r[3].hi));
+}
+__device__ __forceinline__ u32x4 shortk_value(const ShortkRawKC& r) { return r.q; }
+__device__ __forceinline__ u32x4 shortk_value(const ShortkRawMC& r) { return u32x4{r.lo.x, r.lo.y, r.hi.x, r.hi.y}; }
 
 template <bool IS_BF16, bool A_KC, bool B_KC, int OUT>
 __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int tiles_m, int tiles_n, int total_tiles, int slabs) {
@@ -62,11 +84,13 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     using LB = typename std::conditional<B_KC, DmaKC<S::BN, S::BK, S::NT, false>, DmaMC<S::BN, S::BK, S::NT>>::type;
     using FA = typename std::conditional<A_KC, Frag16KC<S::BM, S::BK>, Frag16MC<S::BM, S::BK>>::type;
     using FB = typename std::conditional<B_KC, Frag16KC<S::BN, S::BK>, Frag16MC<S::BN, S::BK>>::type;
+    using RawA = typename std::conditional<A_KC, ShortkRawKC, ShortkRawMC>::type;
+    using RawB = typename std::conditional<B_KC, ShortkRawKC, ShortkRawMC>::type;
 
     const int per_matrix = tiles_m * tiles_n;
     const int64_t in_b = 2, out_b = OB;
     struct Tile { int64_t m0, n0; const char* A; const char* B; char* C; };
-    auto tile_of = [&](int t) {
+    auto tile_of = [&](int t) __attribute__((always_inline)) {
         const int b = t / per_matrix, r = t - b * per_matrix;
         const int tm = r / tiles_n, tn = r - tm * tiles_n;          // consecutive tiles share a panel of A
         Tile x;
@@ -84,7 +108,7 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     lb_full.init(tid, a.ldb, S::BN);
     const int64_t a_step = LA::k_step_bytes(a.lda), b_step = LB::k_step_bytes(a.ldb);
     // all slabs of tile `x` into LDS: a descriptor per slab, exact range checks
-    auto request = [&](const Tile& x) {
+    auto request = [&]<int SLABS>(const Tile& x) __attribute__((always_inline)) {
         LA la = la_full;
         LB lb = lb_full;
         if (LA::TRANSPOSED && a.M - x.m0 < S::BM) la.init(tid, a.lda, (int)(a.M - x.m0));
@@ -93,7 +117,8 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
         const char* pb = LB::tile_base(x.B, x.n0, a.ldb);
         const int64_t a_bytes = LA::total_bytes(a.M, a.K, a.lda) - (pa - x.A);
         const int64_t b_bytes = LB::total_bytes(a.N, a.K, a.ldb) - (pb - x.B);
-        for (int s = 0; s < slabs; ++s) {
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
             const __amdgpu_buffer_rsrc_t ra = make_rsrc(pa + s * a_step, a_bytes - s * a_step);
             const __amdgpu_buffer_rsrc_t rb = make_rsrc(pb + s * b_step, b_bytes - s * b_step);
             char* dst = lds + s * S::SLAB;
@@ -110,36 +135,58 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     for (int i = 0; i < S::TM; ++i) fa[i] = lds0 + FA::base(wm * S::WTM + (FA::PER_TILE_ADDRESS ? i * 16 : 0), lane);
 #pragma unroll
     for (int j = 0; j < S::TN; ++j) fb[j] = lds0 + S::A_BYTES + FB::base(wn * S::WTN + (FB::PER_TILE_ADDRESS ? j * 16 : 0), lane);
-    auto read_slab = [&](Frag16Raw (&af)[S::TM], Frag16Raw (&bf)[S::TN], uint32_t off) {
-        [&]<int... T>(std::integer_sequence<int, T...>) {
-            (FA::template read<T>(fa[FA::PER_TILE_ADDRESS ? T : 0] + off, af[T]), ...);
-            (FB::template read<T>(fb[FB::PER_TILE_ADDRESS ? T : 0] + off, bf[T]), ...);
+    auto read_slab = [&](RawA (&af)[S::TM], RawB (&bf)[S::TN], uint32_t off) __attribute__((always_inline)) {
+        [&]<int... T>(std::integer_sequence<int, T...>) __attribute__((always_inline)) {
+            (shortk_read<T, FA>(fa[FA::PER_TILE_ADDRESS ? T : 0] + off, af[T]), ...);
+            (shortk_read<T, FB>(fb[FB::PER_TILE_ADDRESS ? T : 0] + off, bf[T]), ...);
         }
         (std::make_integer_sequence<int, 4>{});
     };
 
+    // The slabs of a tile are requested at once and arrive one after the other (64 KiB take the load path of
+    // a compute unit half a microsecond); the multiplication starts on the first while the rest is on its way.
+    // landed<Y>() waits until all but the Y last-requested slabs of this wave's loads have landed, then meets
+    // the other waves.  The loads of a wave retire in order among themselves, so once at most LPS * Y operations
+    // are in flight the older loads are done, whatever stores of the tile before are still among them.
+    constexpr int LPS = LA::L + LB::L;          // loads per thread and slab
+    static_assert(LPS == 4, "the wait counts below are written for four loads per slab");
+    auto landed = [&]<int YOUNGER>() __attribute__((always_inline)) {
+        static_assert(YOUNGER >= 0 && YOUNGER <= 3, "at most four slabs");
+        if constexpr (YOUNGER == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else if constexpr (YOUNGER == 1) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else if constexpr (YOUNGER == 2) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
+
     const int c16 = lane & 15, g4 = lane >> 4;
     f32x4 acc[S::TM][S::TN];
-    auto multiply = [&]() {
-        constexpr uint32_t stage_off = 0;
+    // The slab count is a template parameter: a fragment that has been requested from LDS and not yet waited
+    // for must never cross a branch, where the compiler may copy its registers (before the data is there)
+    // to merge the paths.
+    auto multiply = [&]<int SLABS>() __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < S::TM; ++i)
 #pragma unroll
             for (int j = 0; j < S::TN; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        Frag16Raw af[2][S::TM], bf[2][S::TN];
-        read_slab(af[0], bf[0], stage_off);
-#pragma unroll
-        for (int s = 0; s < S::MAX_SLABS; ++s) {
-            if (s < slabs) {
-                wait_raw8(af[s & 1]);
-                wait_raw8(bf[s & 1]);
-                if (s + 1 < slabs) read_slab(af[(s + 1) & 1], bf[(s + 1) & 1], stage_off + (uint32_t)((s + 1) * S::SLAB));
+        RawA af[2][S::TM];
+        RawB bf[2][S::TN];
+        landed.template operator()<SLABS - 1>();
+        read_slab(af[0], bf[0], 0u);
+        [&]<int... SL>(std::integer_sequence<int, SL...>) __attribute__((always_inline)) {
+            ([&]() __attribute__((always_inline)) {
+                constexpr int s = SL;
+                shortk_wait(af[s & 1]);
+                shortk_wait(bf[s & 1]);
+                if constexpr (s + 1 < SLABS) {
+                    landed.template operator()<SLABS - 2 - s>();
+                    read_slab(af[(s + 1) & 1], bf[(s + 1) & 1], (uint32_t)((s + 1) * S::SLAB));
+                }
 #pragma unroll
                 for (int i = 0; i < S::TM; ++i) {
-                    const u32x4 ua = u32x4{af[s & 1][i].lo.x, af[s & 1][i].lo.y, af[s & 1][i].hi.x, af[s & 1][i].hi.y};
+                    const u32x4 ua = shortk_value(af[s & 1][i]);
 #pragma unroll
                     for (int j = 0; j < S::TN; ++j) {
-                        const u32x4 ub = u32x4{bf[s & 1][j].lo.x, bf[s & 1][j].lo.y, bf[s & 1][j].hi.x, bf[s & 1][j].hi.y};
+                        const u32x4 ub = shortk_value(bf[s & 1][j]);
                         // B's fragment first: the block of C comes out transposed, four consecutive columns per lane
                         if constexpr (IS_BF16)
                             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ub), __builtin_bit_cast(bf16x8, ua), acc[i][j], 0, 0, 0);
@@ -147,8 +194,9 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
                             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ub), __builtin_bit_cast(f16x8, ua), acc[i][j], 0, 0, 0);
                     }
                 }
-            }
+            }(), ...);
         }
+        (std::make_integer_sequence<int, SLABS>{});
     };
 
     // Staged layout of a wave's 64 x 64 results: row r at r * ROW_BYTES, 16-byte unit u of the row at
@@ -156,7 +204,7 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     // 4*g4 .. +3) writes 8 (16-bit results) or 16 bytes; the read-back takes whole units.
     auto unit_pos = [](int row, int unit) { return unit ^ (row & (UNITS - 1)); };
     // alpha, activation, rounding; accumulators -> staging
-    auto stage_results = [&]() {
+    auto stage_results = [&]() __attribute__((always_inline)) {
         const float alpha = a.alpha;
         const int act = a.act;
 #pragma unroll
@@ -185,7 +233,7 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
         }
     };
     // staging -> C: the wave's own quadrant, a lane moves one 16-byte unit of a row per trip
-    auto write_results = [&](const Tile& x) {
+    auto write_results = [&](const Tile& x) __attribute__((always_inline)) {
         constexpr int TRIPS = S::WTM / RPI;
         const int rr = lane / UNITS, u = lane % UNITS;
         const int64_t col = x.n0 + wn * S::WTN + (u * 16) / OB;
@@ -213,15 +261,23 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     };
 
     const int stride = (int)gridDim.x;
-    for (int t = (int)blockIdx.x; t < total_tiles; t += stride) {
-        const Tile x = tile_of(t);
-        request(x);
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");      // the operands are in LDS
-        multiply();
-        asm volatile("s_barrier" ::: "memory");                                       // ... and have been read by every wave
-        stage_results();
-        write_results(x);
-        asm volatile("s_barrier" ::: "memory");                                       // the staged results have been read back
+    auto walk = [&]<int SLABS>() __attribute__((always_inline)) {
+        for (int t = (int)blockIdx.x; t < total_tiles; t += stride) {
+            const Tile x = tile_of(t);
+            request.template operator()<SLABS>(x);
+            multiply.template operator()<SLABS>();
+            asm volatile("s_barrier" ::: "memory");                                   // the operands have been read by every wave
+            stage_results();
+            write_results(x);
+            asm volatile("s_barrier" ::: "memory");                                   // the staged results have been read back
+        }
+    };
+    switch (slabs) {
+        case 1: walk.template operator()<1>(); break;
+        case 2: walk.template operator()<2>(); break;
+        case 3: walk.template operator()<3>(); break;
+        case 4: walk.template operator()<4>(); break;
+        default: break;
     }
 }
 
@@ -252,7 +308,9 @@ inline bool shortk_supports(const Args& a) {
     return tiles < ((int64_t)1 << 30);
 }
 
-inline hipError_t launch_shortk_variant(const Args& a, hipStream_t stream) {
+// (a template, so that only the translation unit that calls it holds the kernels)
+template <int UNUSED = 0>
+hipError_t launch_shortk_variant(const Args& a, hipStream_t stream) {
     if (!shortk_supports(a)) return hipErrorInvalidValue;
     const int tiles_m = (int)((a.M + ShortK::BM - 1) / ShortK::BM), tiles_n = (int)((a.N + ShortK::BN - 1) / ShortK::BN);
     const int total = tiles_m * tiles_n * a.batch;
