@@ -117,15 +117,27 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
         const char* pb = LB::tile_base(x.B, x.n0, a.ldb);
         const int64_t a_bytes = LA::total_bytes(a.M, a.K, a.lda) - (pa - x.A);
         const int64_t b_bytes = LB::total_bytes(a.N, a.K, a.ldb) - (pb - x.B);
+        // Slabs go out in pairs: a k-contiguous operand contributes 64 bytes per row and slab, half a cache
+        // line, and the two loads that fetch the two halves of the same rows, issued next to each other, are
+        // merged into one line request on the way (the L2 serves a half-line request at the cost of a full one).
 #pragma unroll
-        for (int s = 0; s < SLABS; ++s) {
-            const __amdgpu_buffer_rsrc_t ra = make_rsrc(pa + s * a_step, a_bytes - s * a_step);
-            const __amdgpu_buffer_rsrc_t rb = make_rsrc(pb + s * b_step, b_bytes - s * b_step);
+        for (int s = 0; s < SLABS; s += 2) {
+            const bool TWO = s + 1 < SLABS;          // (a constant once the loop is unrolled)
+            const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(pa + s * a_step, a_bytes - s * a_step);
+            const __amdgpu_buffer_rsrc_t rb0 = make_rsrc(pb + s * b_step, b_bytes - s * b_step);
+            const __amdgpu_buffer_rsrc_t ra1 = TWO ? make_rsrc(pa + (s + 1) * a_step, a_bytes - (s + 1) * a_step) : ra0;
+            const __amdgpu_buffer_rsrc_t rb1 = TWO ? make_rsrc(pb + (s + 1) * b_step, b_bytes - (s + 1) * b_step) : rb0;
             char* dst = lds + s * S::SLAB;
 #pragma unroll
-            for (int i = 0; i < LA::L; ++i) la.issue(false, i, ra, dst, wave, tid, s * S::BK, (int)a.K);
+            for (int i = 0; i < LA::L; ++i) {
+                la.issue(false, i, ra0, dst, wave, tid, s * S::BK, (int)a.K);
+                if (TWO) la.issue(false, i, ra1, dst + S::SLAB, wave, tid, (s + 1) * S::BK, (int)a.K);
+            }
 #pragma unroll
-            for (int i = 0; i < LB::L; ++i) lb.issue(false, i, rb, dst + S::A_BYTES, wave, tid, s * S::BK, (int)a.K);
+            for (int i = 0; i < LB::L; ++i) {
+                lb.issue(false, i, rb0, dst + S::A_BYTES, wave, tid, s * S::BK, (int)a.K);
+                if (TWO) lb.issue(false, i, rb1, dst + S::SLAB + S::A_BYTES, wave, tid, (s + 1) * S::BK, (int)a.K);
+            }
         }
     };
 
@@ -143,19 +155,15 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
         (std::make_integer_sequence<int, 4>{});
     };
 
-    // The slabs of a tile are requested at once and arrive one after the other (64 KiB take the load path of
-    // a compute unit half a microsecond); the multiplication starts on the first while the rest is on its way.
-    // landed<Y>() waits until all but the Y last-requested slabs of this wave's loads have landed, then meets
-    // the other waves.  The loads of a wave retire in order among themselves, so once at most LPS * Y operations
-    // are in flight the older loads are done, whatever stores of the tile before are still among them.
+    // The slabs of a tile are requested at once and arrive pair after pair (64 KiB take the load path of a
+    // compute unit half a microsecond); the multiplication starts on the first pair while the second is on its
+    // way.  landed<Y>() waits until all but the Y last-requested loads of this wave have landed, then meets the
+    // other waves.  The loads of a wave retire in order among themselves, so once at most Y operations are in
+    // flight the older loads are done, whatever stores of the tile before are still among them.
     constexpr int LPS = LA::L + LB::L;          // loads per thread and slab
-    static_assert(LPS == 4, "the wait counts below are written for four loads per slab");
     auto landed = [&]<int YOUNGER>() __attribute__((always_inline)) {
-        static_assert(YOUNGER >= 0 && YOUNGER <= 3, "at most four slabs");
-        if constexpr (YOUNGER == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        else if constexpr (YOUNGER == 1) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        else if constexpr (YOUNGER == 2) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        static_assert(YOUNGER >= 0 && YOUNGER < 64, "the counter has six bits");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(YOUNGER) : "memory");
     };
 
     const int c16 = lane & 15, g4 = lane >> 4;
@@ -170,7 +178,7 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
             for (int j = 0; j < S::TN; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         RawA af[2][S::TM];
         RawB bf[2][S::TN];
-        landed.template operator()<SLABS - 1>();
+        landed.template operator()<(SLABS > 2 ? SLABS - 2 : 0) * LPS>();
         read_slab(af[0], bf[0], 0u);
         [&]<int... SL>(std::integer_sequence<int, SL...>) __attribute__((always_inline)) {
             ([&]() __attribute__((always_inline)) {
@@ -178,7 +186,7 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
                 shortk_wait(af[s & 1]);
                 shortk_wait(bf[s & 1]);
                 if constexpr (s + 1 < SLABS) {
-                    landed.template operator()<SLABS - 2 - s>();
+                    if constexpr (s == 1) landed.template operator()<0>();        // the second pair
                     read_slab(af[(s + 1) & 1], bf[(s + 1) & 1], (uint32_t)((s + 1) * S::SLAB));
                 }
 #pragma unroll
