@@ -63,13 +63,12 @@ bool tile_variant_supports(const Args& a, int variant) {
     return a_bytes < 0x7ffffff0ll && b_bytes < 0x7ffffff0ll;
 }
 
-// The persistent short-k kernel (kind 5): whole slabs, K <= 128, C write-only, no bias, stored in 16-byte pieces,
-// the operands of a tile or its staged results inside 64 KiB of LDS.  (Restated here from
+// The persistent short-k kernel (kind 5): whole slabs, K <= 128 (the operands of a tile inside 64 KiB of LDS),
+// C write-only, no bias, stored in 16-byte pieces.  (Restated here from
 // tile_shortk_kernel.hpp, which only the variant's own translation unit includes.)
 bool shortk_call_fits(const Args& a) {
     if (a.K % 32 != 0 || a.K > 128 || a.beta != 0.0f || a.bias != nullptr || a.k_total != 0) return false;
     const int64_t ob = elem_bytes(a.out_dtype);
-    if (128 * 128 * ob > 64 * 1024) return false;
     if (a.N % 8 != 0 || a.ldc % (16 / ob) != 0 || ((uintptr_t)a.C & 15)) return false;
     if (a.batch > 1 && (a.strideC * ob) % 16 != 0) return false;
     return true;

@@ -4,19 +4,22 @@
 // arithmetic and a result to write: the per-head score products of attention are the model case (a
 // batch of 2048 x 2048 x 128 products is 89 % result bytes).  Nothing in such a tile can be pipelined
 // along k, and what the general tile kernels spend around their k loop (launch of a workgroup, ring
-// fill, an epilogue staged in fp32 band by band) is here the whole cost.  This kernel keeps the
-// instruction stream of a tile short and lets two workgroups per compute unit take turns:
+// fill, an epilogue staged in fp32 band by band) is here the whole cost.  What bounds this kernel is
+// the path between a compute unit and the L2 (every tile fetches its operands from there and writes
+// its results through it), so the kernel moves as few bytes over it as it can, in an order that keeps
+// the memory channels evenly busy, and lets two workgroups per compute unit take turns:
 //
-//   a workgroup stays on its compute unit and walks a list of tiles; per tile it
-//     requests all operands of the tile at once into its 64 KiB of LDS (direct-to-LDS loads),
-//     multiplies slab by slab as they land (16x16x32 MFMA, four waves of 64x64),
-//     applies alpha, the activation and the one rounding in the accumulator layout and parks the
-//     results, in the type of C, where the operands were (a region per wave, swizzled in 16-byte units),
-//     reads them back row by row and writes C with full 16-byte stores (128-byte row segments for
-//     16-bit results).
-//   While one workgroup of a compute unit waits for its operands or moves its results, the other
-//   multiplies.  The waits for the operands count this wave's operations in flight; the stores of the
-//   tile before are older than the loads and have had the loads' whole latency to retire.
+//   a workgroup stays on its compute unit and walks a run of consecutive tiles down a column of tiles
+//   of C; per tile it
+//     multiplies pair by pair of slabs as they land in its 64 KiB of LDS (16x16x32 MFMA, four waves
+//       of 64x64),
+//     requests the operands of the next tile (direct-to-LDS loads) as soon as every wave has read this
+//       tile's: all of A, and B only where the column ends (the panel of B stays in LDS otherwise),
+//     applies alpha, the activation and the one rounding in the accumulator layout, brings 16
+//       contiguous bytes of a row of C together in every lane (fp32: as they are; 16-bit: lanes trade
+//       halves with v_permlane16_swap) and writes C from the registers: no pass through LDS.
+//   The waits for the operands count this wave's operations in flight, loads and the younger stores
+//   of the tile before.
 //
 // All LDS traffic is assembly: the compiler would make every LDS access wait for the direct-to-LDS
 // loads in flight.  C is write-only here (beta == 0, no bias); calls with beta != 0, a bias, longer or
@@ -33,8 +36,8 @@ struct ShortK {
     static constexpr int A_BYTES = BM * BK * 2;
     static constexpr int LDS_BYTES = 64 * 1024;          // two workgroups per compute unit
     static constexpr int MAX_SLABS = 4;
-    // bytes of LDS a call needs: the operands of a tile, then (in the same place) its staged results
-    static constexpr int lds_need(int slabs, int out_bytes) { return slabs * SLAB > BM * BN * out_bytes ? slabs * SLAB : BM * BN * out_bytes; }
+    // bytes of LDS a call needs: the operands of a tile
+    static constexpr int lds_need(int slabs) { return slabs * SLAB; }
 };
 
 // Registers of a fragment between its LDS read and the wait for it.  The value of a k-contiguous
@@ -67,9 +70,6 @@ template <bool IS_BF16, bool A_KC, bool B_KC, int OUT>
 __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int tiles_m, int tiles_n, int total_tiles, int slabs) {
     using S = ShortK;
     constexpr int OB = OUT == DT_F32 ? 4 : 2;                 // bytes per result element
-    constexpr int ROW_BYTES = S::WTN * OB;                    // a staged row of a wave: 128 or 256 bytes
-    constexpr int UNITS = ROW_BYTES / 16;                     // 16-byte units per staged row
-    constexpr int RPI = 64 / UNITS;                           // rows per read-back instruction
     __shared__ __attribute__((aligned(1024))) char lds[S::LDS_BYTES];
 
     const int tid = threadIdx.x;
@@ -77,8 +77,6 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
     const uint32_t lds0 = (uint32_t)(uintptr_t)GEMM_LDS_PTR(lds);
-    // staged results: the 64 x 64 quadrant of wave q at q * 64 rows
-    const uint32_t staging0 = lds0 + (uint32_t)(wave * (S::WTM * ROW_BYTES));
 
     using LA = typename std::conditional<A_KC, DmaKC<S::BM, S::BK, S::NT, false>, DmaMC<S::BM, S::BK, S::NT>>::type;
     using LB = typename std::conditional<B_KC, DmaKC<S::BN, S::BK, S::NT, false>, DmaMC<S::BN, S::BK, S::NT>>::type;
@@ -92,7 +90,7 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     struct Tile { int64_t m0, n0; const char* A; const char* B; char* C; };
     auto tile_of = [&](int t) __attribute__((always_inline)) {
         const int b = t / per_matrix, r = t - b * per_matrix;
-        const int tm = r / tiles_n, tn = r - tm * tiles_n;          // consecutive tiles share a panel of A
+        const int tn = r / tiles_m, tm = r - tn * tiles_m;          // consecutive tiles share a panel of B
         Tile x;
         x.m0 = (int64_t)tm * S::BM; x.n0 = (int64_t)tn * S::BN;
         x.A = (const char*)a.A + (int64_t)b * a.strideA * in_b;
@@ -107,36 +105,41 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     la_full.init(tid, a.lda, S::BM);
     lb_full.init(tid, a.ldb, S::BN);
     const int64_t a_step = LA::k_step_bytes(a.lda), b_step = LB::k_step_bytes(a.ldb);
-    // all slabs of tile `x` into LDS: a descriptor per slab, exact range checks
-    auto request = [&]<int SLABS>(const Tile& x) __attribute__((always_inline)) {
-        LA la = la_full;
-        LB lb = lb_full;
-        if (LA::TRANSPOSED && a.M - x.m0 < S::BM) la.init(tid, a.lda, (int)(a.M - x.m0));
-        if (LB::TRANSPOSED && a.N - x.n0 < S::BN) lb.init(tid, a.ldb, (int)(a.N - x.n0));
-        const char* pa = LA::tile_base(x.A, x.m0, a.lda);
-        const char* pb = LB::tile_base(x.B, x.n0, a.ldb);
-        const int64_t a_bytes = LA::total_bytes(a.M, a.K, a.lda) - (pa - x.A);
-        const int64_t b_bytes = LB::total_bytes(a.N, a.K, a.ldb) - (pb - x.B);
-        // Slabs go out in pairs: a k-contiguous operand contributes 64 bytes per row and slab, half a cache
-        // line, and the two loads that fetch the two halves of the same rows, issued next to each other, are
-        // merged into one line request on the way (the L2 serves a half-line request at the cost of a full one).
-#pragma unroll
-        for (int s = 0; s < SLABS; s += 2) {
-            const bool TWO = s + 1 < SLABS;          // (a constant once the loop is unrolled)
+    auto slab_offset = [](int s) { return (uint32_t)(s * S::SLAB); };
+    // Pair PAIR (slabs 2*PAIR, 2*PAIR+1, as far as the tile has them) of tile `x` into LDS: a descriptor per
+    // slab, exact range checks.  Every thread issues the same number of loads per slab (LA::L for A, and LB::L for B where B is requested), whatever the tile.
+    // Slabs go out in pairs: a k-contiguous operand contributes 64 bytes per row and slab, half a cache
+    // line, and the two loads that fetch the two halves of the same rows, issued next to each other, are
+    // merged into one line request on the way (the L2 serves a half-line request at the cost of a full one).
+    auto request_pair = [&]<int SLABS, int PAIR>(const Tile& x, bool with_b) __attribute__((always_inline)) {
+        constexpr int s = 2 * PAIR;
+        if constexpr (s < SLABS) {
+            constexpr bool TWO = s + 1 < SLABS;
+            LA la = la_full;
+            LB lb = lb_full;
+            if (LA::TRANSPOSED && a.M - x.m0 < S::BM) la.init(tid, a.lda, (int)(a.M - x.m0));
+            if (LB::TRANSPOSED && a.N - x.n0 < S::BN) lb.init(tid, a.ldb, (int)(a.N - x.n0));
+            const char* pa = LA::tile_base(x.A, x.m0, a.lda);
+            const char* pb = LB::tile_base(x.B, x.n0, a.ldb);
+            const int64_t a_bytes = LA::total_bytes(a.M, a.K, a.lda) - (pa - x.A);
+            const int64_t b_bytes = LB::total_bytes(a.N, a.K, a.ldb) - (pb - x.B);
             const __amdgpu_buffer_rsrc_t ra0 = make_rsrc(pa + s * a_step, a_bytes - s * a_step);
             const __amdgpu_buffer_rsrc_t rb0 = make_rsrc(pb + s * b_step, b_bytes - s * b_step);
             const __amdgpu_buffer_rsrc_t ra1 = TWO ? make_rsrc(pa + (s + 1) * a_step, a_bytes - (s + 1) * a_step) : ra0;
             const __amdgpu_buffer_rsrc_t rb1 = TWO ? make_rsrc(pb + (s + 1) * b_step, b_bytes - (s + 1) * b_step) : rb0;
-            char* dst = lds + s * S::SLAB;
+            char* dst0 = lds + slab_offset(s);
+            char* dst1 = lds + slab_offset(s + 1);
 #pragma unroll
             for (int i = 0; i < LA::L; ++i) {
-                la.issue(false, i, ra0, dst, wave, tid, s * S::BK, (int)a.K);
-                if (TWO) la.issue(false, i, ra1, dst + S::SLAB, wave, tid, (s + 1) * S::BK, (int)a.K);
+                la.issue(false, i, ra0, dst0, wave, tid, s * S::BK, (int)a.K);
+                if (TWO) la.issue(false, i, ra1, dst1, wave, tid, (s + 1) * S::BK, (int)a.K);
             }
+            if (with_b) {
 #pragma unroll
-            for (int i = 0; i < LB::L; ++i) {
-                lb.issue(false, i, rb0, dst + S::A_BYTES, wave, tid, s * S::BK, (int)a.K);
-                if (TWO) lb.issue(false, i, rb1, dst + S::SLAB + S::A_BYTES, wave, tid, (s + 1) * S::BK, (int)a.K);
+                for (int i = 0; i < LB::L; ++i) {
+                    lb.issue(false, i, rb0, dst0 + S::A_BYTES, wave, tid, s * S::BK, (int)a.K);
+                    if (TWO) lb.issue(false, i, rb1, dst1 + S::A_BYTES, wave, tid, (s + 1) * S::BK, (int)a.K);
+                }
             }
         }
     };
@@ -155,12 +158,12 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
         (std::make_integer_sequence<int, 4>{});
     };
 
-    // The slabs of a tile are requested at once and arrive pair after pair (64 KiB take the load path of a
-    // compute unit half a microsecond); the multiplication starts on the first pair while the second is on its
-    // way.  landed<Y>() waits until all but the Y last-requested loads of this wave have landed, then meets the
-    // other waves.  The loads of a wave retire in order among themselves, so once at most Y operations are in
-    // flight the older loads are done, whatever stores of the tile before are still among them.
-    constexpr int LPS = LA::L + LB::L;          // loads per thread and slab
+    // What a wave has in flight when it starts on a tile, oldest first: the loads of the first pair of slabs,
+    // the loads of the second pair, the stores of the tile before (see the tile loop).  Loads and stores of a
+    // wave retire in the order of issue as far as the counter shows (the compiler's own waits rely on the same:
+    // it waits for a load with vmcnt(1) while a younger store is in flight), so once at most Y operations are
+    // outstanding everything but the Y youngest is done.  landed<Y>() waits for that, then meets the other waves.
+    constexpr int NST = OB == 2 ? S::TM * S::TN / 2 : S::TM * S::TN;      // stores per wave and whole tile
     auto landed = [&]<int YOUNGER>() __attribute__((always_inline)) {
         static_assert(YOUNGER >= 0 && YOUNGER < 64, "the counter has six bits");
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(YOUNGER) : "memory");
@@ -171,23 +174,23 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     // The slab count is a template parameter: a fragment that has been requested from LDS and not yet waited
     // for must never cross a branch, where the compiler may copy its registers (before the data is there)
     // to merge the paths.
-    auto multiply = [&]<int SLABS>() __attribute__((always_inline)) {
+    auto multiply = [&]<int SLABS, int LOADS>() __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < S::TM; ++i)
 #pragma unroll
             for (int j = 0; j < S::TN; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         RawA af[2][S::TM];
         RawB bf[2][S::TN];
-        landed.template operator()<(SLABS > 2 ? SLABS - 2 : 0) * LPS>();
-        read_slab(af[0], bf[0], 0u);
+        landed.template operator()<(SLABS > 2 ? SLABS - 2 : 0) * LOADS + NST>();    // the first pair
+        read_slab(af[0], bf[0], slab_offset(0));
         [&]<int... SL>(std::integer_sequence<int, SL...>) __attribute__((always_inline)) {
             ([&]() __attribute__((always_inline)) {
                 constexpr int s = SL;
                 shortk_wait(af[s & 1]);
                 shortk_wait(bf[s & 1]);
                 if constexpr (s + 1 < SLABS) {
-                    if constexpr (s == 1) landed.template operator()<0>();        // the second pair
-                    read_slab(af[(s + 1) & 1], bf[(s + 1) & 1], (uint32_t)((s + 1) * S::SLAB));
+                    if constexpr (s == 1) landed.template operator()<NST>();      // the second pair
+                    read_slab(af[(s + 1) & 1], bf[(s + 1) & 1], slab_offset(s + 1));
                 }
 #pragma unroll
                 for (int i = 0; i < S::TM; ++i) {
@@ -207,77 +210,134 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
         (std::make_integer_sequence<int, SLABS>{});
     };
 
-    // Staged layout of a wave's 64 x 64 results: row r at r * ROW_BYTES, 16-byte unit u of the row at
-    // position u xor (r mod UNITS').  A lane of the accumulator layout (row c16 of a block, columns
-    // 4*g4 .. +3) writes 8 (16-bit results) or 16 bytes; the read-back takes whole units.
-    auto unit_pos = [](int row, int unit) { return unit ^ (row & (UNITS - 1)); };
-    // alpha, activation, rounding; accumulators -> staging
-    auto stage_results = [&]() __attribute__((always_inline)) {
+    // Accumulators -> C, without a pass through LDS.  With B's fragment first a lane of the accumulator layout
+    // holds four consecutive columns of one row of a 16 x 16 block: row c16 of the block, columns 4*g4 .. +3,
+    // where g4 numbers the wave's four rows of 16 lanes.  An fp32 C takes them as they are: 16 bytes per lane,
+    // 64 contiguous bytes per row of C and instruction.  For a 16-bit C they are 8 bytes, and two neighbouring
+    // blocks (columns 16j .. and 16j' .. of the same rows) trade halves first: v_permlane16_swap exchanges the
+    // odd lane rows of its first operand with the even lane rows of its second, after which lane row 0 holds
+    // columns 0-7 of block j, lane row 1 columns 0-7 of block j', lane rows 2 and 3 columns 8-15 of j and j':
+    // 16 bytes per lane and again 64 contiguous bytes per row of C.  The two stores that complete a row's
+    // 128-byte line follow each other.
+    auto whole = [&](const Tile& x) { return x.m0 + S::BM <= a.M && x.n0 + S::BN <= a.N; };
+    // A whole tile takes exactly NST store instructions per wave (assembly, so that the count is the source's
+    // and not the compiler's); an edge tile takes as many as have a lane inside C.
+    auto store16 = [&](bool inside_tile, bool lane_inside, char* p, u32x4 d) __attribute__((always_inline)) {
+        if (inside_tile) asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(d) : "memory");
+        else if (lane_inside) __builtin_nontemporal_store(d, (u32x4*)p);
+    };
+    auto epilogue = [&](const Tile& x) __attribute__((always_inline)) {
         const float alpha = a.alpha;
         const int act = a.act;
+        const bool inside = whole(x);
+        const int64_t row0 = x.m0 + wm * S::WTM + c16;              // this lane's row in block row 0
+        const int64_t colw = x.n0 + wn * S::WTN;                    // the wave's first column
+        const int64_t row_step = (int64_t)16 * a.ldc * out_b;
+        if constexpr (OB == 4) {
+            const int64_t col = colw + 4 * g4;
+            char* p = x.C + (row0 * a.ldc + col) * out_b;
 #pragma unroll
-        for (int j = 0; j < S::TN; ++j) {
-            f32x4 v[S::TM];
+            for (int j = 0; j < S::TN; ++j) {
+                f32x4 v[S::TM];
 #pragma unroll
-            for (int i = 0; i < S::TM; ++i) v[i] = alpha * acc[i][j];
-            apply_act4(v, act);
+                for (int i = 0; i < S::TM; ++i) v[i] = alpha * acc[i][j];
+                apply_act4(v, act);
 #pragma unroll
-            for (int i = 0; i < S::TM; ++i) {
-                const int row = 16 * i + c16;
-                const int byte_in_row = (16 * j + 4 * g4) * OB;
-                const uint32_t addr = staging0 + (uint32_t)(row * ROW_BYTES + (unit_pos(row, byte_in_row >> 4) << 4) + (byte_in_row & 15));
-                if constexpr (OUT == DT_F32) {
-                    asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v[i]) : "memory");
-                } else if constexpr (OUT == DT_BF16) {
-                    typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-                    const u32x2 p = __builtin_bit_cast(u32x2, __builtin_convertvector(v[i], bf16x4));
-                    asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(p) : "memory");
-                } else {
-                    typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
-                    const u32x2 p = __builtin_bit_cast(u32x2, __builtin_convertvector(v[i], f16x4));
-                    asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(p) : "memory");
+                for (int i = 0; i < S::TM; ++i)
+                    store16(inside, row0 + 16 * i < a.M && col + 16 * j < a.N, p + i * row_step + j * 16 * out_b, __builtin_bit_cast(u32x4, v[i]));
+            }
+        } else {
+            const int64_t col = colw + 16 * (g4 & 1) + 8 * (g4 >> 1);      // of the first pair of blocks; the second 32 further
+            char* p = x.C + (row0 * a.ldc + col) * out_b;
+#pragma unroll
+            for (int jp = 0; jp < S::TN / 2; ++jp) {
+                u32x2 packed[2][S::TM];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    f32x4 v[S::TM];
+#pragma unroll
+                    for (int i = 0; i < S::TM; ++i) v[i] = alpha * acc[i][2 * jp + h];
+                    apply_act4(v, act);
+#pragma unroll
+                    for (int i = 0; i < S::TM; ++i) {
+                        if constexpr (OUT == DT_BF16) {
+                            typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+                            packed[h][i] = __builtin_bit_cast(u32x2, __builtin_convertvector(v[i], bf16x4));
+                        } else {
+                            typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+                            packed[h][i] = __builtin_bit_cast(u32x2, __builtin_convertvector(v[i], f16x4));
+                        }
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < S::TM; ++i) {
+                    const auto lo = __builtin_amdgcn_permlane16_swap(packed[0][i].x, packed[1][i].x, false, false);
+                    const auto hi = __builtin_amdgcn_permlane16_swap(packed[0][i].y, packed[1][i].y, false, false);
+                    store16(inside, row0 + 16 * i < a.M && col + 32 * jp < a.N, p + i * row_step + jp * 32 * out_b, u32x4{lo[0], hi[0], lo[1], hi[1]});
                 }
             }
         }
     };
-    // staging -> C: the wave's own quadrant, a lane moves one 16-byte unit of a row per trip
-    auto write_results = [&](const Tile& x) __attribute__((always_inline)) {
-        constexpr int TRIPS = S::WTM / RPI;
-        const int rr = lane / UNITS, u = lane % UNITS;
-        const int64_t col = x.n0 + wn * S::WTN + (u * 16) / OB;
-        const int64_t row0 = x.m0 + wm * S::WTM + rr;
-        u32x4 d[TRIPS];
-#pragma unroll
-        for (int it = 0; it < TRIPS; ++it) {
-            const int row = it * RPI + rr;
-            const uint32_t addr = staging0 + (uint32_t)(row * ROW_BYTES + (unit_pos(row, u) << 4));
-            asm volatile("ds_read_b128 %0, %1" : "=v"(d[it]) : "v"(addr) : "memory");
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int it = 0; it < TRIPS; ++it) asm volatile("" : "+v"(d[it]));          // nothing that uses the data moves ahead of the wait
-        char* p = x.C + (row0 * a.ldc + col) * out_b;
-        const int64_t step = (int64_t)RPI * a.ldc * out_b;
-        if (x.m0 + S::BM <= a.M && x.n0 + S::BN <= a.N) {          // whole tile inside C: no lane conditions
-#pragma unroll
-            for (int it = 0; it < TRIPS; ++it) __builtin_nontemporal_store(d[it], (u32x4*)(p + it * step));
-        } else if (col < a.N) {                                      // N is a multiple of 8: a unit lies inside or outside as a whole
-#pragma unroll
-            for (int it = 0; it < TRIPS; ++it)
-                if (row0 + it * RPI < a.M) __builtin_nontemporal_store(d[it], (u32x4*)(p + it * step));
-        }
-    };
 
-    const int stride = (int)gridDim.x;
+    // The tile loop.  The operands of the next tile are requested as soon as every wave has read this tile's
+    // (the epilogue needs no LDS), ahead of this tile's stores, so that they do not queue behind them.  The
+    // multiplication's waits count NST younger stores; where the tile before was the first, or an edge tile
+    // with fewer stores, everything in flight is awaited instead.
+    // Which tiles a workgroup takes: a run of consecutive tiles.  Consecutive tiles share their panel of B
+    // (until the column of tiles ends), which then stays where it is in LDS: only A is requested, half the
+    // bytes.  Workgroups whose runs start in neighbouring columns of tiles walk down C side by side: what the
+    // chip writes at any moment is spread over the width of C, and with it over the memory channels (runs along
+    // the rows of C, with A staying, had every workgroup write the same few channels at once: 110 us for the
+    // batch below instead of 68), and a panel of A is fetched once for the workgroups that need it together.
+    // Workgroups are handed to the chip's XCDs in turn (workgroup b runs on XCD b mod 8), and each XCD has an L2
+    // of its own: a matrix whose tiles are dealt out over all workgroups is fetched once by every XCD.  So the
+    // tile list is first cut into eight contiguous parts, one per XCD, and each part into the runs of that
+    // XCD's workgroups: the whole operands of a small matrix of a batch then come through one L2 only.
+    constexpr int XCDS = 8;
+    int first, last;
+    {
+        int wg = (int)blockIdx.x, wgs = (int)gridDim.x, lo = 0, hi = total_tiles;
+        if (wgs % XCDS == 0) {
+            const int xcd = wg % XCDS, part = (total_tiles + XCDS - 1) / XCDS;
+            lo = xcd * part < total_tiles ? xcd * part : total_tiles;
+            hi = lo + part < total_tiles ? lo + part : total_tiles;
+            wg /= XCDS;
+            wgs /= XCDS;
+        }
+        const int run = (hi - lo + wgs - 1) / wgs;
+        first = lo + wg * run < hi ? lo + wg * run : hi;
+        last = first + run < hi ? first + run : hi;
+    }
+    // The operands of the next tile are requested as soon as every wave has read this tile's (the epilogue
+    // needs no LDS), ahead of this tile's stores, so that they do not queue behind them.  The multiplication's
+    // waits count NST younger stores; where the tile before was the first, or an edge tile with fewer stores,
+    // everything in flight is awaited instead.
     auto walk = [&]<int SLABS>() __attribute__((always_inline)) {
-        for (int t = (int)blockIdx.x; t < total_tiles; t += stride) {
-            const Tile x = tile_of(t);
-            request.template operator()<SLABS>(x);
-            multiply.template operator()<SLABS>();
+        int t = first;
+        if (t >= last) return;
+        Tile x = tile_of(t);
+        bool with_b = true;
+        request_pair.template operator()<SLABS, 0>(x, true);
+        request_pair.template operator()<SLABS, 1>(x, true);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        while (true) {
+            if (with_b) multiply.template operator()<SLABS, LA::L + LB::L>();
+            else multiply.template operator()<SLABS, LA::L>();
             asm volatile("s_barrier" ::: "memory");                                   // the operands have been read by every wave
-            stage_results();
-            write_results(x);
-            asm volatile("s_barrier" ::: "memory");                                   // the staged results have been read back
+            const int tn = t + 1;
+            const bool more = tn < last;
+            Tile xn = x;
+            if (more) {
+                xn = tile_of(tn);
+                with_b = xn.n0 != x.n0 || xn.B != x.B;
+                request_pair.template operator()<SLABS, 0>(xn, with_b);
+                request_pair.template operator()<SLABS, 1>(xn, with_b);
+            }
+            epilogue(x);
+            if (!whole(x)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (!more) break;
+            x = xn;
+            t = tn;
         }
     };
     switch (slabs) {
@@ -307,7 +367,7 @@ inline bool shortk_supports(const Args& a) {
     if (a.K % ShortK::BK != 0 || a.K > ShortK::MAX_SLABS * ShortK::BK || a.K <= 0) return false;
     if (a.beta != 0.0f || a.bias != nullptr || a.k_total != 0) return false;
     const int ob = elem_bytes(a.out_dtype);
-    if (ShortK::lds_need((int)(a.K / ShortK::BK), ob) > ShortK::LDS_BYTES) return false;
+    if (ShortK::lds_need((int)(a.K / ShortK::BK)) > ShortK::LDS_BYTES) return false;
     // 16-byte stores to C
     const int64_t per16 = 16 / ob;
     if (a.N % 8 != 0 || a.ldc % per16 != 0 || ((uintptr_t)a.C & 15)) return false;

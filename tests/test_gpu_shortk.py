@@ -69,6 +69,24 @@ def test_shortk_many_tiles_per_workgroup_integer_exact(handle, tb):
         lg.gemm_set_plan(handle)
 
 
+@pytest.mark.parametrize("K,ta,tb,out", [(128, 0, 1, wl.BF16), (96, 0, 0, wl.F32), (64, 1, 1, wl.F16), (32, 1, 0, wl.BF16)])
+def test_shortk_runs_of_tiles_with_ragged_edges(handle, K, ta, tb, out):
+    # 6 x 17 x 17 = 1734 tiles on 512 workgroups: runs of four tiles that cross the ragged last row of tiles
+    # (fewer stores than a whole tile), the end of a column of tiles (B changes) and the end of a matrix;
+    # integer data, unique answer in every output type
+    M, N = 2104, 2088
+    dtype = wl.F16 if out == wl.F16 else wl.BF16
+    cfg = cfg_of(M, N, K, ta, tb, dtype, out, alpha=1.0, lda=(M if ta else K) + 8, ldb=(K if tb else N) + 8, ldc=N + 8)
+    lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, SHORTK, 1)
+    try:
+        p = BatchedDeviceProblem(cfg, 6, cfg.stride_a() + 8, cfg.stride_b() + 16, cfg.stride_c() + 8, seed=51 + K, integer=True)
+        p.run(handle)
+        assert lg.gemm_get_last_plan(handle)[:2] == (lg.GEMM_KERNEL_MFMA_TILE, SHORTK)
+        p.check(f"shortk, runs with edges K={K} {ta}{tb} out={out}", exact=True)
+    finally:
+        lg.gemm_set_plan(handle)
+
+
 def test_shortk_refusals_and_automatic_choice(handle):
     lg.gemm_set_plan(handle, lg.GEMM_KERNEL_MFMA_TILE, SHORTK, 1)
     try:
