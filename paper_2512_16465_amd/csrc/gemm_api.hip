@@ -58,8 +58,9 @@ constexpr int kLargeTileVariant = 10, kLargeTileFallback = 0, kSmallTileVariant 
 // K = 512 on: 4096x4096x512 27 against 25, 256x4096x512 7.4 against 6.7; slices take the ring of four)
 constexpr int kSmallTileShortK = 12;
 constexpr int64_t kShortK = 256;
-// ... and for K <= 128 with at least two tiles per compute unit the persistent kernel, which overlaps the
-// loads, the arithmetic and the stores of successive tiles (32 x 2048x2048x128: see the bench row X8)
+// ... and for K <= 128 with at least a tile per compute unit the persistent kernel, which keeps a panel of B in
+// LDS, writes C from the registers and lets two workgroups per compute unit take turns (32 x 2048x2048x128: the
+// bench row X8; level with the small tile from 256 tiles on, ahead from 512)
 constexpr int kPersistentShortK = 17;
 constexpr double kSmallPerK = 0.0094, kSmallFixed = 1.4;     // (the large tile's 0.0203 us per k and 12 us fixed: kFullTile below)
 // A last round that fills less than this fraction of the compute units is split along K (when the
@@ -281,7 +282,7 @@ TileChoice choose_tile(const Args& a, int num_cus) {
         const double tq = dma16_time(kQuarterTile, a, cus, true, &p, &f);
         if (p > 1) return TileChoice{kQuarterTile.variant, (int)f, p, tq};
     }
-    if (slices == 1 && small >= 2 * cus && gemm::tile_variant_supports(a, kPersistentShortK)) return TileChoice{kPersistentShortK, 0, 1, t_small};
+    if (slices == 1 && small >= cus && gemm::tile_variant_supports(a, kPersistentShortK)) return TileChoice{kPersistentShortK, 0, 1, t_small};
     return TileChoice{slices == 1 && a.K <= kShortK ? kSmallTileShortK : kSmallTileVariant, 0, slices, t_small};
 }
 

@@ -223,7 +223,9 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     // A whole tile takes exactly NST store instructions per wave (assembly, so that the count is the source's
     // and not the compiler's); an edge tile takes as many as have a lane inside C.
     auto store16 = [&](bool inside_tile, bool lane_inside, char* p, u32x4 d) __attribute__((always_inline)) {
-        if (inside_tile) asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(d) : "memory");
+        // (a vector instruction that writes the data registers of a store of more than 8 bytes must stay two wait
+        // states behind it; the compiler sees to that for its own stores and cannot know that this is one)
+        if (inside_tile) asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 1" ::"v"(p), "v"(d) : "memory");
         else if (lane_inside) __builtin_nontemporal_store(d, (u32x4*)p);
     };
     auto epilogue = [&](const Tile& x) __attribute__((always_inline)) {

@@ -157,3 +157,32 @@ def check_listing(lines, only=None):
         seen += 1
         findings += [(name,) + r for r in check_function(body)]
     return seen, findings
+
+
+WIDE_STORE = re.compile(r"^(global|flat|buffer|scratch)_store_dwordx[34]\b")
+
+
+def check_wide_store_data(lines, only=None, wait_states=2):
+    """A vector instruction that writes a data register of a store of more than 8 bytes must stay
+    `wait_states` instructions behind that store (gfx940 family: 2; s_nop n counts as n + 1).  The compiler
+    sees to it after its own stores; a store written as inline assembly must bring the distance along.
+    [(function, line number, registers, instruction)]"""
+    findings = []
+    for name, body in functions(lines):
+        if only and only not in name:
+            continue
+        data, left = None, 0
+        for n, code in body:
+            if code.endswith(":"):
+                continue
+            op = code.split()[0]
+            if left > 0 and op.startswith("v_"):
+                hit = regs(code[len(op):].split(",")[0]) & data
+                if hit:
+                    findings.append((name, n, sorted(hit), code))
+            left -= (int(code.split()[1], 0) + 1) if op == "s_nop" else 1
+            if WIDE_STORE.match(op):
+                operands = code[len(op):].split(",")
+                # global/flat/scratch: address, data; buffer: data first
+                data, left = regs(operands[0] if op.startswith("buffer") else operands[1]), wait_states
+    return findings

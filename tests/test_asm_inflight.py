@@ -8,7 +8,7 @@ import os
 
 import pytest
 
-from asm_inflight import check_listing
+from asm_inflight import check_listing, check_wide_store_data
 
 # ---- the checker itself, on listings small enough to read ----
 
@@ -71,6 +71,23 @@ def test_checker_follows_the_control_flow_graph():
     assert len(findings(ACROSS_A_LOOP.replace("AFTER_THE_LOOP", "ds_read_b64_tr_b16 v[6:7], v2"))) == 1
 
 
+def test_checker_flags_a_write_to_store_data_right_behind_a_wide_store():
+    text = """
+_Z1kv:
+	global_store_dwordx4 v[10:11], v[4:7], off nt
+	NEXT
+	s_endpgm
+"""
+    write = "v_lshl_add_u64 v[4:5], v[10:11], 0, s[2:3]"
+    assert len(check_wide_store_data(text.replace("NEXT", write).splitlines())) == 1
+    assert len(check_wide_store_data(text.replace("NEXT", "s_nop 0\n\t" + write).splitlines())) == 1
+    assert len(check_wide_store_data(text.replace("NEXT", "s_mov_b32 s0, 0\n\t" + write).splitlines())) == 1
+    assert check_wide_store_data(text.replace("NEXT", "s_nop 1\n\t" + write).splitlines()) == []
+    assert check_wide_store_data(text.replace("NEXT", "s_nop 0\n\ts_mov_b32 s0, 0\n\t" + write).splitlines()) == []
+    assert check_wide_store_data(text.replace("NEXT", "v_lshl_add_u64 v[10:11], v[10:11], 0, s[2:3]").splitlines()) == []
+    assert check_wide_store_data(text.replace("x4", "x2").replace("NEXT", "v_mov_b32_e32 v4, 0").splitlines()) == []
+
+
 # ---- the library's kernels ----
 
 # every direct-to-LDS variant that the automatic plan can choose, and the kernel family in its unit
@@ -99,3 +116,6 @@ def test_no_fragment_register_is_touched_before_its_wait(listings, unit, family)
         kernels, found = check_listing(f, only=family)
     assert kernels >= 8, f"{unit}: expected the instantiations of {family}, found {kernels} kernels"
     assert not found, f"{unit}: {len(found)} findings, first: {found[0]}"
+    with open(listings[unit]) as f:
+        found = check_wide_store_data(f)
+    assert not found, f"{unit}: wide store data overwritten without a wait state, first: {found[0]}"

@@ -69,7 +69,7 @@ def test_shortk_many_tiles_per_workgroup_integer_exact(handle, tb):
         lg.gemm_set_plan(handle)
 
 
-@pytest.mark.parametrize("K,ta,tb,out", [(128, 0, 1, wl.BF16), (96, 0, 0, wl.F32), (64, 1, 1, wl.F16), (32, 1, 0, wl.BF16)])
+@pytest.mark.parametrize("K,ta,tb,out", [(128, 0, 1, wl.BF16), (96, 0, 0, wl.F32), (64, 1, 1, wl.F16), (32, 1, 0, wl.BF16), (128, 0, 1, wl.F32), (32, 0, 0, wl.F32)])
 def test_shortk_runs_of_tiles_with_ragged_edges(handle, K, ta, tb, out):
     # 6 x 17 x 17 = 1734 tiles on 512 workgroups: runs of four tiles that cross the ragged last row of tiles
     # (fewer stores than a whole tile), the end of a column of tiles (B changes) and the end of a matrix;
@@ -99,7 +99,7 @@ def test_shortk_refusals_and_automatic_choice(handle):
             assert p.run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED, cfg
     finally:
         lg.gemm_set_plan(handle)
-    # the automatic plan takes it for a batch of short products with two or more tiles per compute unit ...
+    # the automatic plan takes it for a batch of short products with a tile or more per compute unit ...
     cfg = cfg_of(1024, 1024, 128, 0, 1, wl.BF16, wl.BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.1))
     p = BatchedDeviceProblem(cfg, 8, cfg.stride_a(), cfg.stride_b(), cfg.stride_c(), seed=33)
     p.run(handle)
