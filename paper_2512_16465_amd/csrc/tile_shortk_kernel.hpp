@@ -217,8 +217,8 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
     // blocks (columns 16j .. and 16j' .. of the same rows) trade halves first: v_permlane16_swap exchanges the
     // odd lane rows of its first operand with the even lane rows of its second, after which lane row 0 holds
     // columns 0-7 of block j, lane row 1 columns 0-7 of block j', lane rows 2 and 3 columns 8-15 of j and j':
-    // 16 bytes per lane and again 64 contiguous bytes per row of C.  The two stores that complete a row's
-    // 128-byte line follow each other.
+    // 16 bytes per lane and again 64 contiguous bytes per row of C.  A second exchange (whole_lines below) makes
+    // whole 128-byte lines of them.
     auto whole = [&](const Tile& x) { return x.m0 + S::BM <= a.M && x.n0 + S::BN <= a.N; };
     // A whole tile takes exactly NST store instructions per wave (assembly, so that the count is the source's
     // and not the compiler's); an edge tile takes as many as have a lane inside C.
@@ -228,31 +228,59 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
         if (inside_tile) asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 1" ::"v"(p), "v"(d) : "memory");
         else if (lane_inside) __builtin_nontemporal_store(d, (u32x4*)p);
     };
+    // Two 16-byte pieces per lane, `lower` 64 bytes before `upper` in the same row of C, held for rows c16 of a
+    // block of 16 rows, become whole 128-byte lines: the two halves of each 16-lane row trade pieces (a rotation
+    // by 8 within the row, written under a bank mask), after which lanes c16 < 8 hold `lower` and lanes
+    // c16 >= 8 hold `upper` of the same eight rows, rows 0-7 in the first result and rows 8-15 in the second.
+    // A store of 64-byte pieces is not only smaller: the L2 writes a line again when its other half arrives
+    // (13 % more bytes written than C has for the batch of 32 products 2048 x 2048 x 128, 45 % with the two halves
+    // stored back to back).
+    auto whole_lines = [&](u32x4 lower, u32x4 upper, u32x4& rows_0_7, u32x4& rows_8_15) __attribute__((always_inline)) {
+        constexpr int ROR8 = 0x128;         // row_ror:8
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            rows_0_7[q] = (uint32_t)__builtin_amdgcn_update_dpp((int)lower[q], (int)upper[q], ROR8, 0xf, 0xc, false);
+            rows_8_15[q] = (uint32_t)__builtin_amdgcn_update_dpp((int)upper[q], (int)lower[q], ROR8, 0xf, 0x3, false);
+        }
+    };
     auto epilogue = [&](const Tile& x) __attribute__((always_inline)) {
         const float alpha = a.alpha;
         const int act = a.act;
         const bool inside = whole(x);
-        const int64_t row0 = x.m0 + wm * S::WTM + c16;              // this lane's row in block row 0
+        const int r8 = c16 & 7, up = c16 >> 3;                      // row inside a half block; 1: this lane stores the upper piece
+        const int64_t row0 = x.m0 + wm * S::WTM + r8;               // this lane's row in the first half of block row 0
         const int64_t colw = x.n0 + wn * S::WTN;                    // the wave's first column
-        const int64_t row_step = (int64_t)16 * a.ldc * out_b;
+        const int64_t row_step = (int64_t)16 * a.ldc * out_b, half_step = (int64_t)8 * a.ldc * out_b;
         if constexpr (OB == 4) {
-            const int64_t col = colw + 4 * g4;
-            char* p = x.C + (row0 * a.ldc + col) * out_b;
-#pragma unroll
-            for (int j = 0; j < S::TN; ++j) {
-                f32x4 v[S::TM];
-#pragma unroll
-                for (int i = 0; i < S::TM; ++i) v[i] = alpha * acc[i][j];
-                apply_act4(v, act);
-#pragma unroll
-                for (int i = 0; i < S::TM; ++i)
-                    store16(inside, row0 + 16 * i < a.M && col + 16 * j < a.N, p + i * row_step + j * 16 * out_b, __builtin_bit_cast(u32x4, v[i]));
-            }
-        } else {
-            const int64_t col = colw + 16 * (g4 & 1) + 8 * (g4 >> 1);      // of the first pair of blocks; the second 32 further
+            // a line is 32 columns: blocks j (lower piece) and j + 1 (upper piece)
+            const int64_t col = colw + 16 * up + 4 * g4;
             char* p = x.C + (row0 * a.ldc + col) * out_b;
 #pragma unroll
             for (int jp = 0; jp < S::TN / 2; ++jp) {
+                f32x4 v[2][S::TM];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                    for (int i = 0; i < S::TM; ++i) v[h][i] = alpha * acc[i][2 * jp + h];
+                    apply_act4(v[h], act);
+                }
+#pragma unroll
+                for (int i = 0; i < S::TM; ++i) {
+                    u32x4 d0, d1;
+                    whole_lines(__builtin_bit_cast(u32x4, v[0][i]), __builtin_bit_cast(u32x4, v[1][i]), d0, d1);
+                    const bool cols_in = col + 32 * jp < a.N;
+                    store16(inside, row0 + 16 * i < a.M && cols_in, p + i * row_step + jp * 32 * out_b, d0);
+                    store16(inside, row0 + 16 * i + 8 < a.M && cols_in, p + i * row_step + half_step + jp * 32 * out_b, d1);
+                }
+            }
+        } else {
+            // a line is the wave's 64 columns: the pair of blocks 0, 1 (lower piece) and the pair 2, 3 (upper piece)
+            static_assert(S::TN == 4, "two pairs of blocks make one line");
+            const int64_t col = colw + 32 * up + 16 * (g4 & 1) + 8 * (g4 >> 1);
+            char* p = x.C + (row0 * a.ldc + col) * out_b;
+            u32x4 piece[2][S::TM];
+#pragma unroll
+            for (int jp = 0; jp < 2; ++jp) {
                 u32x2 packed[2][S::TM];
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
@@ -275,8 +303,16 @@ __global__ __launch_bounds__(ShortK::NT, 2) void tile_shortk_kernel(Args a, int 
                 for (int i = 0; i < S::TM; ++i) {
                     const auto lo = __builtin_amdgcn_permlane16_swap(packed[0][i].x, packed[1][i].x, false, false);
                     const auto hi = __builtin_amdgcn_permlane16_swap(packed[0][i].y, packed[1][i].y, false, false);
-                    store16(inside, row0 + 16 * i < a.M && col + 32 * jp < a.N, p + i * row_step + jp * 32 * out_b, u32x4{lo[0], hi[0], lo[1], hi[1]});
+                    piece[jp][i] = u32x4{lo[0], hi[0], lo[1], hi[1]};
                 }
+            }
+            const bool cols_in = col < a.N;
+#pragma unroll
+            for (int i = 0; i < S::TM; ++i) {
+                u32x4 d0, d1;
+                whole_lines(piece[0][i], piece[1][i], d0, d1);
+                store16(inside, row0 + 16 * i < a.M && cols_in, p + i * row_step, d0);
+                store16(inside, row0 + 16 * i + 8 < a.M && cols_in, p + i * row_step + half_step, d1);
             }
         }
     };
