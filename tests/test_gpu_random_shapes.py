@@ -68,3 +68,37 @@ def test_random_calls_match_the_oracle_exactly(handle, seed):
         if cfg.ld_c() > cfg.N and cfg.M > 1:
             assert np.array_equal(before[:-1, cfg.N:].view(np.uint8), after[:-1, cfg.N:].view(np.uint8)), f"{what}: padding of C written"
     assert len(seen) >= 3, seen       # the draw reaches several kernels
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_batches_of_short_products_match_the_oracle_exactly(handle, seed):
+    """Strided batches with K <= 128 and a tile or more per compute unit, shapes drawn around the tile edges: the
+    automatic plan's persistent short-k kernel where C is write-only, the other tile kernels where it is not."""
+    from gpu_harness import BatchedDeviceProblem
+    rng = np.random.default_rng([31415, seed])
+    seen = set()
+    for i in range(4):
+        M = int(rng.choice([1024, 1032, 1160, 1536, 2040, 2176]))
+        N = int(rng.choice([1024, 1032, 1288, 1536, 2056]))
+        K = int(rng.choice([32, 64, 96, 128]))
+        batch = int(rng.integers(2, 7))
+        ta, tb = int(rng.integers(2)), int(rng.integers(2))
+        dtype = int(rng.choice([wl.BF16, wl.F16]))
+        out = dtype if rng.random() < 0.6 else wl.F32
+        plain = rng.random() < 0.75                      # write-only C, no bias: what the short-k kernel takes
+        pad = lambda: int(rng.choice([0, 8, 24]))
+        cfg = wl.Config("random", M, N, K, ta, tb, dtype, out, alpha=float(rng.choice([1.0, 2.0, -0.5])),
+                        beta=0.0 if plain else float(rng.choice([1.0, -2.0])),
+                        bias_dist=None if plain else ("normal", 1.0), bias_dtype=wl.F32,
+                        act=int(rng.choice([wl.ACT_NONE, wl.ACT_RELU])),
+                        lda=(M if ta else K) + pad(), ldb=(K if tb else N) + pad(), ldc=N + int(rng.choice([0, 8, 16])))
+        what = (f"seed {seed} case {i}: {batch} x {M}x{N}x{K} ta={ta} tb={tb} dtype={dtype} out={out} "
+                f"ld=({cfg.ld_a()},{cfg.ld_b()},{cfg.ld_c()}) alpha={cfg.alpha} beta={cfg.beta} act={cfg.act}")
+        print(what, flush=True)
+        p = BatchedDeviceProblem(cfg, batch, cfg.stride_a() + 8 * int(rng.integers(3)), cfg.stride_b() + 8 * int(rng.integers(3)),
+                                 cfg.stride_c() + 8 * int(rng.integers(3)), seed=1000 * seed + 10 * i, integer=True)
+        p.run(handle)
+        kernel, variant, split = lg.gemm_get_last_plan(handle)
+        seen.add(lg.gemm_variant_name(kernel, variant))
+        p.check(what + f" ({lg.gemm_variant_name(kernel, variant)}, split {split})", exact=True)
+    assert any("shortk" in name for name in seen), seen
