@@ -17,7 +17,8 @@
 //       tile's: all of A, and B only where the column ends (the panel of B stays in LDS otherwise),
 //     applies alpha, the activation and the one rounding in the accumulator layout, brings 16
 //       contiguous bytes of a row of C together in every lane (fp32: as they are; 16-bit: lanes trade
-//       halves with v_permlane16_swap) and writes C from the registers: no pass through LDS.
+//       halves with v_permlane16_swap), then the two halves of each 128-byte line in one instruction
+//       (a rotation within the 16-lane rows), and writes C from the registers: no pass through LDS.
 //   The waits for the operands count this wave's operations in flight, loads and the younger stores
 //   of the tile before.
 //
