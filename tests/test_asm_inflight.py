@@ -119,3 +119,28 @@ def test_no_fragment_register_is_touched_before_its_wait(listings, unit, family)
     with open(listings[unit]) as f:
         found = check_wide_store_data(f)
     assert not found, f"{unit}: wide store data overwritten without a wait state, first: {found[0]}"
+
+
+def test_short_k_kernel_waits_count_the_operations_the_source_says(listings):
+    """The short-k kernel waits for its operands by counting the wave's younger memory operations: the loads of
+    the second pair of slabs (2 per slab for A, 2 more where B is requested too) and the stores of the tile before
+    (8 per wave for a 16-bit C, 16 for fp32).  The immediates in the generated code are those sums:
+    four slabs 2*4+NST or 2*2+NST, three slabs 4+NST or 2+NST, and NST before the second pair and for one or
+    two slabs."""
+    import collections
+    import re
+    waits, kernel = collections.defaultdict(set), None
+    with open(listings["tile_variant_17.hip"]) as f:
+        lines = f.read().splitlines()
+    for i, line in enumerate(lines):
+        m = re.match(r"^(_ZN4gemm4tile18tile_shortk_kernel\S*):", line)
+        if m:
+            kernel = m.group(1)
+        m = re.search(r"s_waitcnt vmcnt\((\d+)\) lgkmcnt\(0\)", line)
+        if m and kernel and "s_barrier" in lines[i + 1]:
+            waits[kernel].add(int(m.group(1)))
+    assert len(waits) == 24
+    for name, seen in waits.items():
+        out = int(re.search(r"ELi(\d)EEEv", name).group(1))          # last template argument: 0 fp32, 1 fp16, 2 bf16
+        nst = 16 if out == 0 else 8
+        assert seen == {nst + 8, nst + 4, nst + 2, nst}, (name, sorted(seen))
