@@ -45,7 +45,14 @@ __device__ __forceinline__ void mfma16(f32x4& c, u32x4 a, u32x4 b) {
 // Both take absolute LDS byte addresses and are assembly, so the compiler neither reorders them
 // nor waits for them: the kernel waits (lgkmcnt) itself before the fragments are used.
 
-struct Frag16Raw { uint2 lo, hi; };
+// Registers of a fragment between its LDS read and the wait for it.  The value of a k-contiguous operand is
+// the one 16-byte register group that the read defines, and it stays whole until the wait has named it: a
+// value taken apart before the wait (two halves, say) may be put together again by register copies that the
+// compiler is free to place ahead of the wait, where they would copy what the registers held before.
+struct Frag16RawKC { u32x4 q; };
+struct Frag16RawMC { u32x2 lo, hi; };
+__device__ __forceinline__ u32x4 frag16_value(const Frag16RawKC& r) { return r.q; }
+__device__ __forceinline__ u32x4 frag16_value(const Frag16RawMC& r) { return u32x4{r.lo.x, r.lo.y, r.hi.x, r.hi.y}; }
 
 template <int ROWS, int BK>
 struct Frag16KC {
@@ -58,12 +65,10 @@ struct Frag16KC {
         const uint32_t line = chunk >> 3;
         return (line << 7) | (((chunk & 7u) ^ kc_line_hash<false>(line)) << 4);
     }
+    typedef Frag16RawKC Raw;
     template <int TILE>
-    static __device__ __forceinline__ void read(uint32_t addr, Frag16Raw& r) {
-        u32x4 v;
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(TILE * 1024));
-        r.lo = uint2{v[0], v[1]};
-        r.hi = uint2{v[2], v[3]};
+    static __device__ __forceinline__ void read(uint32_t addr, Frag16RawKC& r) {
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r.q) : "v"(addr), "n"(TILE * 1024));
     }
 };
 
@@ -80,18 +85,26 @@ struct Frag16MC {
         return (k * CPK + cs) * 16 + (col & 7) * 2;
     }
     static constexpr int HALF_BYTES = 4 * CPK * 16;            // 4 k-rows further
+    typedef Frag16RawMC Raw;
     template <int TILE>
-    static __device__ __forceinline__ void read(uint32_t addr, Frag16Raw& r) {
+    static __device__ __forceinline__ void read(uint32_t addr, Frag16RawMC& r) {
         asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r.lo) : "v"(addr));
         asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(HALF_BYTES));
     }
 };
 
-__device__ __forceinline__ void wait_raw8(Frag16Raw (&r)[4]) {
+__device__ __forceinline__ void wait_raw8(Frag16RawKC (&r)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(r[0].q), "+v"(r[1].q), "+v"(r[2].q), "+v"(r[3].q));
+}
+__device__ __forceinline__ void wait_raw8(Frag16RawKC (&r)[8]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(r[0].q), "+v"(r[1].q), "+v"(r[2].q), "+v"(r[3].q), "+v"(r[4].q), "+v"(r[5].q), "+v"(r[6].q), "+v"(r[7].q));
+}
+__device__ __forceinline__ void wait_raw8(Frag16RawMC (&r)[4]) {
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+v"(r[0].lo), "+v"(r[0].hi), "+v"(r[1].lo), "+v"(r[1].hi), "+v"(r[2].lo), "+v"(r[2].hi), "+v"(r[3].lo), "+v"(r[3].hi));
 }
-__device__ __forceinline__ void wait_raw8(Frag16Raw (&r)[8]) {
+__device__ __forceinline__ void wait_raw8(Frag16RawMC (&r)[8]) {
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+v"(r[0].lo), "+v"(r[0].hi), "+v"(r[1].lo), "+v"(r[1].hi), "+v"(r[2].lo), "+v"(r[2].hi), "+v"(r[3].lo), "+v"(r[3].hi),
                    "+v"(r[4].lo), "+v"(r[4].hi), "+v"(r[5].lo), "+v"(r[5].hi), "+v"(r[6].lo), "+v"(r[6].hi), "+v"(r[7].lo), "+v"(r[7].hi));
@@ -118,7 +131,7 @@ __device__ __forceinline__ void wait_raw8(Frag16Raw (&r)[8]) {
 // Tiles numbered >= split_first are computed by split_parts workgroups each (see TileSplit): such
 // a workgroup runs the same pipeline over its share of the k slabs and stores its accumulators,
 // unscaled, as an fp32 tile in `partials`.
-template <class C, bool IS_BF16, bool A_KC, bool B_KC>
+template <class C, bool IS_BF16, bool A_KC, bool B_KC, bool DIRECT = false>
 __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, int tiles_n, int group_m, int c_vec_ok,
                                                            int split_first, int split_parts, float* partials, int rotate) {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, NT = C::NT, NS = C::NS;
@@ -202,8 +215,8 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     constexpr int NM = TM * TN, NR = TM + TN;     // MFMAs and fragments per step
     constexpr int LPT = LA::L + LB::L;            // loads per thread and slab (= per half of a pair)
 
-    Frag16Raw af[2][TM];                          // fragments of two consecutive slabs
-    Frag16Raw bf[2][TN];
+    typename FA::Raw af[2][TM];                   // fragments of two consecutive slabs
+    typename FB::Raw bf[2][TN];
 
     // Fragment q of the slab in the stage at byte offset `off`, in the order the MFMAs first need
     // them: A0, B0..B7, A1..A7.  `ka`, `kb`: fragment addresses of tile 0 in that stage, for the
@@ -234,9 +247,9 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
         wait_raw8(bf[cur]);
         u32x4 ua[TM], ub[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) ua[i] = u32x4{af[cur][i].lo.x, af[cur][i].lo.y, af[cur][i].hi.x, af[cur][i].hi.y};
+        for (int i = 0; i < TM; ++i) ua[i] = frag16_value(af[cur][i]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) ub[j] = u32x4{bf[cur][j].lo.x, bf[cur][j].lo.y, bf[cur][j].hi.x, bf[cur][j].hi.y};
+        for (int j = 0; j < TN; ++j) ub[j] = frag16_value(bf[cur][j]);
         [&]<int... M>(std::integer_sequence<int, M...>) {
             ([&] {
                 slot(std::integral_constant<int, M>{}, std::false_type{});
@@ -441,6 +454,56 @@ __global__ __launch_bounds__(C::NT) void tile_dma16_kernel(Args a, int tiles_m, 
     // of C transposed: register v of lane l is row l%16, column 4*(l/16) + v, and a lane's four
     // registers are four consecutive columns, parked with one 16-byte LDS write.
     const int c16 = lane & 15, g4 = lane >> 4;
+    if constexpr (DIRECT) {
+        // Whole tiles of a 16-bit C without C_in, bias or activation (the launcher checks) leave from the
+        // registers: no pass through LDS and none of its waits.  A lane's four columns of a block are 8 bytes
+        // once rounded; two neighbouring blocks trade halves (v_permlane16_swap: the odd 16-lane rows of its
+        // first operand against the even rows of its second), which gives every lane 16 contiguous bytes and
+        // every row of C 64; then the two halves of each 16-lane row trade pieces (a rotation by 8 under a
+        // bank mask), which brings the two 64-byte halves of a 128-byte line into one instruction, eight rows
+        // per store.  (Stores of 64-byte pieces make the L2 write lines twice.)
+        // Nothing below moves above the wait that ends the k loop:
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) asm volatile("" : "+a"(acc[i][j]));
+        const float alpha = a.alpha;
+        const bool to_bf16 = a.out_dtype == DT_BF16;
+        const int r8 = c16 & 7, up = c16 >> 3;
+        const int64_t row0 = m0 + wm * C::WTM + r8;
+        const int64_t col = n0 + wn * C::WTN + 32 * up + 16 * (g4 & 1) + 8 * (g4 >> 1);
+        char* p = (char*)a.C + (row0 * a.ldc + col) * 2;
+        const int64_t row_step = (int64_t)16 * a.ldc * 2, half_step = (int64_t)8 * a.ldc * 2;
+        auto pack = [&](const f32x4& v) {
+            typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+            typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+            const f32x4 s = alpha * v;
+            return to_bf16 ? __builtin_bit_cast(u32x2, __builtin_convertvector(s, bf16x4)) : __builtin_bit_cast(u32x2, __builtin_convertvector(s, f16x4));
+        };
+        auto piece = [&](const f32x4& left, const f32x4& right) {
+            const u32x2 pl = pack(left), pr = pack(right);
+            const auto lo = __builtin_amdgcn_permlane16_swap(pl.x, pr.x, false, false);
+            const auto hi = __builtin_amdgcn_permlane16_swap(pl.y, pr.y, false, false);
+            return u32x4{lo[0], hi[0], lo[1], hi[1]};
+        };
+        static_assert(TN % 4 == 0, "a line is four blocks wide");
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int q = 0; q < TN / 4; ++q) {
+                const u32x4 lower = piece(acc[i][4 * q], acc[i][4 * q + 1]), upper = piece(acc[i][4 * q + 2], acc[i][4 * q + 3]);
+                u32x4 d0, d1;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    d0[e] = (uint32_t)__builtin_amdgcn_update_dpp((int)lower[e], (int)upper[e], 0x128, 0xf, 0xc, false);     // row_ror:8
+                    d1[e] = (uint32_t)__builtin_amdgcn_update_dpp((int)upper[e], (int)lower[e], 0x128, 0xf, 0x3, false);
+                }
+                __builtin_nontemporal_store(d0, (u32x4*)(p + i * row_step + q * 128));
+                __builtin_nontemporal_store(d1, (u32x4*)(p + i * row_step + half_step + q * 128));
+            }
+        }
+        return;
+    }
     tile_epilogue_bands<C>(
         [&](auto band, char* region) {
             constexpr int b = decltype(band)::value;
@@ -472,9 +535,25 @@ hipError_t launch_dma16_variant(const Args& a, int group_m, const TileSplit& spl
     const bool a_aliases = akc && (a.lda * 2) % 4096 == 0, b_aliases = bkc && (a.ldb * 2) % 4096 == 0;
     const bool one_panel_each = (tiles_m == 1 || tiles_n == 1) && (a.M + a.N) * a.K * 2 > ((int64_t)256 << 20);
     const int rotate = ((splits && split.parts <= 4) || one_panel_each) && (a_aliases || b_aliases);
-#define GEMM_TILE_LAUNCH(BF, AKC, BKC) \
-    hipLaunchKernelGGL((tile_dma16_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok, \
-                       split_first, split_parts, split.partials, rotate)
+    // whole tiles of a 16-bit C with nothing but alpha in the epilogue: the instances that store from the registers
+    // (the 256 x 256 tile only: the others are chosen for calls that the k loop or the launch dominates; an fp32 C
+    // gains nothing from it: 713 against 715 us at 8192^3)
+    constexpr bool HAS_DIRECT = C::BM == 256 && C::BN == 256 && C::NS == 5;
+    const bool direct = HAS_DIRECT && !splits && a.out_dtype != DT_F32 && a.beta == 0.0f && a.bias == nullptr && a.act == ACT_NONE &&
+                        a.M % C::BM == 0 && a.N % C::BN == 0 && a.ldc % 8 == 0 && ((uintptr_t)a.C & 15) == 0 &&
+                        (a.batch == 1 || (a.strideC * 2) % 16 == 0);
+#define GEMM_TILE_LAUNCH(BF, AKC, BKC)                                                                                          \
+    do {                                                                                                                        \
+        if constexpr (HAS_DIRECT) {                                                                                             \
+            if (direct) {                                                                                                       \
+                hipLaunchKernelGGL((tile_dma16_kernel<C, BF, AKC, BKC, true>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, \
+                                   c_vec_ok, split_first, split_parts, split.partials, rotate);                                 \
+                break;                                                                                                          \
+            }                                                                                                                   \
+        }                                                                                                                       \
+        hipLaunchKernelGGL((tile_dma16_kernel<C, BF, AKC, BKC>), grid, block, 0, stream, a, tiles_m, tiles_n, group_m, c_vec_ok, \
+                           split_first, split_parts, split.partials, rotate);                                                   \
+    } while (0)
     if (bf) {
         if (akc && bkc) GEMM_TILE_LAUNCH(true, true, true);
         else if (akc && !bkc) GEMM_TILE_LAUNCH(true, true, false);
