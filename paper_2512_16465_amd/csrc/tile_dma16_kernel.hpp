@@ -536,9 +536,8 @@ hipError_t launch_dma16_variant(const Args& a, int group_m, const TileSplit& spl
     const bool one_panel_each = (tiles_m == 1 || tiles_n == 1) && (a.M + a.N) * a.K * 2 > ((int64_t)256 << 20);
     const int rotate = ((splits && split.parts <= 4) || one_panel_each) && (a_aliases || b_aliases);
     // whole tiles of a 16-bit C with nothing but alpha in the epilogue: the instances that store from the registers
-    // (the 256 x 256 tile only: the others are chosen for calls that the k loop or the launch dominates; an fp32 C
-    // gains nothing from it: 713 against 715 us at 8192^3)
-    constexpr bool HAS_DIRECT = C::BM == 256 && C::BN == 256 && C::NS == 5;
+    // (an fp32 C gains nothing from it: 713 against 715 us at 8192^3)
+    constexpr bool HAS_DIRECT = C::NS == 5;
     const bool direct = HAS_DIRECT && !splits && a.out_dtype != DT_F32 && a.beta == 0.0f && a.bias == nullptr && a.act == ACT_NONE &&
                         a.M % C::BM == 0 && a.N % C::BN == 0 && a.ldc % 8 == 0 && ((uintptr_t)a.C & 15) == 0 &&
                         (a.batch == 1 || (a.strideC * 2) % 16 == 0);
