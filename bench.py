@@ -9,6 +9,8 @@ fp32 output) with operands resident in HBM.  The protocol follows the paper's ev
 line; `value` is TFLOP/s on C3, `roofline` prices the dominant kernel of C3 against the dense
 bf16 MFMA peak, `cpu_baseline` times the CPU oracle on a bounded sample of the same workload,
 and `other_configs` carries the remaining configurations (C5 is priced against HBM bandwidth).
+`mfma_ceiling` is context for the compute-bound rows: the rate and clock of register-only MFMA
+loops on values drawn like the headline's operands and on zeros, measured in the same process.
 """
 from __future__ import annotations
 
@@ -200,6 +202,67 @@ def cpu_baseline(res: Resident, target_seconds: float = 12.0):
             "projected_seconds": dt * cfg.M * cfg.batch / nrows}
 
 
+def mfma_ceiling(torch, cfg, seed: int, settle_ms: float = 150.0, launches: int = 10, passes: int = 16384):
+    """Rate and clock of register-only MFMA loops (paper_2512_16465_amd/diagnostics/mfma_ceiling.hip: no
+    memory traffic in the timed part, the register blocking of the 256x256 tile) on operand values drawn
+    like cfg's A and B, and on zeros.  What the part's power limit leaves of the nominal peak to any
+    kernel on such data; context for roofline.frac, which stays a fraction of the nominal peak."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2512_16465_amd", "libmfma_ceiling.so")
+    if not os.path.exists(path):
+        return {"error": "libmfma_ceiling.so is not built (python -m paper_2512_16465_amd.build)"}
+    lib = ctypes.CDLL(path)
+    lib.mfma_ceiling_bytes_per_workgroup.restype = ctypes.c_size_t
+    lib.mfma_ceiling_flop.restype = ctypes.c_double
+    lib.mfma_ceiling_flop.argtypes = [ctypes.c_int, ctypes.c_int]
+    lib.mfma_ceiling_launch.restype = ctypes.c_int
+    lib.mfma_ceiling_launch.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
+                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    dev = torch.device("cuda:0")
+    wgs = torch.cuda.get_device_properties(0).multi_processor_count     # one workgroup of four waves per compute unit
+    per_wg = lib.mfma_ceiling_bytes_per_workgroup()
+    assert per_wg == 16 * 256 * 16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    # per workgroup 16 fragments x 256 lanes x 8 values: the first 8 fragments play A, the others B
+    def draw(dist):
+        if dist[0] == "normal":
+            return torch.randn((wgs, 8, 256, 8), generator=gen, device=dev) * dist[1]
+        return (torch.rand((wgs, 8, 256, 8), generator=gen, device=dev) * 2.0 - 1.0) * dist[1]
+    like = torch.cat([draw(cfg.a_dist), draw(cfg.b_dist)], dim=1).to(torch.bfloat16).contiguous()
+    zeros = torch.zeros_like(like)
+    assert like.numel() * 2 == wgs * per_wg
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    stamps = torch.zeros(2 * wgs, dtype=torch.int64, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    flop = lib.mfma_ceiling_flop(wgs, passes)
+    out = {"kernel": "register-only loops of independent MFMAs, 256 accumulator registers per lane, one wave per SIMD",
+           "workgroups": wgs, "passes": passes, "launches": launches, "peak_tflops": MFMA_BF16_PEAK_TFLOPS, "cases": {}}
+    for shape, sname in ((1, "v_mfma_f32_16x16x32_bf16"), (0, "v_mfma_f32_32x32x16_bf16")):
+        for data, dname in ((like, "values drawn like the operands"), (zeros, "zeros")):
+            def launch():
+                rc = lib.mfma_ceiling_launch(shape, wgs, passes, data.data_ptr(), wgs, sink.data_ptr(), stamps.data_ptr(), stream)
+                if rc != 0:
+                    raise RuntimeError(f"mfma_ceiling_launch returned {rc}")
+            t0 = time.perf_counter()
+            while (time.perf_counter() - t0) * 1e3 < settle_ms:      # the clock settles under the load first
+                launch()
+                torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(launches):
+                launch()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / launches
+            st = stamps.cpu().view(wgs, 2).double()
+            ghz = float((st[:, 0] / st[:, 1]).mean()) * 0.1          # shader cycles per tick of the 100 MHz constant clock
+            tf = flop / (ms * 1e-3) / 1e12
+            out["cases"][f"{sname}, {dname}"] = {"tflops": tf, "frac_of_peak": tf / MFMA_BF16_PEAK_TFLOPS, "ghz": ghz,
+                                                 "ms_per_launch": ms}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -215,6 +278,8 @@ def main():
     ap.add_argument("--cpu-seconds-other", type=float, default=1.0,
                     help="oracle time spent on each further configuration (a projection from a few rows of C); 0 = none")
     ap.add_argument("--no-verify", action="store_true")
+    ap.add_argument("--no-mfma-ceiling", action="store_true",
+                    help="skip the register-only MFMA loops that show what the power limit leaves of the nominal peak")
     ap.add_argument("--kernel", type=int, default=0, help="force a kernel family (gemm_kernel_t); 0 = automatic")
     ap.add_argument("--variant", type=int, default=-1, help="tile variant when --kernel is forced")
     ap.add_argument("--split-k", type=int, default=0, help="split-K factor when --kernel is forced; 0 = automatic")
@@ -294,6 +359,10 @@ def main():
         cpu = cpu_baseline(res, args.cpu_seconds)
     torch.cuda.synchronize()
     lg.gemm_destroy(handle)
+    ceiling = None if args.no_mfma_ceiling or cfg.dtype != wl.BF16 else mfma_ceiling(torch, cfg, seed)
+    if ceiling and "cases" in ceiling and roof and roof["bound"] == "mfma":
+        like = ceiling["cases"]["v_mfma_f32_16x16x32_bf16, values drawn like the operands"]["tflops"]
+        ceiling["headline_over_ceiling"] = roof["achieved"] / like      # the GEMM against the loop of its own instruction
     line = {
         "metric": "gemm_tflops_bf16_8192cubed" if name == "C3" else f"gemm_tflops_{name}",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -309,6 +378,7 @@ def main():
         "pct_of_mfma_peak": 100.0 * tflops / MFMA_BF16_PEAK_TFLOPS,
         "roofline": roof,
         "cpu_baseline": cpu,
+        "mfma_ceiling": ceiling,
         "hbm_gbps_at_m32": results["C5"]["algorithmic_gbps"] if "C5" in results else None,
         "other_configs": {k: v for k, v in results.items() if k != name},
         "headline_detail": results[name],

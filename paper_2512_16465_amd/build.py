@@ -7,7 +7,8 @@
         # bench.py --library loads it); its objects go to a directory next to the output
 
 Objects go to paper_2512_16465_amd/_build/ (not tracked); the shared library lands next to
-this file so that it travels with the source tree.
+this file so that it travels with the source tree.  Every build also compiles
+diagnostics/mfma_ceiling.hip into libmfma_ceiling.so, a measuring aid that only bench.py loads.
 """
 from __future__ import annotations
 
@@ -21,6 +22,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgemm.so")
+
+DIAG_SRC = os.path.join(HERE, "diagnostics", "mfma_ceiling.hip")
+DIAG_LIB = os.path.join(HERE, "libmfma_ceiling.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -79,6 +83,16 @@ def _compile(unit):
     return p.returncode, " ".join(cmd), err
 
 
+def build_diagnostics(force: bool = False) -> str:
+    """libmfma_ceiling.so: the register-only MFMA loops bench.py times beside the GEMM (one source file)."""
+    if force or not os.path.exists(DIAG_LIB) or os.path.getmtime(DIAG_LIB) < os.path.getmtime(DIAG_SRC):
+        cmd = [HIPCC, *FLAGS, "-shared", DIAG_SRC, "-o", DIAG_LIB]
+        p = subprocess.run(cmd, capture_output=True, text=True)
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc failed: {' '.join(cmd)}\n{p.stderr}")
+    return DIAG_LIB
+
+
 def build_library(force: bool = False, jobs: int = 8, verbose: bool = True, defines=(), output: str = "") -> str:
     global OBJ, LIB, FLAGS
     if output:
@@ -113,4 +127,6 @@ if __name__ == "__main__":
     argv = sys.argv[1:]
     defs = [argv[i + 1] for i, x in enumerate(argv) if x == "--define" and i + 1 < len(argv)]
     outp = next((argv[i + 1] for i, x in enumerate(argv) if x == "--output" and i + 1 < len(argv)), "")
+    if not outp:
+        print(build_diagnostics(force="--force" in argv))
     print(build_library(force="--force" in argv or bool(defs), defines=defs, output=outp))

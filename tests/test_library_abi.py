@@ -30,6 +30,25 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert isinstance(lib, ctypes.CDLL)
 
 
+def test_measuring_aid_of_the_bench_is_built_and_answers_on_the_host():
+    """libmfma_ceiling.so (register-only MFMA loops, loaded by bench.py alone) exports its three entry points;
+    the two that make no HIP call answer here, and the launcher refuses bad arguments before any HIP call."""
+    path = os.path.join(ROOT, "paper_2512_16465_amd", "libmfma_ceiling.so")
+    assert os.path.exists(path), "run python -m paper_2512_16465_amd.build"
+    lib = ctypes.CDLL(path)
+    lib.mfma_ceiling_bytes_per_workgroup.restype = ctypes.c_size_t
+    lib.mfma_ceiling_flop.restype = ctypes.c_double
+    lib.mfma_ceiling_flop.argtypes = [ctypes.c_int, ctypes.c_int]
+    assert lib.mfma_ceiling_bytes_per_workgroup() == 16 * 256 * 16
+    # 64 instructions of 2*16*16*32 flop (or 32 of 2*32*32*16) per pass and wave, four waves per workgroup
+    assert lib.mfma_ceiling_flop(256, 1000) == 256 * 4 * 1000 * 64 * 2 * 16 * 16 * 32
+    lib.mfma_ceiling_launch.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
+                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.mfma_ceiling_launch(2, 256, 16, 16, 1, 16, 16, None) == -1      # unknown shape
+    assert lib.mfma_ceiling_launch(1, 256, 16, None, 1, 16, 16, None) == -1    # no data
+    assert lib.mfma_ceiling_launch(1, 256, 0, 16, 1, 16, 16, None) == -1       # no passes
+
+
 def test_host_only_entry_points_answer_without_a_gpu():
     assert lg.gemm_status_string(0) == "success"
     assert "invalid" in lg.gemm_status_string(1)
