@@ -10,7 +10,8 @@ line; `value` is TFLOP/s on C3, `roofline` prices the dominant kernel of C3 agai
 bf16 MFMA peak, `cpu_baseline` times the CPU oracle on a bounded sample of the same workload,
 and `other_configs` carries the remaining configurations (C5 is priced against HBM bandwidth).
 `mfma_ceiling` is context for the compute-bound rows: the rate and clock of register-only MFMA
-loops on values drawn like the headline's operands and on zeros, measured in the same process.
+loops on values drawn like the headline's operands and on zeros, measured in the same process;
+`hbm_read_ceiling` is the same for the bandwidth-bound rows: what a kernel that only reads gets.
 """
 from __future__ import annotations
 
@@ -202,16 +203,69 @@ def cpu_baseline(res: Resident, target_seconds: float = 12.0):
             "projected_seconds": dt * cfg.M * cfg.batch / nrows}
 
 
+def _ceilings_library():
+    """The measuring aids of paper_2512_16465_amd/diagnostics/ (a library of their own), or None when not built."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2512_16465_amd", "libceilings.so")
+    return ctypes.CDLL(path) if os.path.exists(path) else None
+
+
+def hbm_read_ceiling(torch, sizes_mib=(128, 512), launches: int = 40, settle_ms: float = 30.0):
+    """GB/s of a kernel that only reads (paper_2512_16465_amd/diagnostics/hbm_read_ceiling.hip: coalesced 16-byte
+    loads, eight per lane in flight) over buffers of the sizes of the streamed weights, 1 GiB of buffers in
+    rotation so that the 256 MB last-level cache cannot serve them, best of three grid sizes.  Context for the
+    bandwidth-bound rows, whose roofline.frac stays a fraction of the nominal 8 TB/s."""
+    import ctypes
+    lib = _ceilings_library()
+    if lib is None:
+        return {"error": "libceilings.so is not built (python -m paper_2512_16465_amd.build)"}
+    lib.hbm_read_launch.restype = ctypes.c_int
+    lib.hbm_read_launch.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    dev = torch.device("cuda:0")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {"kernel": "grid-stride 16-byte loads, 8 per lane in flight, nothing stored", "peak_gbps": HBM_PEAK_GBPS,
+           "launches": launches, "sizes": {}}
+    for mib in sizes_mib:
+        nbytes = mib << 20
+        bufs = [torch.full((nbytes,), 0x5a, dtype=torch.uint8, device=dev) for _ in range(max(2, 1024 // mib))]
+        best = None
+        for per_cu in (4, 8, 16):
+            def launch(i):
+                rc = lib.hbm_read_launch(bufs[i % len(bufs)].data_ptr(), nbytes, cus * per_cu, sink.data_ptr(), stream)
+                if rc != 0:
+                    raise RuntimeError(f"hbm_read_launch returned {rc}")
+            t0, i = time.perf_counter(), 0
+            while (time.perf_counter() - t0) * 1e3 < settle_ms:
+                launch(i)
+                i += 1
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(launches):
+                launch(i)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / launches
+            gbps = nbytes / (ms * 1e-3) / 1e9
+            if best is None or gbps > best["gbps"]:
+                best = {"gbps": gbps, "frac_of_peak": gbps / HBM_PEAK_GBPS, "us_per_launch": ms * 1e3, "workgroups_per_cu": per_cu}
+        out["sizes"][f"{mib} MiB"] = best
+        del bufs
+        torch.cuda.empty_cache()
+    return out
+
+
 def mfma_ceiling(torch, cfg, seed: int, settle_ms: float = 150.0, launches: int = 10, passes: int = 16384):
     """Rate and clock of register-only MFMA loops (paper_2512_16465_amd/diagnostics/mfma_ceiling.hip: no
     memory traffic in the timed part, the register blocking of the 256x256 tile) on operand values drawn
     like cfg's A and B, and on zeros.  What the part's power limit leaves of the nominal peak to any
     kernel on such data; context for roofline.frac, which stays a fraction of the nominal peak."""
     import ctypes
-    path = os.path.join(ROOT, "paper_2512_16465_amd", "libmfma_ceiling.so")
-    if not os.path.exists(path):
-        return {"error": "libmfma_ceiling.so is not built (python -m paper_2512_16465_amd.build)"}
-    lib = ctypes.CDLL(path)
+    lib = _ceilings_library()
+    if lib is None:
+        return {"error": "libceilings.so is not built (python -m paper_2512_16465_amd.build)"}
     lib.mfma_ceiling_bytes_per_workgroup.restype = ctypes.c_size_t
     lib.mfma_ceiling_flop.restype = ctypes.c_double
     lib.mfma_ceiling_flop.argtypes = [ctypes.c_int, ctypes.c_int]
@@ -280,6 +334,7 @@ def main():
     ap.add_argument("--no-verify", action="store_true")
     ap.add_argument("--no-mfma-ceiling", action="store_true",
                     help="skip the register-only MFMA loops that show what the power limit leaves of the nominal peak")
+    ap.add_argument("--no-hbm-ceiling", action="store_true", help="skip the read-only kernel that shows what plain reads get of 8 TB/s")
     ap.add_argument("--kernel", type=int, default=0, help="force a kernel family (gemm_kernel_t); 0 = automatic")
     ap.add_argument("--variant", type=int, default=-1, help="tile variant when --kernel is forced")
     ap.add_argument("--split-k", type=int, default=0, help="split-K factor when --kernel is forced; 0 = automatic")
@@ -379,6 +434,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "mfma_ceiling": ceiling,
+        "hbm_read_ceiling": None if args.no_hbm_ceiling else hbm_read_ceiling(torch),
         "hbm_gbps_at_m32": results["C5"]["algorithmic_gbps"] if "C5" in results else None,
         "other_configs": {k: v for k, v in results.items() if k != name},
         "headline_detail": results[name],

@@ -8,7 +8,7 @@
 
 Objects go to paper_2512_16465_amd/_build/ (not tracked); the shared library lands next to
 this file so that it travels with the source tree.  Every build also compiles
-diagnostics/mfma_ceiling.hip into libmfma_ceiling.so, a measuring aid that only bench.py loads.
+diagnostics/*.hip into libceilings.so, measuring aids that only bench.py loads.
 """
 from __future__ import annotations
 
@@ -23,8 +23,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgemm.so")
 
-DIAG_SRC = os.path.join(HERE, "diagnostics", "mfma_ceiling.hip")
-DIAG_LIB = os.path.join(HERE, "libmfma_ceiling.so")
+DIAG_SRC = [os.path.join(HERE, "diagnostics", n) for n in ("mfma_ceiling.hip", "hbm_read_ceiling.hip")]
+DIAG_LIB = os.path.join(HERE, "libceilings.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -84,9 +84,9 @@ def _compile(unit):
 
 
 def build_diagnostics(force: bool = False) -> str:
-    """libmfma_ceiling.so: the register-only MFMA loops bench.py times beside the GEMM (one source file)."""
-    if force or not os.path.exists(DIAG_LIB) or os.path.getmtime(DIAG_LIB) < os.path.getmtime(DIAG_SRC):
-        cmd = [HIPCC, *FLAGS, "-shared", DIAG_SRC, "-o", DIAG_LIB]
+    """libceilings.so: the register-only MFMA loops and the plain read kernel bench.py times beside the GEMM."""
+    if force or not os.path.exists(DIAG_LIB) or os.path.getmtime(DIAG_LIB) < max(os.path.getmtime(f) for f in DIAG_SRC):
+        cmd = [HIPCC, *FLAGS, "-shared", *DIAG_SRC, "-o", DIAG_LIB]
         p = subprocess.run(cmd, capture_output=True, text=True)
         if p.returncode != 0:
             raise RuntimeError(f"hipcc failed: {' '.join(cmd)}\n{p.stderr}")

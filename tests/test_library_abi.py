@@ -30,10 +30,10 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert isinstance(lib, ctypes.CDLL)
 
 
-def test_measuring_aid_of_the_bench_is_built_and_answers_on_the_host():
-    """libmfma_ceiling.so (register-only MFMA loops, loaded by bench.py alone) exports its three entry points;
-    the two that make no HIP call answer here, and the launcher refuses bad arguments before any HIP call."""
-    path = os.path.join(ROOT, "paper_2512_16465_amd", "libmfma_ceiling.so")
+def test_measuring_aids_of_the_bench_are_built_and_answer_on_the_host():
+    """libceilings.so (register-only MFMA loops and a read-only kernel, loaded by bench.py alone) exports its entry
+    points; those that make no HIP call answer here, and the launchers refuse bad arguments before any HIP call."""
+    path = os.path.join(ROOT, "paper_2512_16465_amd", "libceilings.so")
     assert os.path.exists(path), "run python -m paper_2512_16465_amd.build"
     lib = ctypes.CDLL(path)
     lib.mfma_ceiling_bytes_per_workgroup.restype = ctypes.c_size_t
@@ -47,6 +47,10 @@ def test_measuring_aid_of_the_bench_is_built_and_answers_on_the_host():
     assert lib.mfma_ceiling_launch(2, 256, 16, 16, 1, 16, 16, None) == -1      # unknown shape
     assert lib.mfma_ceiling_launch(1, 256, 16, None, 1, 16, 16, None) == -1    # no data
     assert lib.mfma_ceiling_launch(1, 256, 0, 16, 1, 16, 16, None) == -1       # no passes
+    lib.hbm_read_launch.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.hbm_read_launch(None, 1 << 20, 256, 16, None) == -1             # no data
+    assert lib.hbm_read_launch(16, (1 << 20) + 16, 256, 16, None) == -1        # not whole trips
+    assert lib.hbm_read_launch(16, 1 << 20, 0, 16, None) == -1                 # no workgroups
 
 
 def test_host_only_entry_points_answer_without_a_gpu():
