@@ -322,7 +322,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5,X6,X7,X8,X11,G1,G2,G3,G4,G5,G6",
+    ap.add_argument("--configs", default="C3,C5,C2,C4,C1,X1,X2,X3,X4,X5,X6,X7,X8,X11,G1,G2,G3,G4,G5,G6,G7,G8",
                     help="first one is the headline workload; X* are the further shapes of workloads.EXTRA_CONFIGS")
     ap.add_argument("--settle-ms", type=float, default=80.0,
                     help="the warm-up keeps launching until this much time has passed (clock ramp after idle); 0 = exactly --warmup launches")

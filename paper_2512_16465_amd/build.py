@@ -47,7 +47,7 @@ def _tile_variant_indices():
 def _units():
     """(source, object, extra flags) for every translation unit."""
     units = []
-    for name in ("gemm_api.hip", "general_kernel.hip", "skinny_kernel.hip", "gemv_f32_kernel.hip", "tile_dispatch.hip"):
+    for name in ("gemm_api.hip", "general_kernel.hip", "skinny_kernel.hip", "gemv_f32_kernel.hip", "gemv16_kernel.hip", "tile_dispatch.hip"):
         units.append((os.path.join(CSRC, name), os.path.join(OBJ, name.replace(".hip", ".o")), []))
     for i in _tile_variant_indices():      # one small source file per variant of tile_variants.def
         units.append((os.path.join(CSRC, f"tile_variant_{i}.hip"), os.path.join(OBJ, f"tile_variant_{i}.o"), []))

@@ -198,13 +198,16 @@ hipError_t launch_tile_split_reduce(const Args& a, int variant, int group_m, con
 
 bool skinny_supports(const Args& a);
 const char* skinny_variant_name(int variant);
-// the variant that serves the call's layout, and the largest split factor it takes
+// the variant the family prefers for the call, whether `variant` can serve it as well (a call with at most
+// 8 rows on a 16-bit weight stored N x K has two), and the largest split factor a variant takes;
+// variant < 0 stands for skinny_variant_of(a) everywhere below
 int skinny_variant_of(const Args& a);
-int skinny_max_split(const Args& a);
+bool skinny_variant_serves(const Args& a, int variant);
+int skinny_max_split(const Args& a, int variant = -1);
 // bytes of fp32 workspace the skinny kernel needs for this split factor (0 when split_k == 1)
 size_t skinny_workspace_bytes(const Args& a, int split_k);
-int skinny_default_split(const Args& a, int num_cus);
-hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream_t stream);
+int skinny_default_split(const Args& a, int num_cus, int variant = -1);
+hipError_t launch_skinny(const Args& a, int split_k, float* workspace, hipStream_t stream, int variant = -1);
 // Adds `split_k` fp32 partial results `partials[s][M][N]` (rows N apart) in the order of s and applies
 // the epilogue of `a` into C.  N must be a multiple of 8.
 hipError_t launch_splitk_reduce(const Args& a, int split_k, const float* partials, hipStream_t stream);
@@ -214,6 +217,13 @@ bool gemv_f32_supports(const Args& a);
 int gemv_f32_max_split(const Args& a);
 int gemv_f32_default_split(const Args& a, int num_cus);
 hipError_t launch_gemv_f32(const Args& a, int split_k, float* workspace, hipStream_t stream);
+
+// bf16 / fp16 operands, at most 8 rows, B stored N x K: the matrix-vector kernel on the vector ALUs (part of the
+// skinny family)
+bool gemv16_supports(const Args& a);
+int gemv16_max_split(const Args& a);
+int gemv16_default_split(const Args& a, int num_cus);
+hipError_t launch_gemv16(const Args& a, int split_k, float* workspace, hipStream_t stream);
 
 hipError_t launch_general(const Args& a, hipStream_t stream);
 

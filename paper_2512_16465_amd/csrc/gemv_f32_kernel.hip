@@ -13,6 +13,7 @@
 //     k, 256 elements per trip; A is read the same way (it stays in the caches), and the 64 partial
 //     dot products of a lane are folded across the wave at the end of the k range.
 #include "common.hpp"
+#include "gemv_common.hpp"
 
 namespace gemm {
 
@@ -24,29 +25,6 @@ constexpr int GV_NN_UNROLL = 8;          // k-rows per step
 constexpr int GV_NT_COLS_PER_WAVE = 8;   // stored rows of B per wave
 constexpr int GV_NT_COLS = GV_WAVES * GV_NT_COLS_PER_WAVE;
 constexpr int GV_NT_TRIP = 256;          // k per trip of a wave
-constexpr uint32_t GV_MASKED = 0x7ffffff0u;
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t gv_rsrc(const void* base, int64_t bytes) {
-    const int64_t cap = 0xffffffffll;
-    const uint32_t n = (uint32_t)(bytes < 0 ? 0 : (bytes > cap ? cap : bytes));
-    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)n, 0x00020000);
-}
-
-__device__ __forceinline__ f32x4 gv_load4(__amdgpu_buffer_rsrc_t r, uint32_t off) {
-    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
-}
-
-// one output element: the epilogue of the call, or a raw partial sum of slice `slice`
-__device__ __forceinline__ void gv_store(const Args& a, int split_k, int slice, float* ws, int64_t row, int64_t col, float x) {
-    if (split_k > 1) {
-        ws[((int64_t)slice * a.M + row) * a.N + col] = x;
-        return;
-    }
-    const int64_t ci = row * a.ldc + col;
-    const float c_in = a.beta != 0.0f ? load_elem(a.C, a.out_dtype, ci) : 0.0f;
-    const float bj = a.bias ? load_elem(a.bias, a.bias_dtype, col) : 0.0f;
-    store_elem(a.C, a.out_dtype, ci, epilogue_value(x, a.alpha, a.beta, c_in, bj, a.act));
-}
 
 template <int R>
 __global__ __launch_bounds__(GV_WAVES * 64) void gemv_f32_nn_kernel(Args a, int split_k, float* ws) {

@@ -23,6 +23,11 @@ constexpr int SK_COLS = 256;     // columns per workgroup
 constexpr int SK_WAVES = 4;      // waves per workgroup (one per SIMD), each a slice of the workgroup's k range
 constexpr int SK_DEPTH = 3;      // steps of 16 k-rows in flight per wave (8 KiB each)
 constexpr int SK_MAX_ROWS = 64;  // rows of C the skinny kernels take
+// Up to here a 16-bit weight stored N x K goes to the vector-ALU kernel (variant 4): with 1, 2 and 4 rows it is ahead of
+// the MFMA kernel on every weight measured (1 x 8192 x 8192 21.3 against 26.0 us, 4 x 28672 x 8192 78 against 79.5) or
+// level (4 x 16384 x 16384 90.4 against 89.5); with 8 rows its multiplications show (8 x 8192 x 8192 29 against 27.5,
+// 8 x 28672 x 8192 102 against 79).
+constexpr int SK_GEMV16_ROWS = 4;
 constexpr uint32_t SK_MASKED = 0x7ffffff0u;   // an offset past the end of any operand: the load returns zero
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t sk_rsrc(const void* base, int64_t bytes) {
@@ -539,29 +544,44 @@ bool skinny_supports(const Args& a) {
 
 // variant 0: row-major B (K x N); variant 1: B stored N x K.  The layout of the call decides.
 // Variants 2 and 3: the same two layouts for fp32 operands and at most 8 rows (gemv_f32_kernel.hip).
+// Variant 4: 16-bit operands, B stored N x K, at most 8 rows, on the vector ALUs (gemv16_kernel.hip);
+// preferred to variant 1 up to SK_GEMV16_ROWS rows.
 const char* skinny_variant_name(int variant) {
     switch (variant) {
         case 0: return "skinny_nn_32x256_w4";
         case 1: return "skinny_nt_32x256_w4";
         case 2: return "gemv_f32_nn_8x256_w4";
         case 3: return "gemv_f32_nt_8x32_w4";
+        case 4: return "gemv16_nt_8x32_w4";
         default: return nullptr;
     }
 }
 
-int skinny_variant_of(const Args& a) { return (a.dtype == DT_F32 ? 2 : 0) + (a.transB ? 1 : 0); }
+int skinny_variant_of(const Args& a) {
+    if (a.dtype != DT_F32 && a.M <= SK_GEMV16_ROWS && gemv16_supports(a)) return 4;
+    return (a.dtype == DT_F32 ? 2 : 0) + (a.transB ? 1 : 0);
+}
+
+bool skinny_variant_serves(const Args& a, int variant) {
+    if (variant < 0 || variant == skinny_variant_of(a)) return true;
+    if (variant == 4) return gemv16_supports(a);
+    // the MFMA kernel for a weight stored N x K also takes the calls that variant 4 is preferred for
+    return variant == 1 && a.dtype != DT_F32 && a.transB;
+}
 
 // units the k range is cut in: steps of 16 (row-major B) or chunks of ST_CHUNK (B stored N x K)
 static int64_t skinny_k_units(const Args& a) { return a.transB ? (a.K + ST_CHUNK - 1) / ST_CHUNK : (a.K + 15) / 16; }
 
-int skinny_max_split(const Args& a) {
+int skinny_max_split(const Args& a, int variant) {
     if (a.dtype == DT_F32) return gemv_f32_max_split(a);
+    if ((variant < 0 ? skinny_variant_of(a) : variant) == 4) return gemv16_max_split(a);
     const int64_t units = skinny_k_units(a);
     return (int)(units < 1 ? 1 : (units > 64 ? 64 : units));
 }
 
-int skinny_default_split(const Args& a, int num_cus) {
+int skinny_default_split(const Args& a, int num_cus, int variant) {
     if (a.dtype == DT_F32) return gemv_f32_default_split(a, num_cus);
+    if ((variant < 0 ? skinny_variant_of(a) : variant) == 4) return gemv16_default_split(a, num_cus);
     const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS, cus = num_cus > 0 ? num_cus : 256;
     // keep the pipeline of every wave filled a few times over (row-major B: the waves of a
     // workgroup share its k range; B stored N x K: every wave walks all of it, four visits per chunk)
@@ -607,8 +627,9 @@ void launch_nt(const Args& a, dim3 grid, int split_k, float* ws, hipStream_t str
 }
 }  // namespace
 
-hipError_t launch_skinny(const Args& call, int split_k, float* workspace, hipStream_t stream) {
+hipError_t launch_skinny(const Args& call, int split_k, float* workspace, hipStream_t stream, int variant) {
     if (call.dtype == DT_F32) return launch_gemv_f32(call, split_k, workspace, stream);
+    if ((variant < 0 ? skinny_variant_of(call) : variant) == 4) return launch_gemv16(call, split_k, workspace, stream);
     Args a = call;
     if (call.transA) {
         if (workspace == nullptr) return hipErrorInvalidValue;

@@ -364,7 +364,7 @@ def test_skinny_gaussian_and_split_agreement(handle, M, tb):
         ref, _, mag = oracle.gemm_full(oracle_problem(cfg, inp), want_bounds=True)
         for s in (1, 2, 3, 8):
             print(f"skinny M={M} tb={tb} dtype={dtype} split={s}", flush=True)
-            lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, -1, s)
+            lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, tb, s)      # the MFMA kernel of the layout, also where few rows would go to the vector ALUs
             p = DeviceProblem(cfg, inp)
             p.run(handle)
             assert lg.gemm_get_last_plan(handle) == (lg.GEMM_KERNEL_SKINNY, tb, s)

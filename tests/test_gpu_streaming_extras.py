@@ -104,3 +104,65 @@ def test_f32_streaming_refusals_and_automatic_choice(handle):
     q = DeviceProblem(small, wl.make_inputs(small, 5))
     q.run(handle)
     assert lg.gemm_get_last_plan(handle)[0] == lg.GEMM_KERNEL_MFMA_TILE
+
+
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F16])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 7, 8])
+def test_vector_alu_kernel_for_a_16_bit_weight_stored_n_by_k(handle, M, dtype):
+    """Variant 4 of the streaming family (at most 8 rows, B stored N x K, the sums on the vector ALUs): ragged last
+    group of columns (1048 = 65 * 16 + 8), a K that is no multiple of a trip of 512, padded leading dimensions, every
+    epilogue term, and a split of k through the reduction kernel."""
+    N, K = 1048, 2072
+    cfg = cfg_of(M, N, K, 0, 1, dtype, alpha=0.5, beta=-1.5, a_dist=("normal", 1.0), b_dist=("normal", 0.05),
+                 c_dist=("normal", 1.0), bias_dist=("normal", 0.3), bias_dtype=wl.F32, act=wl.ACT_GELU_TANH,
+                 lda=K + 8, ldb=K + 24, ldc=N + 5)
+    inp = wl.make_inputs(cfg, 90 + M)
+    # what lies behind the last k of a stored row must not reach the sums: NaN in the padding of both operands
+    nan16 = np.uint16(0x7fc0 if dtype == wl.BF16 else 0x7e00)
+    inp["A"].reshape(M, K + 8)[:, K:] = nan16
+    inp["B"].reshape(N, K + 24)[:, K:] = nan16
+    ref, _, mag = oracle.gemm_full(oracle_problem(cfg, inp), want_bounds=True)
+    assert np.isfinite(ref).all()
+    for s in (1, 2, 5):
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 4, s)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        kernel, variant, split = lg.gemm_get_last_plan(handle)
+        assert (kernel, variant) == (lg.GEMM_KERNEL_SKINNY, 4) and split <= s
+        assert_close(cfg, decode_c(cfg, p.result_bits()), ref, mag, f"16-bit vector-ALU kernel M={M} split {s}")
+        first = p.result_bits().copy()
+        p.reset_c()
+        p.run(handle)
+        assert np.array_equal(first.view(np.uint8), p.result_bits().view(np.uint8)), "two runs differ"
+    # integer data: a unique answer, whatever the kernel and the split; short and long k, fp32 and 16-bit C
+    for (n, k, out) in [(264, 4096, wl.F32), (40, 8, dtype), (8, 520, wl.F32), (4104, 1032, dtype)]:
+        icfg = cfg_of(M, n, k, 0, 1, dtype, out, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.F32)
+        iinp, _ = wl.make_integer_inputs(icfg, 17, -3, 3)
+        want = oracle.decode(out, expected_bits_exact(icfg, iinp))
+        for plan in [(lg.GEMM_KERNEL_SKINNY, 4, 0), (lg.GEMM_KERNEL_SKINNY, 4, 1), (lg.GEMM_KERNEL_SKINNY, 4, 3),
+                     (lg.GEMM_KERNEL_SKINNY, 1, 0), (0, -1, 0)]:
+            lg.gemm_set_plan(handle, *plan)
+            p = DeviceProblem(icfg, iinp)
+            p.run(handle)
+            assert np.array_equal(decode_c(icfg, p.result_bits()), want), (n, k, plan)
+    lg.gemm_set_plan(handle)
+
+
+def test_vector_alu_kernel_refusals_and_automatic_choice(handle):
+    # more than 8 rows, an A stored K x M, a row-major B, or a K that is no multiple of 8 are not for variant 4
+    for (M, N, K, ta, tb) in [(9, 1024, 1024, 0, 1), (4, 1024, 1024, 1, 1), (4, 1024, 1024, 0, 0), (4, 1024, 1020, 0, 1)]:
+        cfg = cfg_of(M, N, K, ta, tb, wl.BF16)
+        p = DeviceProblem(cfg, wl.make_inputs(cfg, 3))
+        lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 4, 1)
+        assert p.run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED
+    lg.gemm_set_plan(handle)
+    # the automatic plan: up to four rows on a weight stored N x K take it at every size, more rows do not
+    for (M, N, K, expect) in [(1, 4096, 4096, True), (4, 512, 512, True), (1, 8192, 8192, True), (5, 4096, 4096, False)]:
+        cfg = cfg_of(M, N, K, 0, 1, wl.BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.03))
+        inp = wl.make_inputs(cfg, 4)
+        p = DeviceProblem(cfg, inp)
+        p.run(handle)
+        kernel, variant, _ = lg.gemm_get_last_plan(handle)
+        assert ((kernel, variant) == (lg.GEMM_KERNEL_SKINNY, 4)) == expect, (M, N, K)
+        ref, _, mag = oracle.gemm_full(oracle_problem(cfg, inp), want_bounds=True)
+        assert_close(cfg, decode_c(cfg, p.result_bits()), ref, mag, f"automatic plan {M}x{N}x{K}")

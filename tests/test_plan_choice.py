@@ -44,6 +44,24 @@ def test_benchmark_configurations():
     assert (kernel, name) == (TILE, big) and split > 1
 
 
+def test_few_rows_on_a_16_bit_weight_stored_n_by_k_take_the_vector_alu_kernel():
+    """Up to four rows, B stored N x K, A row-major, one matrix: variant 4 of the streaming family in one launch at
+    every size (two slices only where N gives between a quarter and one workgroup per compute unit); more rows, the
+    other layouts, fp32 and batches keep their kernels."""
+    valu = "gemv16_nt_8x32_w4"
+    assert plan_of("G1") == (SKINNY, valu, 1) and plan_of("G7") == (SKINNY, valu, 1) and plan_of("G8") == (SKINNY, valu, 1)
+    for (M, N, K) in [(1, 512, 512), (2, 4096, 4096), (3, 16384, 16384), (4, 32000, 4096), (4, 128, 128)]:
+        for dtype in (wl.BF16, wl.F16):
+            assert plan(M, N, K, 0, 1, dtype=dtype)[:2] == (SKINNY, valu), (M, N, K)
+    assert plan(1, 1536, 8192, 0, 1) == (SKINNY, valu, 2)           # 96 groups of 16 columns on 256 units
+    assert plan(5, 4096, 4096, 0, 1)[0] == TILE and plan(8, 8192, 8192, 0, 1)[:2] == (SKINNY, "skinny_nt_32x256_w4")
+    assert plan(1, 4096, 4096, 0, 0)[0] == TILE                       # row-major B
+    assert plan(1, 4096, 4096, 1, 1)[1] != valu                       # A stored K x M
+    assert plan(4, 4096, 4100, 0, 1)[1] != valu                       # K no multiple of 8
+    c = wl.Config("b", 2, 512, 512, 0, 1, wl.BF16, wl.BF16, batch=3)
+    assert plan(c.M, c.N, c.K, 0, 1, c.dtype, c.out_dtype, c.batch, c.ld_a(), c.ld_b(), c.ld_c())[1] != valu
+
+
 def test_family_by_rows_and_weight_size():
     # the streaming kernels: up to 32 rows on a B of 128 MiB or more with K and N of 4096 or more
     assert plan(32, 8192, 8192)[0] == SKINNY and plan(1, 16384, 4096, 0, 1)[0] == SKINNY

@@ -179,6 +179,10 @@ EXTRA_CONFIGS: Dict[str, Config] = {
                  note="bf16 1x4096x4096 NN: a matrix-vector product on a 32 MiB weight (cache resident, launch bound)"),
     "G4": Config("G4", 8, 4096, 4096, 0, 1, BF16, BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
                  note="bf16 8x4096x4096 NT: 8 rows on a 32 MiB weight kept as [out, in] (cache resident, launch bound)"),
+    "G7": Config("G7", 1, 4096, 4096, 0, 1, BF16, BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                 note="bf16 1x4096x4096 NT: a matrix-vector product on a 32 MiB weight kept as [out, in] (cache resident; one launch on the vector ALUs)"),
+    "G8": Config("G8", 4, 28672, 8192, 0, 1, BF16, BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
+                 note="bf16 4x28672x8192 NT: 4 rows on a 448 MiB weight kept as [out, in] (a decoding step of four sequences)"),
     "G5": Config("G5", 1, 8192, 8192, 0, 0, F32, F32, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
                  note="fp32 1x8192x8192 NN: a matrix-vector product on a 256 MiB weight, vector ALUs"),
     "G6": Config("G6", 8, 8192, 8192, 0, 1, F32, F32, a_dist=("normal", 1.0), b_dist=("normal", 0.02),
