@@ -136,11 +136,11 @@ __global__ __launch_bounds__(GV_WAVES * 64) void gemv_f32_nt_kernel(Args a, int 
     // are fetched at an offset past the end of either and read as zero
     auto load = [&](f32x4 (&b)[CB], f32x4 (&av)[R], int trip) {
         const int k = trip * GV_NT_TRIP + 4 * lane;
-        const bool in = k < K;
+        const uint32_t k_off = k < K ? (uint32_t)k * 4 : GV_MASKED;      // one address register per trip; the rows are scalars
 #pragma unroll
-        for (int c = 0; c < CB; ++c) b[c] = gv_load4(rb, in ? b_row[c] + (uint32_t)k * 4 : GV_MASKED);
+        for (int c = 0; c < CB; ++c) b[c] = __builtin_bit_cast(f32x4, gv_load16(rb, k_off, b_row[c]));
 #pragma unroll
-        for (int r = 0; r < R; ++r) av[r] = gv_load4(ra, in ? a_row[r] + (uint32_t)k * 4 : GV_MASKED);
+        for (int r = 0; r < R; ++r) av[r] = __builtin_bit_cast(f32x4, gv_load16(ra, k_off, a_row[r]));
     };
     auto multiply = [&](const f32x4 (&b)[CB], const f32x4 (&av)[R]) {
 #pragma unroll
@@ -150,13 +150,41 @@ __global__ __launch_bounds__(GV_WAVES * 64) void gemv_f32_nt_kernel(Args a, int 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[c][r] = fmaf(av[r][e], b[c][e], acc[c][r]);
     };
+    // A fixed position along k is a fixed memory channel whatever the stored row when the rows are a power of two
+    // apart, and waves that walked k in step would queue on a few channels: every wave starts at a trip of its
+    // own and wraps around.  The start is not the wave's index itself (with rows of 32 KiB that puts the same
+    // bits into the address twice, and the part's channel choice folds them onto each other: 8 x 8192 x 8192
+    // 58 -> 65 us) but the index multiplied by 11 with its upper bits added.  The order of a column's sum is a
+    // fixed function of its wave.
+    const int n_trips = end - beg;
+    const unsigned walker = (unsigned)blockIdx.x * GV_WAVES + (unsigned)wave;
+    const int rot = n_trips > 0 ? (int)((walker * 11u + (walker >> 5) * 3u) % (unsigned)n_trips) : 0;
+    auto trip_at = [&](int i) { const int j = i + rot; return beg + (j >= n_trips ? j - n_trips : j); };
+    // two sets of landing registers; the fences keep the compiler from moving a trip's loads above the
+    // multiplications that still read their registers (it would need a third set)
     f32x4 b0[CB], b1[CB], a0[R], a1[R];
-    if (beg < end) load(b0, a0, beg);
-    for (int t = beg; t < end; t += 2) {
-        if (t + 1 < end) load(b1, a1, t + 1);
-        multiply(b0, a0);
-        if (t + 2 < end) load(b0, a0, t + 2);
-        if (t + 1 < end) multiply(b1, a1);
+    if (n_trips > 0) {
+        int t = 0;
+        load(b0, a0, trip_at(0));
+        for (; t + 2 < n_trips; t += 2) {
+            load(b1, a1, trip_at(t + 1));
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(b0, a0);
+            __builtin_amdgcn_sched_barrier(0);
+            load(b0, a0, trip_at(t + 2));
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(b1, a1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // one or two trips are left, the first of them requested already
+        if (t + 1 < n_trips) {
+            load(b1, a1, trip_at(t + 1));
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(b0, a0);
+            multiply(b1, a1);
+        } else {
+            multiply(b0, a0);
+        }
     }
 
     // fold the lanes' partial dot products: after the six exchanges every lane holds every sum
@@ -207,12 +235,15 @@ int gemv_f32_max_split(const Args& a) {
 // Measured on 2048^2 ... 16384^2 weights with 1, 4 and 8 rows.  Row-major B: one workgroup per compute
 // unit (two with more than four rows, whose steps are long) - 1 x 8192 x 8192: 49 us in 8 slices, 56 in
 // 16, 84 in 2.  B stored N x K: a workgroup streams whole stored rows and needs no help from a split
-// once there are enough column groups; only between a quarter and one group per unit do two slices
-// pay for the second kernel (8 x 4096 x 4096: 21 us in 2 slices, 26 whole; 1 x 2048 x 2048: 7 whole, 10 in 2).
+// once there are enough column groups; with at most half a group per unit the slices that fill the units
+// pay for the second kernel from 32 MiB on (8 x 4096 x 4096: 20 us in 2 slices, 22 whole; 1 x 2048 x 2048,
+// 16 MiB: 7 whole, 10 in 2).
 int gemv_f32_default_split(const Args& a, int num_cus) {
     const int64_t cus = num_cus > 0 ? num_cus : 256, groups = gemv_f32_groups(a), max_s = gemv_f32_max_split(a);
     int64_t s;
-    if (a.transB) s = (groups * 4 > cus && groups * 2 <= cus) ? 2 : 1;
+    // (with at most half a group per unit and 32 MiB or more to stream, as many slices as fill the units:
+    // 8 x 2048 x 8192 36 us whole, 21 in 4 slices)
+    if (a.transB) s = (groups * 2 <= cus && a.N * a.K * 4 >= ((int64_t)32 << 20)) ? cus / groups : 1;
     else s = ((a.M > 4 ? 2 : 1) * cus + groups - 1) / groups;
     if (s > max_s) s = max_s;
     if (s < 1) s = 1;

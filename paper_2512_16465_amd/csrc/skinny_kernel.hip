@@ -340,7 +340,7 @@ __global__ __launch_bounds__(ST_WAVES * 64) void skinny_nt_kernel(Args a, int sp
     // memory channel whatever the row: workgroups that walked k in step would all queue on the
     // same few channels.  Every column group therefore starts at a chunk of its own and wraps
     // around (the order of summation is a fixed function of the column group).
-    const int rot = nch > 0 ? (int)(blockIdx.x % (unsigned)nch) : 0;
+    const int rot = nch > 0 ? (int)(((unsigned)blockIdx.x * 11u + ((unsigned)blockIdx.x >> 5) * 3u) % (unsigned)nch) : 0;
     auto chunk_of = [&](int v) {      // for v < nvis
         const int c = (v >> 2) + rot;
         return cbeg + (c >= nch ? c - nch : c);
