@@ -39,6 +39,8 @@ def plans_for(M, dtype, ta):
              (lg.GEMM_KERNEL_MFMA_TILE, 5, 2), (lg.GEMM_KERNEL_GENERAL, 0, 1)]
     if M <= 64 and not ta:
         plans += [(lg.GEMM_KERNEL_SKINNY, -1, 1), (lg.GEMM_KERNEL_SKINNY, -1, 2)]
+    if M <= 8 and not ta:        # few rows: both kernels for a weight stored N x K, by name (each refuses the other layout)
+        plans += [(lg.GEMM_KERNEL_SKINNY, 1, 1), (lg.GEMM_KERNEL_SKINNY, 4, 1), (lg.GEMM_KERNEL_SKINNY, 4, 2)]
     return plans
 
 
@@ -68,7 +70,7 @@ def same_values(got, want):
 
 
 @pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
-@pytest.mark.parametrize("M,tb", [(48, 0), (48, 1), (264, 1), (264, 0)])
+@pytest.mark.parametrize("M,tb", [(48, 0), (48, 1), (264, 1), (264, 0), (4, 1), (8, 1)])
 def test_subnormal_inputs_are_multiplied_not_flushed(handle, dtype, M, tb):
     # A holds small integers times the smallest subnormal of the type, B small integers times a power of two
     # that brings every product and every sum back into the normal fp32 range: all arithmetic is exact
@@ -90,7 +92,7 @@ def test_subnormal_inputs_are_multiplied_not_flushed(handle, dtype, M, tb):
     assert ran >= 4
 
 
-@pytest.mark.parametrize("M,tb", [(40, 0), (40, 1), (136, 1)])
+@pytest.mark.parametrize("M,tb", [(40, 0), (40, 1), (136, 1), (3, 1), (8, 1)])
 def test_results_below_the_normal_range_of_fp32(handle, M, tb):
     # every product is an integer multiple of 2^-149: sums are exact subnormal fp32 numbers
     N, K = 128, 32
@@ -106,7 +108,7 @@ def test_results_below_the_normal_range_of_fp32(handle, M, tb):
 
 
 @pytest.mark.parametrize("dtype,limit", [(wl.F16, 65504.0), (wl.BF16, 3.3895313892515355e38)])
-@pytest.mark.parametrize("M,tb", [(32, 0), (32, 1), (200, 1)])
+@pytest.mark.parametrize("M,tb", [(32, 0), (32, 1), (200, 1), (2, 1), (8, 1)])
 def test_sums_beyond_the_output_type_become_infinite(handle, dtype, limit, M, tb):
     # column j of C is j * step: finite below the largest number of the type, an infinity above it, the sign
     # alternating by row
@@ -126,7 +128,7 @@ def test_sums_beyond_the_output_type_become_infinite(handle, dtype, limit, M, tb
 
 
 @pytest.mark.parametrize("dtype", [wl.F16, wl.BF16, wl.F32])
-@pytest.mark.parametrize("M,tb", [(24, 0), (24, 1), (160, 1)])
+@pytest.mark.parametrize("M,tb", [(24, 0), (24, 1), (160, 1), (4, 1), (8, 1)])
 def test_an_infinite_input_follows_ieee(handle, dtype, M, tb):
     # A[1][3] = +Inf, A[2][5] = -Inf; B small integers with zeros: Inf * positive = Inf, Inf * 0 = NaN, and rows
     # without an infinity stay finite and exact
