@@ -619,7 +619,10 @@ AutoPlan automatic_plan(const Args& a, int num_cus, bool batch_aligned) {
     // up to four rows on a 16-bit weight stored N x K: one launch of the vector-ALU kernel, at every size
     // (1 x 4096 x 4096 6.4 us against 12.0 on split tiles, 1 x 512 x 512 5.8 against 8.0); a batch would be
     // one launch per matrix and stays with the tiles
-    const bool few_rows = a.dtype != gemm::DT_F32 && a.batch == 1 && gemm::skinny_supports(a) && gemm::skinny_variant_of(a) == 4;
+    // ... and up to 16 rows on such a weight with at most 4096 stored rows and below 128 MiB: one launch of the
+    // MFMA kernel with 16 columns per workgroup (8 x 4096 x 4096 8.7 us against 12.3)
+    const bool few_rows = a.dtype != gemm::DT_F32 && a.batch == 1 && gemm::skinny_supports(a) &&
+                          (gemm::skinny_variant_of(a) == 4 || gemm::skinny_variant_of(a) == 5);
     if (may_stream && (long_stream || only_stream || few_rows)) {
         ap.plan = gemm_plan_t{GEMM_KERNEL_SKINNY, gemm::skinny_variant_of(a), gemm::skinny_default_split(a, num_cus)};
     } else if (gemm::tile_supports(a) && batch_aligned &&

@@ -28,6 +28,14 @@ constexpr int SK_MAX_ROWS = 64;  // rows of C the skinny kernels take
 // level (4 x 16384 x 16384 90.4 against 89.5); with 8 rows its multiplications show (8 x 8192 x 8192 29 against 27.5,
 // 8 x 28672 x 8192 102 against 79).
 constexpr int SK_GEMV16_ROWS = 4;
+// The kernel with 16 columns per workgroup (variant 5) takes up to 16 rows and is preferred where N / 16 workgroups
+// are one round of the chip at most, each with a k range long enough to fill its ring, on a weight below 128 MiB:
+// 8 x 4096 x 4096 8.7 us against 12.3 on split tiles and 16.3 in the wide kernel, 16 x 4096 x 4096 10.0 against 12.2,
+// 8 x 1024 x 8192 10.6 against 14.2, 8 x 4096 x 14336 21.8 against 24.2.  Beyond N = 4096 the short-lived
+// workgroups lose (8 x 11008 x 4096 25.8 against 20.4 wide, 8 x 16384 x 2048 29.6 against 17.3), and with 32 rows
+// (two row blocks, three visits in flight) it lost everywhere: that instance is not built.
+constexpr int SK_NARROW_ROWS = 16;
+constexpr int64_t SK_NARROW_BYTES = (int64_t)128 << 20, SK_NARROW_MAX_N = 4096, SK_NARROW_MIN_K = 2048;
 constexpr uint32_t SK_MASKED = 0x7ffffff0u;   // an offset past the end of any operand: the load returns zero
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t sk_rsrc(const void* base, int64_t bytes) {
@@ -468,6 +476,162 @@ __global__ __launch_bounds__(ST_WAVES * 64) void skinny_nt_kernel(Args a, int sp
         }
 }
 
+// The same kernel cut for weights that are short of workgroups: a workgroup owns one block of 16 columns
+// and its four waves take every fourth chunk of the k range each, adding their sums through LDS at the end
+// (wave 0 adds waves 1, 2, 3 in that order).  N / 16 workgroups fill the chip from N = 4096 on, so a weight
+// below 128 MiB needs no split of k and no second launch, which is what the wide kernel costs there
+// (8 x 4096 x 4096: 16 us in 4 slices).  The price is A: every visit brings its own pieces of A (the wide
+// kernel shares them over four column blocks) into the registers of its ring slot, as many bytes through the
+// caches as B brings from memory.  Four visits in flight per wave (the waits count the wave's younger loads,
+// 16 per visit, and the counter ends at 63).
+template <bool IS_BF16, int H>
+__global__ __launch_bounds__(ST_WAVES * 64) void skinny_nt_narrow_kernel(Args a, int split_k, float* ws) {
+    static_assert(H == 1, "16 rows of C (a second row block needs the registers of a visit in flight)");
+    constexpr int D = 4;                              // visits in flight per wave
+    constexpr int PER_VISIT = 8 + 8 * H;              // loads a visit issues: 8 H for A, 8 for B
+    static_assert((D - 1) * PER_VISIT <= 63, "the wait counter has six bits");
+    __shared__ __attribute__((aligned(1024))) char ring[ST_WAVES * D * ST_VISIT_BYTES];
+    __shared__ f32x4 red[(ST_WAVES - 1) * H * 64];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c16 = lane & 15, g = lane >> 4;
+    const int M = (int)a.M, K = (int)a.K;
+    const int64_t N = a.N;
+
+    const int total_chunks = (K + ST_CHUNK - 1) / ST_CHUNK;
+    const int per_split = (total_chunks + split_k - 1) / split_k;
+    const int cbeg = blockIdx.y * per_split;
+    const int cend = (cbeg + per_split) < total_chunks ? (cbeg + per_split) : total_chunks;
+    const int nch = cend > cbeg ? cend - cbeg : 0;
+    // wave w takes the chunks at positions w, w + 4, ... of the workgroup's walk, which starts at a chunk of
+    // the column block's own and wraps around (the starts decorrelated from the block's index as in
+    // gemv16_kernel.hip); the order of summation is a fixed function of the column block
+    const int nvis = nch > wave ? (nch - wave + ST_WAVES - 1) / ST_WAVES : 0;
+    const int rot = nch > 0 ? (int)(((unsigned)blockIdx.x * 11u + ((unsigned)blockIdx.x >> 5) * 3u) % (unsigned)nch) : 0;
+    auto chunk_of = [&](int v) {      // for v < nvis
+        const int c = v * ST_WAVES + wave + rot;
+        return cbeg + (c >= nch ? c - nch : c);
+    };
+
+    const int64_t n0 = (int64_t)blockIdx.x * 16;
+    const __amdgpu_buffer_rsrc_t rb = sk_rsrc(a.B, ((int64_t)(N - 1) * a.ldb + K) * 2);
+    const __amdgpu_buffer_rsrc_t ra = sk_rsrc(a.A, ((int64_t)(M - 1) * a.lda + K) * 2);
+
+    // global side of a visit: instruction i fetches stored rows 2i and 2i+1 of the block; this
+    // lane serves row 2i + lr, slot ls, i.e. piece ls xor (2i + lr) of that row
+    const int lr = lane >> 5, ls = lane & 31;
+    const int n_first = (int)n0, n_last = (int)N - 1;
+    const uint32_t ldb_b = (uint32_t)a.ldb * 2;
+    char* const my_ring = ring + wave * (D * ST_VISIT_BYTES);
+    // LDS side: operand of step t for this lane = row c16, piece 4t + g, kept in slot (4t + g) xor c16
+    uint32_t frag_addr[ST_RUN];
+#pragma unroll
+    for (int t = 0; t < ST_RUN; ++t)
+        frag_addr[t] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)my_ring + (uint32_t)(c16 * 512 + (((4 * t + g) ^ c16) << 4));
+
+    uint32_t a_row_off[H];
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        const int r = 16 * h + c16;
+        a_row_off[h] = (uint32_t)((r < M ? r : M - 1) * a.lda * 2);     // rows >= M repeat a valid one and are never stored
+    }
+
+    f32x4 acc[H];
+#pragma unroll
+    for (int h = 0; h < H; ++h) acc[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 aq[D][H][ST_RUN];              // the pieces of A of the visit in each ring slot
+
+    // Every visit slot of the loop below issues its loads whether the visit exists or not (a visit past
+    // the end fetches nothing: all its offsets are masked and read as zero), so the number of loads in
+    // flight behind any given one is the same on every path and the waits can be exact.
+    auto load_visit = [&](auto slot_c, int v) {
+        constexpr int slot = decltype(slot_c)::value;
+        const bool live = v < nvis;
+        const int chunk = live ? chunk_of(v) : cbeg;
+        const int kbase = chunk * ST_CHUNK + 8 * g;
+#pragma unroll
+        for (int t = 0; t < ST_RUN; ++t) {
+            const int k = kbase + 32 * t;
+#pragma unroll
+            for (int h = 0; h < H; ++h)
+                aq[slot][h][t] = __builtin_amdgcn_raw_buffer_load_b128(ra, (live && k < K) ? a_row_off[h] + (uint32_t)k * 2 : ST_MASKED, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int rl = 2 * i + lr;                                   // row of the block
+            const int n = n_first + rl;
+            const int k = chunk * ST_CHUNK + ((ls ^ rl) << 3);
+            const uint32_t off = (uint32_t)(n < n_last ? n : n_last) * ldb_b + (uint32_t)k * 2;   // columns >= N repeat a valid one and are never stored
+            const uint32_t masked_off = (live && k < K) ? off : ST_MASKED;
+            st_load_to_lds(rb, my_ring + slot * ST_VISIT_BYTES + i * 1024, masked_off);
+        }
+    };
+    // Loads issued after this visit's own: those of the D - 1 visits behind it in the ring.  The slot is
+    // refilled (visit v + D, LDS and registers of A alike) once the multiplications that read it are issued.
+    auto process = [&](auto slot_c, int v) {
+        constexpr int slot = decltype(slot_c)::value;
+        st_wait_loads<(D - 1) * PER_VISIT>();
+        u32x4 cur[ST_RUN];
+#pragma unroll
+        for (int t = 0; t < ST_RUN; ++t)
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(cur[t]) : "v"(frag_addr[t]), "n"(slot * ST_VISIT_BYTES) : "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(cur[0]), "+v"(cur[1]), "+v"(cur[2]), "+v"(cur[3]), "+v"(cur[4]), "+v"(cur[5]), "+v"(cur[6]), "+v"(cur[7])
+                     :: "memory");
+#pragma unroll
+        for (int t = 0; t < ST_RUN; ++t)
+#pragma unroll
+            for (int h = 0; h < H; ++h) acc[h] = st_mfma<IS_BF16>(aq[slot][h][t], cur[t], acc[h]);
+        __builtin_amdgcn_sched_barrier(0);
+        load_visit(slot_c, v + D);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    load_visit(std::integral_constant<int, 0>{}, 0);
+    load_visit(std::integral_constant<int, 1>{}, 1);
+    load_visit(std::integral_constant<int, 2>{}, 2);
+    load_visit(std::integral_constant<int, 3>{}, 3);
+    for (int v0 = 0; v0 < nvis; v0 += D) {      // a trailing part of a group works on zeros
+        process(std::integral_constant<int, 0>{}, v0 + 0);
+        process(std::integral_constant<int, 1>{}, v0 + 1);
+        process(std::integral_constant<int, 2>{}, v0 + 2);
+        process(std::integral_constant<int, 3>{}, v0 + 3);
+    }
+    st_wait_loads<0>();      // the masked loads of the last visits still write (zeros) to LDS
+
+    // waves 1 .. 3 park their sums; wave 0 adds them in the order of the waves
+    if (wave > 0) {
+#pragma unroll
+        for (int h = 0; h < H; ++h) red[((wave - 1) * H + h) * 64 + lane] = acc[h];
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int w = 0; w < ST_WAVES - 1; ++w)
+#pragma unroll
+        for (int h = 0; h < H; ++h) acc[h] += red[(w * H + h) * 64 + lane];
+#pragma unroll
+    for (int h = 0; h < H; ++h)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int row = 16 * h + 4 * g + v;
+            if (row >= M) continue;
+            const int64_t col = n0 + c16;
+            if (col >= N) continue;
+            const float x = acc[h][v];
+            if (split_k > 1) {
+                ws[((int64_t)blockIdx.y * M + row) * N + col] = x;
+            } else {
+                const int64_t ci = row * a.ldc + col;
+                const float c_in = a.beta != 0.0f ? load_elem(a.C, a.out_dtype, ci) : 0.0f;
+                const float bj = a.bias ? load_elem(a.bias, a.bias_dtype, col) : 0.0f;
+                store_elem(a.C, a.out_dtype, ci, epilogue_value(x, a.alpha, a.beta, c_in, bj, a.act));
+            }
+        }
+}
+
 // Sums the split-K slices in the order 0, 1, ..., S-1 and applies the epilogue; 8 columns per thread.
 // The kernel is one round trip to memory long, so everything it reads is requested before
 // anything is used: S > 0 fixes the number of slices at compile time (all their loads are issued
@@ -546,6 +710,8 @@ bool skinny_supports(const Args& a) {
 // Variants 2 and 3: the same two layouts for fp32 operands and at most 8 rows (gemv_f32_kernel.hip).
 // Variant 4: 16-bit operands, B stored N x K, at most 8 rows, on the vector ALUs (gemv16_kernel.hip);
 // preferred to variant 1 up to SK_GEMV16_ROWS rows.
+// Variant 5: variant 1 with 16 columns per workgroup (skinny_nt_narrow_kernel), at most 16 rows; preferred
+// to variant 1 for small weights (see SK_NARROW_ROWS).
 const char* skinny_variant_name(int variant) {
     switch (variant) {
         case 0: return "skinny_nn_32x256_w4";
@@ -553,19 +719,24 @@ const char* skinny_variant_name(int variant) {
         case 2: return "gemv_f32_nn_8x256_w4";
         case 3: return "gemv_f32_nt_8x32_w4";
         case 4: return "gemv16_nt_8x32_w4";
+        case 5: return "skinny_nt_16x16_w4";
         default: return nullptr;
     }
 }
 
+static bool skinny_narrow_serves(const Args& a) { return a.dtype != DT_F32 && a.transB && a.M <= SK_NARROW_ROWS; }
+
 int skinny_variant_of(const Args& a) {
     if (a.dtype != DT_F32 && a.M <= SK_GEMV16_ROWS && gemv16_supports(a)) return 4;
+    if (skinny_narrow_serves(a) && !a.transA && a.N <= SK_NARROW_MAX_N && a.K >= SK_NARROW_MIN_K && a.N * a.K * 2 < SK_NARROW_BYTES) return 5;
     return (a.dtype == DT_F32 ? 2 : 0) + (a.transB ? 1 : 0);
 }
 
 bool skinny_variant_serves(const Args& a, int variant) {
     if (variant < 0 || variant == skinny_variant_of(a)) return true;
     if (variant == 4) return gemv16_supports(a);
-    // the MFMA kernel for a weight stored N x K also takes the calls that variant 4 is preferred for
+    if (variant == 5) return skinny_narrow_serves(a);
+    // the wide MFMA kernel for a weight stored N x K also takes the calls that variants 4 and 5 are preferred for
     return variant == 1 && a.dtype != DT_F32 && a.transB;
 }
 
@@ -574,14 +745,26 @@ static int64_t skinny_k_units(const Args& a) { return a.transB ? (a.K + ST_CHUNK
 
 int skinny_max_split(const Args& a, int variant) {
     if (a.dtype == DT_F32) return gemv_f32_max_split(a);
-    if ((variant < 0 ? skinny_variant_of(a) : variant) == 4) return gemv16_max_split(a);
+    const int v = variant < 0 ? skinny_variant_of(a) : variant;
+    if (v == 4) return gemv16_max_split(a);
+    if (v == 5) {      // four visits per wave and slice at least
+        const int64_t s = skinny_k_units(a) / (ST_WAVES * 4);
+        return (int)(s < 1 ? 1 : (s > 64 ? 64 : s));
+    }
     const int64_t units = skinny_k_units(a);
     return (int)(units < 1 ? 1 : (units > 64 ? 64 : units));
 }
 
 int skinny_default_split(const Args& a, int num_cus, int variant) {
     if (a.dtype == DT_F32) return gemv_f32_default_split(a, num_cus);
-    if ((variant < 0 ? skinny_variant_of(a) : variant) == 4) return gemv16_default_split(a, num_cus);
+    const int v = variant < 0 ? skinny_variant_of(a) : variant;
+    if (v == 4) return gemv16_default_split(a, num_cus);
+    if (v == 5) {      // one launch wherever N gives half a workgroup per compute unit or more; else the slices that fill the units
+        const int64_t g16 = (a.N + 15) / 16, units = num_cus > 0 ? num_cus : 256, max16 = skinny_max_split(a, 5);
+        int64_t s16 = g16 * 2 <= units ? units / g16 : 1;
+        if (s16 > max16) s16 = max16;
+        return (int)(s16 < 1 ? 1 : s16);
+    }
     const int64_t groups = (a.N + SK_COLS - 1) / SK_COLS, cus = num_cus > 0 ? num_cus : 256;
     // keep the pipeline of every wave filled a few times over (row-major B: the waves of a
     // workgroup share its k range; B stored N x K: every wave walks all of it, four visits per chunk)
@@ -629,7 +812,8 @@ void launch_nt(const Args& a, dim3 grid, int split_k, float* ws, hipStream_t str
 
 hipError_t launch_skinny(const Args& call, int split_k, float* workspace, hipStream_t stream, int variant) {
     if (call.dtype == DT_F32) return launch_gemv_f32(call, split_k, workspace, stream);
-    if ((variant < 0 ? skinny_variant_of(call) : variant) == 4) return launch_gemv16(call, split_k, workspace, stream);
+    const int v = variant < 0 ? skinny_variant_of(call) : variant;
+    if (v == 4) return launch_gemv16(call, split_k, workspace, stream);
     Args a = call;
     if (call.transA) {
         if (workspace == nullptr) return hipErrorInvalidValue;
@@ -651,7 +835,12 @@ hipError_t launch_skinny(const Args& call, int split_k, float* workspace, hipStr
     // 8 outputs per vector store: 32 bytes of fp32 or 16 bytes of a 16-bit type
     const int c_vec_ok = (a.ldc % 8 == 0) && ((uintptr_t)a.C % 16 == 0);
     const dim3 grid((unsigned)groups, (unsigned)split_k), block(SK_WAVES * 64);
-    if (a.transB) {
+    if (a.transB && v == 5) {
+        if (a.M > SK_NARROW_ROWS) return hipErrorInvalidValue;
+        const dim3 ngrid((unsigned)((a.N + 15) / 16), (unsigned)split_k), nblock(ST_WAVES * 64);
+        if (a.dtype == DT_BF16) hipLaunchKernelGGL((skinny_nt_narrow_kernel<true, 1>), ngrid, nblock, 0, stream, a, split_k, workspace);
+        else hipLaunchKernelGGL((skinny_nt_narrow_kernel<false, 1>), ngrid, nblock, 0, stream, a, split_k, workspace);
+    } else if (a.transB) {
         if (a.dtype == DT_BF16) launch_nt<true>(a, grid, split_k, workspace, stream);
         else launch_nt<false>(a, grid, split_k, workspace, stream);
     } else if (a.dtype == DT_BF16) {

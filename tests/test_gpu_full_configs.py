@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 FULL = ["C2", "C3", "C4", "C5", "X1", "X2", "X3", "X4", "X5", "X6", "X7", "X9", "X10", "X11",
         "G1", "G2", "G3", "G4", "G5", "G6", "G7", "G8"]
 ALL = {**wl.CONFIGS, **wl.EXTRA_CONFIGS}
-SKINNY = ("C5", "X5", "X7", "G1", "G2", "G5", "G6", "G7", "G8")      # the streaming kernels (bf16/fp16 skinny, fp32 rows)
+SKINNY = ("C5", "X5", "X7", "G1", "G2", "G4", "G5", "G6", "G7", "G8")      # the streaming kernels (bf16/fp16 skinny, fp32 rows)
 
 
 @pytest.fixture(scope="module")

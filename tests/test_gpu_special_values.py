@@ -40,7 +40,7 @@ def plans_for(M, dtype, ta):
     if M <= 64 and not ta:
         plans += [(lg.GEMM_KERNEL_SKINNY, -1, 1), (lg.GEMM_KERNEL_SKINNY, -1, 2)]
     if M <= 8 and not ta:        # few rows: both kernels for a weight stored N x K, by name (each refuses the other layout)
-        plans += [(lg.GEMM_KERNEL_SKINNY, 1, 1), (lg.GEMM_KERNEL_SKINNY, 4, 1), (lg.GEMM_KERNEL_SKINNY, 4, 2)]
+        plans += [(lg.GEMM_KERNEL_SKINNY, 1, 1), (lg.GEMM_KERNEL_SKINNY, 4, 1), (lg.GEMM_KERNEL_SKINNY, 4, 2), (lg.GEMM_KERNEL_SKINNY, 5, 1)]
     return plans
 
 
