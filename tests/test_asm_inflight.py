@@ -102,6 +102,8 @@ CHECKED_UNITS = [
     ("tile_variant_10.hip", "tile_dma16_kernel"), ("tile_variant_14.hip", "tile_dma16_kernel"),
     ("tile_variant_15.hip", "tile_dma16_kernel"), ("tile_variant_16.hip", "tile_dma16_kernel"),
     ("tile_variant_17.hip", "tile_shortk_kernel"),
+    # the streaming kernels for B stored N x K read their ring with the same kind of assembly (wide and 16-column form)
+    ("skinny_kernel.hip", "skinny_nt"),
 ]
 
 
