@@ -36,6 +36,11 @@ constexpr int SK_GEMV16_ROWS = 4;
 // (two row blocks, three visits in flight) it lost everywhere: that instance is not built.
 constexpr int SK_NARROW_ROWS = 16;
 constexpr int64_t SK_NARROW_BYTES = (int64_t)128 << 20, SK_NARROW_MAX_N = 4096, SK_NARROW_MIN_K = 2048;
+// Up to three rounds of workgroups it still pays with two visits in flight per wave, so that two workgroups share a
+// compute unit and fill each other's gaps, where k is long enough: 8 x 8192 x 8192 25.0 us against 27.5 wide,
+// 8 x 8192 x 4096 14.6 against 17.4 on split tiles, 8 x 11008 x 4096 19.9 against 20.4 wide and 23.3 on tiles; not
+// beyond (8 x 32000 x 4096 56 against 52.5, 16 x 28672 x 8192 96 against 79).
+constexpr int64_t SK_NARROW_FAR_N = 12288, SK_NARROW_FAR_K = 4096;
 constexpr uint32_t SK_MASKED = 0x7ffffff0u;   // an offset past the end of any operand: the load returns zero
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t sk_rsrc(const void* base, int64_t bytes) {
@@ -484,10 +489,10 @@ __global__ __launch_bounds__(ST_WAVES * 64) void skinny_nt_kernel(Args a, int sp
 // kernel shares them over four column blocks) into the registers of its ring slot, as many bytes through the
 // caches as B brings from memory.  Four visits in flight per wave (the waits count the wave's younger loads,
 // 16 per visit, and the counter ends at 63).
-template <bool IS_BF16, int H>
+template <bool IS_BF16, int H, int D>
 __global__ __launch_bounds__(ST_WAVES * 64) void skinny_nt_narrow_kernel(Args a, int split_k, float* ws) {
     static_assert(H == 1, "16 rows of C (a second row block needs the registers of a visit in flight)");
-    constexpr int D = 4;                              // visits in flight per wave
+    static_assert(D == 2 || D == 4, "visits in flight per wave: four, or two with two workgroups per compute unit");
     constexpr int PER_VISIT = 8 + 8 * H;              // loads a visit issues: 8 H for A, 8 for B
     static_assert((D - 1) * PER_VISIT <= 63, "the wait counter has six bits");
     __shared__ __attribute__((aligned(1024))) char ring[ST_WAVES * D * ST_VISIT_BYTES];
@@ -591,13 +596,17 @@ __global__ __launch_bounds__(ST_WAVES * 64) void skinny_nt_narrow_kernel(Args a,
 
     load_visit(std::integral_constant<int, 0>{}, 0);
     load_visit(std::integral_constant<int, 1>{}, 1);
-    load_visit(std::integral_constant<int, 2>{}, 2);
-    load_visit(std::integral_constant<int, 3>{}, 3);
+    if constexpr (D == 4) {
+        load_visit(std::integral_constant<int, 2>{}, 2);
+        load_visit(std::integral_constant<int, 3>{}, 3);
+    }
     for (int v0 = 0; v0 < nvis; v0 += D) {      // a trailing part of a group works on zeros
         process(std::integral_constant<int, 0>{}, v0 + 0);
         process(std::integral_constant<int, 1>{}, v0 + 1);
-        process(std::integral_constant<int, 2>{}, v0 + 2);
-        process(std::integral_constant<int, 3>{}, v0 + 3);
+        if constexpr (D == 4) {
+            process(std::integral_constant<int, 2>{}, v0 + 2);
+            process(std::integral_constant<int, 3>{}, v0 + 3);
+        }
     }
     st_wait_loads<0>();      // the masked loads of the last visits still write (zeros) to LDS
 
@@ -728,7 +737,9 @@ static bool skinny_narrow_serves(const Args& a) { return a.dtype != DT_F32 && a.
 
 int skinny_variant_of(const Args& a) {
     if (a.dtype != DT_F32 && a.M <= SK_GEMV16_ROWS && gemv16_supports(a)) return 4;
-    if (skinny_narrow_serves(a) && !a.transA && a.N <= SK_NARROW_MAX_N && a.K >= SK_NARROW_MIN_K && a.N * a.K * 2 < SK_NARROW_BYTES) return 5;
+    if (skinny_narrow_serves(a) && !a.transA && a.K >= SK_NARROW_MIN_K && a.N * a.K * 2 <= SK_NARROW_BYTES &&
+        (a.N <= SK_NARROW_MAX_N || (a.N <= SK_NARROW_FAR_N && a.K >= SK_NARROW_FAR_K)))
+        return 5;
     return (a.dtype == DT_F32 ? 2 : 0) + (a.transB ? 1 : 0);
 }
 
@@ -838,8 +849,14 @@ hipError_t launch_skinny(const Args& call, int split_k, float* workspace, hipStr
     if (a.transB && v == 5) {
         if (a.M > SK_NARROW_ROWS) return hipErrorInvalidValue;
         const dim3 ngrid((unsigned)((a.N + 15) / 16), (unsigned)split_k), nblock(ST_WAVES * 64);
-        if (a.dtype == DT_BF16) hipLaunchKernelGGL((skinny_nt_narrow_kernel<true, 1>), ngrid, nblock, 0, stream, a, split_k, workspace);
-        else hipLaunchKernelGGL((skinny_nt_narrow_kernel<false, 1>), ngrid, nblock, 0, stream, a, split_k, workspace);
+        // one round of workgroups at most: four visits in flight per wave; more: two, and two workgroups per compute unit
+        if (a.N <= SK_NARROW_MAX_N) {
+            if (a.dtype == DT_BF16) hipLaunchKernelGGL((skinny_nt_narrow_kernel<true, 1, 4>), ngrid, nblock, 0, stream, a, split_k, workspace);
+            else hipLaunchKernelGGL((skinny_nt_narrow_kernel<false, 1, 4>), ngrid, nblock, 0, stream, a, split_k, workspace);
+        } else {
+            if (a.dtype == DT_BF16) hipLaunchKernelGGL((skinny_nt_narrow_kernel<true, 1, 2>), ngrid, nblock, 0, stream, a, split_k, workspace);
+            else hipLaunchKernelGGL((skinny_nt_narrow_kernel<false, 1, 2>), ngrid, nblock, 0, stream, a, split_k, workspace);
+        }
     } else if (a.transB) {
         if (a.dtype == DT_BF16) launch_nt<true>(a, grid, split_k, workspace, stream);
         else launch_nt<false>(a, grid, split_k, workspace, stream);

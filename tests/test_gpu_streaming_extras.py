@@ -169,13 +169,15 @@ def test_vector_alu_kernel_refusals_and_automatic_choice(handle):
 
 
 @pytest.mark.parametrize("dtype", [wl.BF16, wl.F16])
+@pytest.mark.parametrize("N", [1048, 4360])
 @pytest.mark.parametrize("M", [1, 5, 8, 13, 16])
-def test_mfma_kernel_with_16_columns_per_workgroup(handle, M, dtype):
+def test_mfma_kernel_with_16_columns_per_workgroup(handle, M, N, dtype):
     """Variant 5 of the streaming family (B stored N x K, at most 16 rows, one block of 16 columns per workgroup whose
-    waves share the k range): a ragged last block (1048 = 65 * 16 + 8), a K that is no multiple of a chunk of 256 and
-    gives the four waves 3, 2, 2 and 2 chunks, padded leading dimensions with NaN behind every row, every epilogue term,
-    and slices of k through the reduction kernel."""
-    N, K = 1048, 2072
+    waves share the k range), with four visits in flight per wave (N <= 4096) and with two: a ragged last block
+    (1048 = 65 * 16 + 8, 4360 = 272 * 16 + 8), a K that is no multiple of a chunk of 256 and gives the four waves 3, 2, 2
+    and 2 chunks, padded leading dimensions with NaN behind every row, every epilogue term, and slices of k through
+    the reduction kernel."""
+    K = 2072
     cfg = cfg_of(M, N, K, 0, 1, dtype, alpha=0.5, beta=-1.5, a_dist=("normal", 1.0), b_dist=("normal", 0.05),
                  c_dist=("normal", 1.0), bias_dist=("normal", 0.3), bias_dtype=wl.F32, act=wl.ACT_GELU_TANH,
                  lda=K + 8, ldb=K + 24, ldc=N + 5)
@@ -197,7 +199,7 @@ def test_mfma_kernel_with_16_columns_per_workgroup(handle, M, dtype):
         p.run(handle)
         assert np.array_equal(first.view(np.uint8), p.result_bits().view(np.uint8)), "two runs differ"
     # integer data: a unique answer, whatever the kernel and the split; one chunk, fewer chunks than waves, many
-    for (n, k, out) in [(264, 4096, wl.F32), (40, 8, dtype), (24, 520, wl.F32), (4104, 1032, dtype), (4096, 8192, wl.F32)]:
+    for (n, k, out) in [(264, 4096, wl.F32), (40, 8, dtype), (24, 520, wl.F32), (4104, 1032, dtype), (4096, 8192, wl.F32), (6152, 4360, dtype)]:
         icfg = cfg_of(M, n, k, 0, 1, dtype, out, alpha=1.0, beta=1.0, bias_dist=("normal", 1.0), bias_dtype=wl.F32)
         iinp, _ = wl.make_integer_inputs(icfg, 19, -3, 3)
         want = oracle.decode(out, expected_bits_exact(icfg, iinp))
@@ -218,7 +220,7 @@ def test_mfma_kernel_with_16_columns_refusals_and_automatic_choice(handle):
         lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 5, 1)
         assert p.run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED
     lg.gemm_set_plan(handle)
-    for (M, N, K, expect) in [(8, 4096, 4096, True), (16, 2048, 4096, True), (17, 4096, 4096, False), (8, 8192, 4096, False)]:
+    for (M, N, K, expect) in [(8, 4096, 4096, True), (16, 2048, 4096, True), (17, 4096, 4096, False), (8, 8192, 4096, True), (8, 8192, 2048, False)]:
         cfg = cfg_of(M, N, K, 0, 1, wl.BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.03))
         inp = wl.make_inputs(cfg, 4)
         p = DeviceProblem(cfg, inp)

@@ -54,16 +54,17 @@ def test_few_rows_on_a_16_bit_weight_stored_n_by_k_take_the_vector_alu_kernel():
         for dtype in (wl.BF16, wl.F16):
             assert plan(M, N, K, 0, 1, dtype=dtype)[:2] == (SKINNY, valu), (M, N, K)
     assert plan(1, 1536, 8192, 0, 1) == (SKINNY, valu, 2)           # 96 groups of 16 columns on 256 units
-    assert plan(8, 8192, 8192, 0, 1)[:2] == (SKINNY, "skinny_nt_32x256_w4")
-    # 5 to 16 rows where N / 16 workgroups are one round at most and k is long: the MFMA kernel with 16 columns per
-    # workgroup, in one launch (two slices where N leaves half the units idle)
+    assert plan(17, 8192, 8192, 0, 1)[:2] == (SKINNY, "skinny_nt_32x256_w4") and plan(8, 16384, 8192, 0, 1)[:2] == (SKINNY, "skinny_nt_32x256_w4")
+    # 5 to 16 rows on a weight of 128 MiB at most with a long k: the MFMA kernel with 16 columns per workgroup, in
+    # one launch (two slices where N leaves half the units idle), up to 4096 stored rows, and up to 12288 where K >= 4096
     narrow = "skinny_nt_16x16_w4"
     assert plan(5, 4096, 4096, 0, 1) == (SKINNY, narrow, 1) and plan(16, 4096, 14336, 0, 1) == (SKINNY, narrow, 1)
     assert plan_of("G4") == (SKINNY, narrow, 1)
     assert plan(8, 1024, 8192, 0, 1) == (SKINNY, narrow, 2) and plan(16, 2048, 2048, 0, 1) == (SKINNY, narrow, 1)      # at least four visits per wave and slice
-    for (M, N, K) in [(17, 4096, 4096), (8, 4104, 4096), (8, 4096, 1024), (8, 11008, 4096)]:
+    for (M, N, K) in [(8, 8192, 8192), (8, 4096, 16384), (16, 11008, 4096), (8, 4104, 4096), (5, 12288, 5120)]:
+        assert plan(M, N, K, 0, 1) == (SKINNY, narrow, 1), (M, N, K)
+    for (M, N, K) in [(17, 4096, 4096), (8, 4096, 1024), (8, 8192, 2048), (8, 12296, 4096)]:
         assert plan(M, N, K, 0, 1)[0] == TILE, (M, N, K)
-    assert plan(8, 4096, 16384, 0, 1)[:2] == (SKINNY, "skinny_nt_32x256_w4")     # 128 MiB: the wide kernel with its slices
     assert plan(8, 4096, 4096, 1, 1)[1] != narrow and plan(8, 4096, 4096, 0, 0)[1] != narrow
     assert plan(1, 4096, 4096, 0, 0)[0] == TILE                       # row-major B
     assert plan(1, 4096, 4096, 1, 1)[1] != valu                       # A stored K x M
