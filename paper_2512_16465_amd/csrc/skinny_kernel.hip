@@ -35,12 +35,16 @@ constexpr int SK_GEMV16_ROWS = 4;
 // workgroups lose (8 x 11008 x 4096 25.8 against 20.4 wide, 8 x 16384 x 2048 29.6 against 17.3), and with 32 rows
 // (two row blocks, three visits in flight) it lost everywhere: that instance is not built.
 constexpr int SK_NARROW_ROWS = 16;
-constexpr int64_t SK_NARROW_BYTES = (int64_t)128 << 20, SK_NARROW_MAX_N = 4096, SK_NARROW_MIN_K = 2048;
+// (a short k does not hurt it: 8 x 4096 x 256 7.2 us against 8.1, 8 x 1024 x 1024 7.7 against 10.4, 16 x 4096 x 512 7.4 against 9.3)
+constexpr int64_t SK_NARROW_BYTES = (int64_t)128 << 20, SK_NARROW_MAX_N = 4096, SK_NARROW_MIN_K = 256;
 // Up to three rounds of workgroups it still pays with two visits in flight per wave, so that two workgroups share a
 // compute unit and fill each other's gaps, where k is long enough: 8 x 8192 x 8192 25.0 us against 27.5 wide,
 // 8 x 8192 x 4096 14.6 against 17.4 on split tiles, 8 x 11008 x 4096 19.9 against 20.4 wide and 23.3 on tiles; not
 // beyond (8 x 32000 x 4096 56 against 52.5, 16 x 28672 x 8192 96 against 79).
-constexpr int64_t SK_NARROW_FAR_N = 12288, SK_NARROW_FAR_K = 4096;
+// With 9 to 16 rows the partly filled last round shows: 16 x 5120 x 5120 18.2 against 15.4 on split tiles (320 workgroups
+// on 512 places), 16 x 9216 x 4608 22.7 against 20.1 (576 on 1024), but 16 x 11008 x 4096 22.0 against 23.3 (688 on 1024):
+// then the places must be 65 % full.  The places are those of a 256-unit part.
+constexpr int64_t SK_NARROW_FAR_N = 12288, SK_NARROW_FAR_K = 1024, SK_NARROW_PLACES = 512;
 constexpr uint32_t SK_MASKED = 0x7ffffff0u;   // an offset past the end of any operand: the load returns zero
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t sk_rsrc(const void* base, int64_t bytes) {
@@ -737,9 +741,11 @@ static bool skinny_narrow_serves(const Args& a) { return a.dtype != DT_F32 && a.
 
 int skinny_variant_of(const Args& a) {
     if (a.dtype != DT_F32 && a.M <= SK_GEMV16_ROWS && gemv16_supports(a)) return 4;
-    if (skinny_narrow_serves(a) && !a.transA && a.K >= SK_NARROW_MIN_K && a.N * a.K * 2 <= SK_NARROW_BYTES &&
-        (a.N <= SK_NARROW_MAX_N || (a.N <= SK_NARROW_FAR_N && a.K >= SK_NARROW_FAR_K)))
-        return 5;
+    if (skinny_narrow_serves(a) && !a.transA && a.K >= SK_NARROW_MIN_K && a.N * a.K * 2 <= SK_NARROW_BYTES) {
+        const int64_t groups = (a.N + 15) / 16, rounds = (groups + SK_NARROW_PLACES - 1) / SK_NARROW_PLACES;
+        const bool full_enough = a.M <= 8 || groups * 100 >= rounds * SK_NARROW_PLACES * 65;
+        if (a.N <= SK_NARROW_MAX_N || (a.N <= SK_NARROW_FAR_N && a.K >= SK_NARROW_FAR_K && full_enough)) return 5;
+    }
     return (a.dtype == DT_F32 ? 2 : 0) + (a.transB ? 1 : 0);
 }
 

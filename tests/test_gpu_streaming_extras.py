@@ -220,7 +220,7 @@ def test_mfma_kernel_with_16_columns_refusals_and_automatic_choice(handle):
         lg.gemm_set_plan(handle, lg.GEMM_KERNEL_SKINNY, 5, 1)
         assert p.run(handle, check=False) == lg.GEMM_ERR_UNSUPPORTED
     lg.gemm_set_plan(handle)
-    for (M, N, K, expect) in [(8, 4096, 4096, True), (16, 2048, 4096, True), (17, 4096, 4096, False), (8, 8192, 4096, True), (8, 8192, 2048, False)]:
+    for (M, N, K, expect) in [(8, 4096, 4096, True), (16, 2048, 4096, True), (17, 4096, 4096, False), (8, 8192, 4096, True), (8, 8192, 512, False)]:
         cfg = cfg_of(M, N, K, 0, 1, wl.BF16, a_dist=("normal", 1.0), b_dist=("normal", 0.03))
         inp = wl.make_inputs(cfg, 4)
         p = DeviceProblem(cfg, inp)

@@ -63,7 +63,10 @@ def test_few_rows_on_a_16_bit_weight_stored_n_by_k_take_the_vector_alu_kernel():
     assert plan(8, 1024, 8192, 0, 1) == (SKINNY, narrow, 2) and plan(16, 2048, 2048, 0, 1) == (SKINNY, narrow, 1)      # at least four visits per wave and slice
     for (M, N, K) in [(8, 8192, 8192), (8, 4096, 16384), (16, 11008, 4096), (8, 4104, 4096), (5, 12288, 5120)]:
         assert plan(M, N, K, 0, 1) == (SKINNY, narrow, 1), (M, N, K)
-    for (M, N, K) in [(17, 4096, 4096), (8, 4096, 1024), (8, 8192, 2048), (8, 12296, 4096)]:
+    assert plan(8, 4096, 1024, 0, 1)[:2] == (SKINNY, narrow) and plan(12, 8192, 2048, 0, 1)[:2] == (SKINNY, narrow)      # a short k does not hurt it
+    # 9 to 16 rows beyond one round: only where the last round is 65 % full (320 and 576 workgroups on 512 places are not, 688 are)
+    assert plan(16, 5120, 5120, 0, 1)[0] == TILE and plan(12, 9216, 4608, 0, 1)[0] == TILE and plan(8, 5120, 5120, 0, 1)[:2] == (SKINNY, narrow)
+    for (M, N, K) in [(17, 4096, 4096), (8, 4096, 128), (8, 8192, 512), (8, 12296, 4096)]:
         assert plan(M, N, K, 0, 1)[0] == TILE, (M, N, K)
     assert plan(8, 4096, 4096, 1, 1)[1] != narrow and plan(8, 4096, 4096, 0, 0)[1] != narrow
     assert plan(1, 4096, 4096, 0, 0)[0] == TILE                       # row-major B

@@ -28,7 +28,7 @@ def cfg_of(M, N, K, ta, tb, out, **kw):
 # (plan, first call, second and smaller call); every plan splits K, i.e. uses the scratch buffer
 CASES = [
     ((lg.GEMM_KERNEL_SKINNY, -1, 4), (32, 2048, 4096, 0, 0), (24, 1024, 2048, 0, 0)),          # streaming kernel, row-major B
-    ((lg.GEMM_KERNEL_SKINNY, -1, 8), (17, 1536, 4096, 0, 1), (5, 512, 1024, 0, 1)),            # ... B stored N x K
+    ((lg.GEMM_KERNEL_SKINNY, 1, 8), (17, 1536, 4096, 0, 1), (5, 512, 1024, 0, 1)),             # ... B stored N x K (the wide kernel by name: the second call would go to the one-launch kernel)
     ((lg.GEMM_KERNEL_MFMA_TILE, 5, 3), (392, 328, 1096, 0, 1), (136, 264, 520, 0, 0)),         # k slices of the 128x128 tile
     ((lg.GEMM_KERNEL_MFMA_TILE, 10, 4), (520, 776, 4096, 0, 0), (256, 264, 2048, 1, 0)),       # split tiles of the 256x256 tile
     ((lg.GEMM_KERNEL_AUTO, -1, 0), (48, 4096, 4096, 0, 1), (33, 1024, 2048, 0, 0)),            # whatever the library picks
