@@ -212,8 +212,12 @@ typedef enum {
     GEMM_KERNEL_SKINNY = 3     /* streaming kernels with split-K for few rows of C.  bf16 / fp16, M <= 64: variant 0
                                   for a row-major B (K x N), variant 1 for B stored N x K (an A stored K x M is first
                                   gathered into a row-major copy in the workspace).  fp32, M <= 8, A row-major:
-                                  variants 2 and 3, the same two layouts on the vector ALUs.  The layout and type
-                                  of the call decide; a variant forced against them is GEMM_ERR_UNSUPPORTED */
+                                  variants 2 and 3, the same two layouts on the vector ALUs.  B stored N x K, bf16 /
+                                  fp16, A row-major, has two one-launch forms besides variant 1: variant 4 on the vector
+                                  ALUs (M <= 8; automatic up to 4 rows) and variant 5, variant 1 with 16 columns per
+                                  workgroup (M <= 16; automatic for 5 to 16 rows on weights of 128 MiB at most).  The
+                                  layout and type of the call decide among them; variant -1 takes the automatic one, a
+                                  variant forced against the call is GEMM_ERR_UNSUPPORTED */
 } gemm_kernel_t;
 
 typedef struct {
