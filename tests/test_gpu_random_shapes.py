@@ -71,6 +71,43 @@ def test_random_calls_match_the_oracle_exactly(handle, seed):
 
 
 @pytest.mark.parametrize("seed", range(4))
+def test_random_few_row_calls_on_weights_stored_n_by_k_match_the_oracle_exactly(handle, seed):
+    """1 to 16 rows on a 16-bit weight stored N x K, A row-major, shapes drawn around the edges of the one-launch
+    kernels (16 columns per workgroup, trips of 512 and chunks of 256 along k): the automatic plan's vector-ALU kernel
+    and 16-column MFMA kernel, exact on integer data like every other call."""
+    rng = np.random.default_rng([1618, seed])
+    seen = set()
+    for i in range(12):
+        M = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16]))
+        N = int(rng.choice([8, 24, 136, 520, 1032, 4104, 6152]))
+        K = int(rng.choice([8, 40, 256, 520, 2048, 4104, 8192]))
+        dtype = int(rng.choice([wl.BF16, wl.F16]))
+        cfg = wl.Config("few", M, N, K, 0, 1, dtype, dtype if rng.random() < 0.5 else wl.F32,
+                        alpha=float(rng.choice([1.0, 2.0, -0.5])), beta=float(rng.choice([0.0, 1.0, -2.0])),
+                        bias_dist=("normal", 1.0) if rng.random() < 0.4 else None, bias_dtype=wl.F32,
+                        act=int(rng.choice([wl.ACT_NONE, wl.ACT_RELU])),
+                        lda=K + int(rng.choice([0, 8, 24])), ldb=K + int(rng.choice([0, 8, 24])), ldc=N + int(rng.choice([0, 8, 5])))
+        inp, _ = wl.make_integer_inputs(cfg, 1000 * seed + i, -2, 2)
+        what = (f"seed {seed} case {i}: {M}x{N}x{K} dtype={dtype} out={cfg.out_dtype} ld=({cfg.ld_a()},{cfg.ld_b()},{cfg.ld_c()}) "
+                f"alpha={cfg.alpha} beta={cfg.beta} bias={cfg.bias_dist is not None} act={cfg.act}")
+        print(what, flush=True)
+        want = expected_bits_exact(cfg, inp)
+        p = DeviceProblem(cfg, inp)
+        before = p.result_bits().copy()
+        p.run(handle)
+        after = p.result_bits()
+        kernel, variant, split = lg.gemm_get_last_plan(handle)
+        name = lg.gemm_variant_name(kernel, variant)
+        seen.add(name)
+        g = oracle.decode(cfg.out_dtype, c_bits_as_uint(cfg, after))
+        r = oracle.decode(cfg.out_dtype, c_bits_as_uint(cfg, want.reshape(cfg.M, cfg.N)))
+        assert np.array_equal(g, r), f"{what}: {np.sum(g != r)} elements differ ({name}, split {split})"
+        if cfg.ld_c() > cfg.N and cfg.M > 1:
+            assert np.array_equal(before[:-1, cfg.N:].view(np.uint8), after[:-1, cfg.N:].view(np.uint8)), f"{what}: padding of C written"
+    assert "gemv16_nt_8x32_w4" in seen and "skinny_nt_16x16_w4" in seen, seen
+
+
+@pytest.mark.parametrize("seed", range(4))
 def test_random_batches_of_short_products_match_the_oracle_exactly(handle, seed):
     """Strided batches with K <= 128 and a tile or more per compute unit, shapes drawn around the tile edges: the
     automatic plan's persistent short-k kernel where C is write-only, the other tile kernels where it is not."""
